@@ -1,0 +1,177 @@
+/*
+ * fog.h -- C ABI of the MI355X (gfx950) FP8 hot path of FOG-style training.
+ *
+ * The library computes what the paper states as the end-to-end FP8 product
+ * (Appendix E):
+ *
+ *     GEMM(X, Y) = 1 / (rho(X) rho(Y)) * FP8GEMM(FP8cast(rho(X) X), FP8cast(rho(Y) Y)),
+ *     rho(X)     = FP8MaxValue / (2^m * max H),        H = history of abs-max values,
+ *
+ * for every GEMM of a transformer block in forward and backward, and for the two
+ * products inside attention, P = Softmax(s Q K^T + M) and P V (Appendix B, eq. P;
+ * Appendix E, table of FP8 methods: under FP8DPA both run in FP8).  Forward tensors
+ * use E4M3, backward tensors E5M2 (Section 2).
+ *
+ * Conventions (all entry points)
+ *   - Every data pointer is a DEVICE pointer.  Scalars that depend on data
+ *     (abs-max, scales) also live in device memory, so that just-in-time scaling
+ *     needs no host round trip.  Matrices are row-major; ld* are in ELEMENTS.
+ *   - The caller owns every buffer.  The library never allocates, frees or keeps a
+ *     pointer after the call; scratch memory is passed in as `workspace`, sized by
+ *     the fog_*_workspace queries (which are pure host functions).
+ *   - Every call only enqueues work on `stream` (a hipStream_t cast to void*; NULL is
+ *     the default stream) and returns without synchronising.
+ *   - Errors are returned as fog_status; nothing is thrown and nothing aborts.
+ *     Argument errors are detected on the host before anything is launched, so a
+ *     failing call has no effect on device memory.
+ *   - Inputs must be finite.  FP8 codes are OCP E4M3 / E5M2 bytes.
+ */
+#ifndef FOG_H_
+#define FOG_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FOG_OK = 0,
+  FOG_ERR_NULL = 1,        /* a required pointer is NULL */
+  FOG_ERR_SHAPE = 2,       /* negative size, or a leading dimension smaller than the row */
+  FOG_ERR_ALIGN = 3,       /* a pointer or leading dimension breaks the stated alignment */
+  FOG_ERR_UNSUPPORTED = 4, /* valid problem the kernels do not cover (stated per call) */
+  FOG_ERR_WORKSPACE = 5,   /* workspace missing or smaller than the query says */
+  FOG_ERR_HIP = 6          /* the HIP runtime refused a launch */
+} fog_status;
+
+typedef enum { FOG_E4M3 = 0, FOG_E5M2 = 1 } fog_fp8;
+
+typedef enum {
+  FOG_NT = 0, /* C[M,N] = A[M,K] . B[N,K]^T   forward:      Y  = X~ . W~^T   */
+  FOG_NN = 1, /* C[M,N] = A[M,K] . B[K,N]     data grad:    dX = dY~ . W~    */
+  FOG_TN = 2  /* C[M,N] = A[K,M]^T . B[K,N]   weight grad:  dW = dY~^T . X~  */
+} fog_layout;
+
+const char* fog_status_string(fog_status s);
+int fog_version(void);
+
+/*
+ * Abs-max of a tensor, max_i |x_i| -- the only statistic per-tensor scaling needs
+ * (Appendix E, history update; Appendix C, absmax).
+ *   x_bf16 : n bfloat16 values, contiguous, 16-byte aligned.
+ *   amax   : one float, overwritten (0 for n == 0).
+ * Errors: NULL, n < 0 (SHAPE), misaligned x (ALIGN).
+ */
+fog_status fog_amax(const void* x_bf16, int64_t n, float* amax, void* stream);
+
+/*
+ * Scale from an abs-max (Appendix E): scale = fl32(FP8MaxValue / (2^margin * amax)),
+ * FP8MaxValue = 448 (E4M3) or 57344 (E5M2); scale_inv = fl32(1 / scale).
+ * scale = 1 when amax is zero or not finite; scale is capped at FLT_MAX.
+ *   amax      : one float (for delayed scaling: the maximum of the history).
+ *   scale, scale_inv : one float each, overwritten.  scale_inv may be NULL.
+ */
+fog_status fog_scale(const float* amax, fog_fp8 fmt, int margin, float* scale, float* scale_inv, void* stream);
+
+/*
+ * Delayed scaling (Appendix E, history length l = 1024 in the paper's runs): folds the abs-max
+ * of the tensor just cast into the history, H <- {new_amax} U {h_t}_{t>=2} (the history is kept
+ * newest first; the oldest entry, the last, falls out), then writes
+ * scale = fl32(FP8MaxValue / (2^margin * max H)) and scale_inv for the NEXT iteration's cast.
+ * One small kernel, no host round trip.
+ *   history : len >= 1 floats, updated in place;  new_amax : one float;  scale_inv may be NULL.
+ */
+fog_status fog_scale_delayed(float* history, int len, const float* new_amax, fog_fp8 fmt, int margin,
+                             float* scale, float* scale_inv, void* stream);
+
+/*
+ * FP8cast(scale * X) (Appendix E), optionally also laid out transposed so that the
+ * weight-gradient and data-gradient products find their contraction index contiguous:
+ *     q[r, c] = sat_rne_fmt( fl32( float(x[r, c]) * scale ) ),      qT[c, r] = q[r, c].
+ * The product is rounded to binary32 once, then to FP8 with round-to-nearest-even,
+ * saturating at +-FP8MaxValue.
+ *   x_bf16 : [rows, cols], leading dimension ldx.
+ *   scale  : one float (from fog_scale, or from a history under delayed scaling).
+ *   q      : [rows, cols] bytes, leading dimension ldq.   May be NULL if qT is given.
+ *   qT     : [cols, rows] bytes, leading dimension ldqT, or NULL.
+ *   amax_out : NULL, or one float that receives max |x| in the same pass (the single-pass
+ *              flow of delayed scaling, Section 2).  Overwritten.
+ * The fast path needs cols % 16 == 0 (rows % 16 == 0 too when qT is given), 16-byte aligned
+ * pointers and leading dimensions that are multiples of 16; other shapes take a slower
+ * general kernel with identical results.
+ * Errors: NULL x / scale / both outputs, negative sizes or ld < row length (SHAPE).
+ */
+fog_status fog_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, fog_fp8 fmt,
+                        const float* scale, uint8_t* q, int64_t ldq, uint8_t* qT, int64_t ldqT,
+                        float* amax_out, void* stream);
+
+/*
+ * Scaled FP8 product (Appendix E): C = scale_inv_A * scale_inv_B * (decode(A) x decode(B)) in
+ * the given layout, FP8 products accumulated in binary32, result rounded once to bfloat16.
+ *   A, B   : FP8 codes (fmtA / fmtB may differ: E5M2 gradients times E4M3 weights), lda / ldb.
+ *   scale_inv_A / _B : one float each (the reciprocal scales of the casts).
+ *   C_bf16 : [M, N] bfloat16, leading dimension ldc.
+ *   workspace : unused by the current kernels (fog_fp8_gemm_workspace returns 0); may be NULL.
+ * Requirements: A, B 16-byte aligned, lda, ldb multiples of 16; C 4-byte aligned, ldc even;
+ * the contiguous dimension of each operand a multiple of 16 (K for row-major-in-K operands,
+ * M or N for the K-major operands of NN / TN).  M, N, K otherwise arbitrary; M == 0 or N == 0
+ * is a no-op and K == 0 writes zeros.
+ * Errors: NULL, SHAPE, ALIGN, UNSUPPORTED (a multiple-of-16 rule above broken).
+ */
+fog_status fog_fp8_gemm(fog_layout layout, int64_t M, int64_t N, int64_t K,
+                        const uint8_t* A, fog_fp8 fmtA, int64_t lda, const float* scale_inv_A,
+                        const uint8_t* B, fog_fp8 fmtB, int64_t ldb, const float* scale_inv_B,
+                        void* C_bf16, int64_t ldc, void* workspace, size_t workspace_bytes, void* stream);
+size_t fog_fp8_gemm_workspace(fog_layout layout, int64_t M, int64_t N, int64_t K);
+
+/*
+ * FP8 dot-product attention forward (Appendix B, eq. P; Appendix E, FP8DPA row):
+ *     O = Softmax(s Q K^T + M) V   per (batch, head), M the causal mask when causal != 0,
+ * with Q~, K~, V~ in E4M3 and the probabilities cast to E4M3 for the P V product.
+ * Steps, in the log2 domain: x = s log2(e) sinv_q sinv_k (Q~ K~^T); row reference
+ * m_i = ceil(max_j x_ij) (an integer, so that the cast of p is independent of the order in
+ * which keys are visited); p = 2^(x - m_i); l_i = sum_j p_ij (binary32, p not cast);
+ * P~ = sat_rne_E4M3(scale_p * p);  O = sinv_v (P~ V~) / (scale_p l_i);  lse_i = m_i + log2 l_i.
+ *   Q, K, V : [B, H, S, D] contiguous E4M3 bytes;  D must be 128, S a multiple of 64.
+ *   sinv_* : reciprocal scales of the casts, one float each.  scale_p: one float (p <= 1, so
+ *            the paper's formula gives 448).
+ *   O_bf16 : [B, H, S, D] bfloat16;  lse : [B, H, S] floats (log2 domain).
+ *   amax_p : NULL or one float receiving max p (for a delayed scale_p).  Overwritten.
+ * Errors: NULL, SHAPE, ALIGN (16 bytes), UNSUPPORTED (D != 128, S % 64 != 0).
+ */
+fog_status fog_fp8_attn_fwd(int B, int H, int S, int D, float softmax_scale, int causal,
+                            const uint8_t* Q, const uint8_t* K, const uint8_t* V,
+                            const float* sinv_q, const float* sinv_k, const float* sinv_v, const float* scale_p,
+                            void* O_bf16, float* lse, float* amax_p,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * FP8 attention backward: the gradient of the forward above with all five products in FP8
+ * (Section 2: E5M2 for backward tensors).  Per (batch, head):
+ *     D_i  = sum_d dO_id O_id                      (from the bf16 tensors, binary32)
+ *     P    = 2^(x - lse_i);  P~ = sat_rne_E4M3(scale_p P)
+ *     dV   = sinv_do / scale_p  * (P~^T dO~)
+ *     dP   = sinv_do sinv_v     * (dO~ V~^T)
+ *     dS   = P o (dP - D_i);    dS~ = sat_rne_E5M2(scale_ds dS)
+ *     dQ   = s sinv_k / scale_ds * (dS~ K~),   dK = s sinv_q / scale_ds * (dS~^T Q~)
+ *   dO_e5m2 : dO cast to E5M2 with reciprocal scale sinv_do;  dO_bf16, O_bf16: the bf16 tensors.
+ *   lse : from the forward.  scale_ds : one float (delayed-style: amax_ds of a previous call).
+ *   dQ, dK, dV : [B, H, S, D] bfloat16, overwritten.   amax_ds : NULL or one float, max |dS|.
+ *   workspace : fog_fp8_attn_workspace(B, H, S, D, 1) bytes (holds D_i).
+ * Same shape rules and errors as the forward; WORKSPACE when the workspace is too small.
+ */
+fog_status fog_fp8_attn_bwd(int B, int H, int S, int D, float softmax_scale, int causal,
+                            const uint8_t* Q, const uint8_t* K, const uint8_t* V,
+                            const float* sinv_q, const float* sinv_k, const float* sinv_v,
+                            const void* O_bf16, const void* dO_bf16, const uint8_t* dO_e5m2, const float* sinv_do,
+                            const float* lse, const float* scale_p, const float* scale_ds,
+                            void* dQ_bf16, void* dK_bf16, void* dV_bf16, float* amax_ds,
+                            void* workspace, size_t workspace_bytes, void* stream);
+size_t fog_fp8_attn_workspace(int B, int H, int S, int D, int is_bwd);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FOG_H_ */

@@ -1,0 +1,344 @@
+// Per-tensor scaling kernels: abs-max, scale, FP8 cast (optionally fused with a transpose).
+//
+// What they compute (Appendix E of the paper): rho = FP8MaxValue / (2^m max H) and
+// FP8cast(rho X); Section 2 calls the two-pass flow (abs-max, then cast) just-in-time scaling
+// and the one-pass flow (cast with last iteration's scale, abs-max as a by-product) delayed
+// scaling.  All of these are HBM-bound: every element is read once with 16-byte loads and
+// every output byte is written once with 8- or 16-byte stores.
+#include "common.h"
+#include "launch.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__global__ void zero_u32_kernel(uint32_t* p) { *p = 0u; }
+
+// ---------------------------------------------------------------- abs-max
+// bf16 magnitudes order like unsigned 16-bit integers, so the running maximum is a packed
+// u16 max over the sign-cleared bit patterns; the result is the float whose upper half is it.
+__global__ __launch_bounds__(kThreads) void amax_kernel(const uint4* __restrict__ x, int64_t nvec,
+                                                        const uint16_t* __restrict__ tail, int ntail,
+                                                        uint32_t* __restrict__ out) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  uint32_t m0 = 0, m1 = 0, m2 = 0, m3 = 0;
+  for (; i + 3 * stride < nvec; i += 4 * stride) {
+    uint4 a = ld_nt16(x + i);
+    uint4 b = ld_nt16(x + i + stride);
+    uint4 c = ld_nt16(x + i + 2 * stride);
+    uint4 d = ld_nt16(x + i + 3 * stride);
+    m0 = pkmax_abs_bf16(pkmax_abs_bf16(m0, a.x), a.y); m1 = pkmax_abs_bf16(pkmax_abs_bf16(m1, a.z), a.w);
+    m2 = pkmax_abs_bf16(pkmax_abs_bf16(m2, b.x), b.y); m3 = pkmax_abs_bf16(pkmax_abs_bf16(m3, b.z), b.w);
+    m0 = pkmax_abs_bf16(pkmax_abs_bf16(m0, c.x), c.y); m1 = pkmax_abs_bf16(pkmax_abs_bf16(m1, c.z), c.w);
+    m2 = pkmax_abs_bf16(pkmax_abs_bf16(m2, d.x), d.y); m3 = pkmax_abs_bf16(pkmax_abs_bf16(m3, d.z), d.w);
+  }
+  for (; i < nvec; i += stride) {
+    uint4 a = x[i];
+    m0 = pkmax_abs_bf16(pkmax_abs_bf16(m0, a.x), a.y); m1 = pkmax_abs_bf16(pkmax_abs_bf16(m1, a.z), a.w);
+  }
+  uint32_t m = pkmax_abs_bf16(pkmax_abs_bf16(m0, m1), pkmax_abs_bf16(m2, m3));
+  uint32_t h = (m >> 16) > (m & 0xFFFFu) ? (m >> 16) : (m & 0xFFFFu);
+  if (blockIdx.x == 0 && (int)threadIdx.x < ntail) {
+    uint32_t t = tail[threadIdx.x] & 0x7FFFu;
+    h = h > t ? h : t;
+  }
+  h = wave_max_u32(h);
+  __shared__ uint32_t part[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = h;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t r = part[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) r = r > part[w] ? r : part[w];
+    if (r) atomicMax(out, r << 16);
+  }
+}
+
+// ---------------------------------------------------------------- scale
+FOG_DEVICE void scale_from_amax(float a, int fmt, int margin, float* scale, float* scale_inv) {
+  const float fmax = fmt == FOG_E4M3 ? 448.0f : 57344.0f;
+  float rho = 1.0f;
+  if (a > 0.0f && a <= 3.402823466e38f) {
+    float denom = ldexpf(a, margin);
+    rho = fmax / denom;  // correctly rounded binary32 division
+    if (rho > 3.402823466e38f) rho = 3.402823466e38f;
+    if (!(rho > 0.0f)) rho = 1.0f;
+  }
+  *scale = rho;
+  if (scale_inv) *scale_inv = 1.0f / rho;
+}
+
+__global__ void scale_kernel(const float* amax, int fmt, int margin, float* scale, float* scale_inv) {
+  scale_from_amax(*amax, fmt, margin, scale, scale_inv);
+}
+
+// One workgroup: roll the history by one (newest first), then scale from its maximum.
+__global__ __launch_bounds__(kThreads) void scale_delayed_kernel(float* hist, int len, const float* new_amax, int fmt,
+                                                                int margin, float* scale, float* scale_inv) {
+  __shared__ float part[kThreads / 64];
+  const float na = *new_amax;
+  float m = 0.0f;
+  // Walk the history from the back in blocks so that every element is read before it is overwritten.
+  for (int base = ((len - 1) / kThreads) * kThreads; base >= 0; base -= kThreads) {
+    int i = base + threadIdx.x;
+    float v = 0.0f;
+    bool in = i < len;
+    if (in) v = i == 0 ? na : hist[i - 1];
+    __syncthreads();
+    if (in) hist[i] = v;
+    m = fmaxf(m, v);
+    __syncthreads();
+  }
+  m = wave_max_f32(m);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float r = part[0];
+    for (int w = 1; w < kThreads / 64; ++w) r = fmaxf(r, part[w]);
+    scale_from_amax(r, fmt, margin, scale, scale_inv);
+  }
+}
+
+// ---------------------------------------------------------------- cast, row-major output only
+template <int FMT>
+FOG_DEVICE uint2 cast8(uint4 v, float rho) {
+  uint2 o;
+  o.x = cvt4_fp8<FMT>(bf16lo(v.x) * rho, bf16hi(v.x) * rho, bf16lo(v.y) * rho, bf16hi(v.y) * rho);
+  o.y = cvt4_fp8<FMT>(bf16lo(v.z) * rho, bf16hi(v.z) * rho, bf16lo(v.w) * rho, bf16hi(v.w) * rho);
+  return o;
+}
+
+// Each thread turns 16 bf16 (two 16-byte loads) into 16 FP8 codes (one 16-byte store).
+template <int FMT, bool AMAX>
+__global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t* __restrict__ x, int64_t rows,
+                                                                 int64_t chunks_per_row, int64_t ldx,
+                                                                 const float* __restrict__ scale, uint8_t* __restrict__ q,
+                                                                 int64_t ldq, uint32_t* __restrict__ amax_out) {
+  const float rho = *scale;
+  const int64_t total = rows * chunks_per_row;
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  uint32_t m = 0;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+    int64_t r = i / chunks_per_row, c = i - r * chunks_per_row;
+    const uint4* src = reinterpret_cast<const uint4*>(x + r * ldx + c * 16);
+    uint4 a = ld_nt16(src);
+    uint4 b = ld_nt16(src + 1);
+    if (AMAX) {
+      m = pkmax_abs_bf16(pkmax_abs_bf16(pkmax_abs_bf16(pkmax_abs_bf16(m, a.x), a.y), a.z), a.w);
+      m = pkmax_abs_bf16(pkmax_abs_bf16(pkmax_abs_bf16(pkmax_abs_bf16(m, b.x), b.y), b.z), b.w);
+    }
+    uint2 lo = cast8<FMT>(a, rho), hi = cast8<FMT>(b, rho);
+    uint4 o = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    st_nt16(q + r * ldq + c * 16, o);
+  }
+  if (AMAX) {
+    uint32_t h = (m >> 16) > (m & 0xFFFFu) ? (m >> 16) : (m & 0xFFFFu);
+    h = wave_max_u32(h);
+    if ((threadIdx.x & 63) == 0 && h) atomicMax(amax_out, h << 16);
+  }
+}
+
+// ---------------------------------------------------------------- cast fused with transpose
+// One workgroup handles a 128 x 128 element tile.  A thread owns units of 4 rows x 8 columns:
+// it loads 16 bytes from each of four consecutive rows, casts, stores 8 code bytes per row to q,
+// transposes the 4 x 8 code block in registers (byte permutes) and parks the eight resulting
+// dwords (4 rows of one column each) in an LDS tile that is column-major; the tile is then
+// streamed out to qT in 16-byte pieces.  LDS 16-byte chunks are XOR-swizzled by column group so
+// that neither the dword writes nor the 16-byte reads pile onto the same banks.
+constexpr int kTile = 128;
+
+FOG_DEVICE void transpose4x4(uint32_t r0, uint32_t r1, uint32_t r2, uint32_t r3, uint32_t* t) {
+  uint32_t lo01 = __builtin_amdgcn_perm(r1, r0, 0x05010400u);  // r0.b0 r1.b0 r0.b1 r1.b1
+  uint32_t hi01 = __builtin_amdgcn_perm(r1, r0, 0x07030602u);  // r0.b2 r1.b2 r0.b3 r1.b3
+  uint32_t lo23 = __builtin_amdgcn_perm(r3, r2, 0x05010400u);
+  uint32_t hi23 = __builtin_amdgcn_perm(r3, r2, 0x07030602u);
+  t[0] = __builtin_amdgcn_perm(lo23, lo01, 0x05040100u);
+  t[1] = __builtin_amdgcn_perm(lo23, lo01, 0x07060302u);
+  t[2] = __builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
+  t[3] = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
+}
+
+template <int FMT, bool AMAX, bool WRITE_Q>
+__global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const uint16_t* __restrict__ x, int64_t rows,
+                                                                      int64_t cols, int64_t ldx,
+                                                                      const float* __restrict__ scale,
+                                                                      uint8_t* __restrict__ q, int64_t ldq,
+                                                                      uint8_t* __restrict__ qT, int64_t ldqT,
+                                                                      uint32_t* __restrict__ amax_out, int tiles_c) {
+  __shared__ __attribute__((aligned(16))) uint8_t tile[kTile * kTile];  // [col][row], chunk-swizzled
+  const float rho = *scale;
+  const int64_t r0 = (int64_t)(blockIdx.x / tiles_c) * kTile;
+  const int64_t c0 = (int64_t)(blockIdx.x % tiles_c) * kTile;
+  uint32_t m = 0;
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const int u = threadIdx.x + it * kThreads;  // 512 units: 32 row groups x 16 column chunks
+    const int cc = u & 15, rg = u >> 4;
+    const int64_t r = r0 + rg * 4, c = c0 + cc * 8;
+    uint2 code[4];
+    const bool in = r < rows && c < cols;  // rows % 4 == 0 and cols % 8 == 0 on this path
+    if (in) {
+      uint4 v[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) v[k] = ld_nt16(x + (r + k) * ldx + c);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (AMAX) m = pkmax_abs_bf16(pkmax_abs_bf16(pkmax_abs_bf16(pkmax_abs_bf16(m, v[k].x), v[k].y), v[k].z), v[k].w);
+        code[k] = cast8<FMT>(v[k], rho);
+        if (WRITE_Q) st_nt8(q + (r + k) * ldq + c, code[k]);
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) code[k] = make_uint2(0u, 0u);
+    }
+    uint32_t t[8];
+    transpose4x4(code[0].x, code[1].x, code[2].x, code[3].x, t);
+    transpose4x4(code[0].y, code[1].y, code[2].y, code[3].y, t + 4);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int col = cc * 8 + j;
+      const int chunk = (rg >> 2) ^ (cc & 7);
+      *reinterpret_cast<uint32_t*>(tile + col * kTile + chunk * 16 + (rg & 3) * 4) = t[j];
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int idx = threadIdx.x + it * kThreads;  // 1024 pieces: 128 columns x 8 chunks of 16 rows
+    const int col = idx >> 3, ch = idx & 7;
+    const int64_t c = c0 + col, r = r0 + ch * 16;
+    if (c < cols && r < rows) {  // rows % 16 == 0 on this path
+      uint4 v = *reinterpret_cast<const uint4*>(tile + col * kTile + ((ch ^ ((col >> 3) & 7)) * 16));
+      st_nt16(qT + c * ldqT + r, v);
+    }
+  }
+  if (AMAX) {
+    uint32_t h = (m >> 16) > (m & 0xFFFFu) ? (m >> 16) : (m & 0xFFFFu);
+    h = wave_max_u32(h);
+    if ((threadIdx.x & 63) == 0 && h) atomicMax(amax_out, h << 16);
+  }
+}
+
+// ---------------------------------------------------------------- general shapes (slow, same results)
+template <int FMT>
+__global__ __launch_bounds__(kThreads) void quantize_general_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                                    int64_t ldx, const float* __restrict__ scale,
+                                                                    uint8_t* __restrict__ q, int64_t ldq,
+                                                                    uint8_t* __restrict__ qT, int64_t ldqT,
+                                                                    uint32_t* __restrict__ amax_out) {
+  const float rho = *scale;
+  const int64_t total = rows * cols;
+  uint32_t m = 0;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
+    int64_t r = i / cols, c = i - r * cols;
+    uint32_t w = x[r * ldx + c];
+    uint32_t a = w & 0x7FFFu;
+    m = m > a ? m : a;
+    float t = bf16lo(w) * rho;
+    uint8_t code = (uint8_t)(cvt4_fp8<FMT>(t, t, t, t) & 0xFFu);
+    if (q) q[r * ldq + c] = code;
+    if (qT) qT[c * ldqT + r] = code;
+  }
+  if (amax_out) {
+    m = wave_max_u32(m);
+    if ((threadIdx.x & 63) == 0 && m) atomicMax(amax_out, m << 16);
+  }
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+// ---------------------------------------------------------------- host entry points
+extern "C" fog_status fog_amax(const void* x_bf16, int64_t n, float* amax, void* stream) {
+  if (!amax || (!x_bf16 && n > 0)) return FOG_ERR_NULL;
+  if (n < 0) return FOG_ERR_SHAPE;
+  if (n > 0 && !aligned16(x_bf16)) return FOG_ERR_ALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  zero_u32_kernel<<<1, 1, 0, s>>>(reinterpret_cast<uint32_t*>(amax));
+  if (n > 0) {
+    const int64_t nvec = n / 8;
+    const int ntail = (int)(n - nvec * 8);
+    int64_t blocks = (nvec + kThreads * 4 - 1) / (kThreads * 4);
+    if (blocks > 2048) blocks = 2048;
+    if (blocks < 1) blocks = 1;
+    amax_kernel<<<(int)blocks, kThreads, 0, s>>>(reinterpret_cast<const uint4*>(x_bf16), nvec,
+                                                 reinterpret_cast<const uint16_t*>(x_bf16) + nvec * 8, ntail,
+                                                 reinterpret_cast<uint32_t*>(amax));
+  }
+  return fog_launch_status();
+}
+
+extern "C" fog_status fog_scale(const float* amax, fog_fp8 fmt, int margin, float* scale, float* scale_inv, void* stream) {
+  if (!amax || !scale) return FOG_ERR_NULL;
+  if (fmt != FOG_E4M3 && fmt != FOG_E5M2) return FOG_ERR_UNSUPPORTED;
+  if (margin < -64 || margin > 64) return FOG_ERR_SHAPE;
+  scale_kernel<<<1, 1, 0, (hipStream_t)stream>>>(amax, (int)fmt, margin, scale, scale_inv);
+  return fog_launch_status();
+}
+
+extern "C" fog_status fog_scale_delayed(float* history, int len, const float* new_amax, fog_fp8 fmt, int margin,
+                                        float* scale, float* scale_inv, void* stream) {
+  if (!history || !new_amax || !scale) return FOG_ERR_NULL;
+  if (len < 1 || margin < -64 || margin > 64) return FOG_ERR_SHAPE;
+  if (fmt != FOG_E4M3 && fmt != FOG_E5M2) return FOG_ERR_UNSUPPORTED;
+  scale_delayed_kernel<<<1, kThreads, 0, (hipStream_t)stream>>>(history, len, new_amax, (int)fmt, margin, scale, scale_inv);
+  return fog_launch_status();
+}
+
+template <int FMT>
+static void launch_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ldx, const float* scale, uint8_t* q,
+                            int64_t ldq, uint8_t* qT, int64_t ldqT, uint32_t* amax_out, hipStream_t s) {
+  const bool base_ok = cols % 16 == 0 && ldx % 16 == 0 && aligned16(x) && (!q || (ldq % 16 == 0 && aligned16(q)));
+  if (!qT && base_ok) {
+    int64_t r = rows, cpr = cols / 16, lx = ldx, lq = ldq;
+    if (ldx == cols && ldq == cols) { cpr = rows * cpr; r = 1; }  // contiguous: one long row
+    int64_t total = r * cpr;
+    int64_t blocks = (total + kThreads - 1) / kThreads;
+    if (blocks > 4096) blocks = 4096;
+    if (amax_out)
+      quantize_rows_kernel<FMT, true><<<(int)blocks, kThreads, 0, s>>>(x, r, cpr, lx, scale, q, lq, amax_out);
+    else
+      quantize_rows_kernel<FMT, false><<<(int)blocks, kThreads, 0, s>>>(x, r, cpr, lx, scale, q, lq, amax_out);
+    return;
+  }
+  if (qT && base_ok && rows % 16 == 0 && ldqT % 16 == 0 && aligned16(qT)) {
+    const int64_t tr = (rows + kTile - 1) / kTile, tc = (cols + kTile - 1) / kTile;
+    if (tr * tc <= 0x7FFFFFFF) {
+      const int grid = (int)(tr * tc);
+#define FOG_QT(AM, WQ) quantize_transpose_kernel<FMT, AM, WQ><<<grid, kThreads, 0, s>>>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, amax_out, (int)tc)
+      if (amax_out) { if (q) FOG_QT(true, true); else FOG_QT(true, false); }
+      else          { if (q) FOG_QT(false, true); else FOG_QT(false, false); }
+#undef FOG_QT
+      return;
+    }
+  }
+  int64_t total = rows * cols;
+  int64_t blocks = (total + kThreads - 1) / kThreads;
+  if (blocks > 8192) blocks = 8192;
+  quantize_general_kernel<FMT><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, amax_out);
+}
+
+extern "C" fog_status fog_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, fog_fp8 fmt,
+                                   const float* scale, uint8_t* q, int64_t ldq, uint8_t* qT, int64_t ldqT,
+                                   float* amax_out, void* stream) {
+  if (!scale || (!q && !qT)) return FOG_ERR_NULL;
+  if (rows < 0 || cols < 0) return FOG_ERR_SHAPE;
+  if (fmt != FOG_E4M3 && fmt != FOG_E5M2) return FOG_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  const bool empty = rows == 0 || cols == 0;
+  if (!empty) {
+    if (!x_bf16) return FOG_ERR_NULL;
+    if (ldx < cols || (q && ldq < cols) || (qT && ldqT < rows)) return FOG_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(x_bf16) & 1u) != 0) return FOG_ERR_ALIGN;
+  }
+  if (amax_out) zero_u32_kernel<<<1, 1, 0, s>>>(reinterpret_cast<uint32_t*>(amax_out));
+  if (!empty) {
+    const uint16_t* x = reinterpret_cast<const uint16_t*>(x_bf16);
+    uint32_t* am = reinterpret_cast<uint32_t*>(amax_out);
+    if (fmt == FOG_E4M3) launch_quantize<FOG_E4M3>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, am, s);
+    else                 launch_quantize<FOG_E5M2>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, am, s);
+  }
+  return fog_launch_status();
+}

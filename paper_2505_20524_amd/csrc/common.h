@@ -1,0 +1,93 @@
+// Device-side helpers shared by the HIP kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/fog.h"
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+
+#define FOG_DEVICE static __device__ __forceinline__
+
+// bf16 bit pattern (low 16 bits) -> float, exact.
+FOG_DEVICE float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
+FOG_DEVICE float bf16hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// float -> bf16 bits, round to nearest even (finite inputs; NaN stays NaN).
+FOG_DEVICE uint32_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+FOG_DEVICE uint32_t pack_bf16x2(float lo, float hi) { return f32_to_bf16(lo) | (f32_to_bf16(hi) << 16); }
+
+// Saturating round-to-nearest-even cast of four floats to one dword of FP8 codes (byte i <- v_i).
+// The hardware convert rounds to nearest even but turns overflow into NaN / infinity, so the
+// magnitude is clamped to the largest finite value first.
+template <int FMT>
+FOG_DEVICE uint32_t cvt4_fp8(float a, float b, float c, float d) {
+  uint32_t r = 0;
+  if (FMT == FOG_E4M3) {
+    const float mx = 448.0f;
+    a = __builtin_amdgcn_fmed3f(a, -mx, mx); b = __builtin_amdgcn_fmed3f(b, -mx, mx);
+    c = __builtin_amdgcn_fmed3f(c, -mx, mx); d = __builtin_amdgcn_fmed3f(d, -mx, mx);
+    r = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, r, false);
+    r = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, r, true);
+  } else {
+    const float mx = 57344.0f;
+    a = __builtin_amdgcn_fmed3f(a, -mx, mx); b = __builtin_amdgcn_fmed3f(b, -mx, mx);
+    c = __builtin_amdgcn_fmed3f(c, -mx, mx); d = __builtin_amdgcn_fmed3f(d, -mx, mx);
+    r = __builtin_amdgcn_cvt_pk_bf8_f32(a, b, r, false);
+    r = __builtin_amdgcn_cvt_pk_bf8_f32(c, d, r, true);
+  }
+  return r;
+}
+
+// Wave-wide (64 lanes) reductions through cross-lane shuffles.
+FOG_DEVICE uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    uint32_t t = (uint32_t)__shfl_xor((int)v, o, 64);
+    v = v > t ? v : t;
+  }
+  return v;
+}
+FOG_DEVICE float wave_max_f32(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+FOG_DEVICE float wave_sum_f32(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// max over the magnitudes of the two bf16 halves of each dword, kept as packed u16 pairs.
+FOG_DEVICE uint32_t pkmax_abs_bf16(uint32_t acc, uint32_t w) {
+  us2 a = __builtin_bit_cast(us2, acc);
+  us2 b = __builtin_bit_cast(us2, w & 0x7FFF7FFFu);
+  us2 m = __builtin_elementwise_max(a, b);
+  return __builtin_bit_cast(uint32_t, m);
+}
+
+// Streaming (non-temporal) 16- and 8-byte global accesses: data touched once should not evict
+// what other kernels keep in cache.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+FOG_DEVICE uint4 ld_nt16(const void* p) {
+  u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+FOG_DEVICE void st_nt16(void* p, uint4 v) {
+  u32x4 w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(p));
+}
+FOG_DEVICE void st_nt8(void* p, uint2 v) {
+  u32x2 w = {v.x, v.y};
+  __builtin_nontemporal_store(w, reinterpret_cast<u32x2*>(p));
+}

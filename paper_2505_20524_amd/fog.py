@@ -1,0 +1,126 @@
+"""Thin ctypes binding over libfog.so: the same calls as include/fog.h, argument marshalling only.
+
+Tensors are torch CUDA tensors used purely as device buffers (`data_ptr()`); every step of the
+path runs in the library's HIP kernels.  There is no CPU fallback: if the library has not been
+built, `load()` raises.
+"""
+import ctypes
+import os
+
+import torch
+
+E4M3, E5M2 = 0, 1
+NT, NN, TN = 0, 1, 2
+
+_LIB = None
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfog.so")
+
+_c = ctypes
+_P, _I64, _I, _F, _SZ = _c.c_void_p, _c.c_int64, _c.c_int, _c.c_float, _c.c_size_t
+
+SIGNATURES = {
+    "fog_status_string": (_c.c_char_p, [_I]),
+    "fog_version": (_I, []),
+    "fog_amax": (_I, [_P, _I64, _P, _P]),
+    "fog_scale": (_I, [_P, _I, _I, _P, _P, _P]),
+    "fog_scale_delayed": (_I, [_P, _I, _P, _I, _I, _P, _P, _P]),
+    "fog_quantize": (_I, [_P, _I64, _I64, _I64, _I, _P, _P, _I64, _P, _I64, _P, _P]),
+    "fog_fp8_gemm": (_I, [_I, _I64, _I64, _I64, _P, _I, _I64, _P, _P, _I, _I64, _P, _P, _I64, _P, _SZ, _P]),
+    "fog_fp8_gemm_workspace": (_SZ, [_I, _I64, _I64, _I64]),
+    "fog_fp8_attn_fwd": (_I, [_I, _I, _I, _I, _F, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
+    "fog_fp8_attn_bwd": (_I, [_I, _I, _I, _I, _F, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P,
+                              _P, _P, _P, _P, _P, _SZ, _P]),
+    "fog_fp8_attn_workspace": (_SZ, [_I, _I, _I, _I, _I]),
+}
+
+
+class FogError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        msg = load().fog_status_string(code).decode()
+        super().__init__("%s failed: %s (status %d)" % (where, msg, code))
+
+
+def load():
+    """Loads libfog.so (built by __graft_entry__.build()); raises if it is missing."""
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libfog.so is not built: run `python __graft_entry__.py` (hipcc, gfx950) first; "
+                               "there is no fallback path")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _LIB = lib
+    return _LIB
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream
+
+
+def _check(code, where):
+    if code != 0:
+        raise FogError(code, where)
+
+
+def amax(x, out, stream=None):
+    _check(load().fog_amax(_ptr(x), x.numel(), _ptr(out), _stream(stream)), "fog_amax")
+
+
+def scale(amax_t, fmt, scale_out, scale_inv_out, margin=0, stream=None):
+    _check(load().fog_scale(_ptr(amax_t), fmt, margin, _ptr(scale_out), _ptr(scale_inv_out), _stream(stream)), "fog_scale")
+
+
+def scale_delayed(history, new_amax, fmt, scale_out, scale_inv_out, margin=0, stream=None):
+    _check(load().fog_scale_delayed(_ptr(history), history.numel(), _ptr(new_amax), fmt, margin, _ptr(scale_out),
+                                    _ptr(scale_inv_out), _stream(stream)), "fog_scale_delayed")
+
+
+def quantize(x, fmt, scale_t, q=None, qT=None, amax_out=None, stream=None):
+    rows, cols = x.shape
+    _check(load().fog_quantize(_ptr(x), rows, cols, x.stride(0), fmt, _ptr(scale_t),
+                               _ptr(q), q.stride(0) if q is not None else 0,
+                               _ptr(qT), qT.stride(0) if qT is not None else 0,
+                               _ptr(amax_out), _stream(stream)), "fog_quantize")
+
+
+def fp8_gemm(layout, M, N, K, A, fmt_a, sinv_a, B, fmt_b, sinv_b, C, workspace=None, stream=None):
+    ws = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().fog_fp8_gemm(layout, M, N, K, _ptr(A), fmt_a, A.stride(0), _ptr(sinv_a),
+                               _ptr(B), fmt_b, B.stride(0), _ptr(sinv_b), _ptr(C), C.stride(0),
+                               _ptr(workspace), ws, _stream(stream)), "fog_fp8_gemm")
+
+
+def fp8_gemm_workspace(layout, M, N, K):
+    return load().fog_fp8_gemm_workspace(layout, M, N, K)
+
+
+def fp8_attn_fwd(B, H, S, D, softmax_scale, causal, Q, K, V, sinv_q, sinv_k, sinv_v, scale_p, O, lse,
+                 amax_p=None, workspace=None, stream=None):
+    ws = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().fog_fp8_attn_fwd(B, H, S, D, softmax_scale, int(causal), _ptr(Q), _ptr(K), _ptr(V),
+                                   _ptr(sinv_q), _ptr(sinv_k), _ptr(sinv_v), _ptr(scale_p), _ptr(O), _ptr(lse),
+                                   _ptr(amax_p), _ptr(workspace), ws, _stream(stream)), "fog_fp8_attn_fwd")
+
+
+def fp8_attn_bwd(B, H, S, D, softmax_scale, causal, Q, K, V, sinv_q, sinv_k, sinv_v, O, dO, dO8, sinv_do,
+                 lse, scale_p, scale_ds, dQ, dK, dV, amax_ds=None, workspace=None, stream=None):
+    ws = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().fog_fp8_attn_bwd(B, H, S, D, softmax_scale, int(causal), _ptr(Q), _ptr(K), _ptr(V),
+                                   _ptr(sinv_q), _ptr(sinv_k), _ptr(sinv_v), _ptr(O), _ptr(dO), _ptr(dO8),
+                                   _ptr(sinv_do), _ptr(lse), _ptr(scale_p), _ptr(scale_ds),
+                                   _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(amax_ds), _ptr(workspace), ws,
+                                   _stream(stream)), "fog_fp8_attn_bwd")
+
+
+def fp8_attn_workspace(B, H, S, D, is_bwd):
+    return load().fog_fp8_attn_workspace(B, H, S, D, int(is_bwd))

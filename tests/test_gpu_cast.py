@@ -1,0 +1,153 @@
+"""GPU parity: abs-max, scale and cast kernels against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fp8, scaling
+from paper_2505_20524_amd import fog, synth
+from parity import dev, fscalar
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_amax(xb):
+    out = torch.full((1,), -1.0, device="cuda")
+    fog.amax(dev(xb), out)
+    return np.float32(out.item())
+
+
+@pytest.mark.parametrize("n", [0, 1, 7, 8, 9, 1023, 4096, 100003, 512 * 1024, 4096 * 2048 + 5])
+def test_amax_bit_exact(n):
+    rng = np.random.default_rng(n)
+    xb = synth.f32_to_bf16_bits(rng.standard_normal(n).astype(np.float32) * 3)
+    if n:
+        assert gpu_amax(xb) == scaling.amax(xb)
+        for pos in {0, n - 1, n // 2, max(n - 3, 0)}:
+            y = xb.copy(); y[pos] = 0xC2C8            # plant -100 at an edge position
+            assert gpu_amax(y) == np.float32(100.0)
+    else:
+        out = torch.full((1,), -1.0, device="cuda")
+        fog.load().fog_amax(None, 0, out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        assert out.item() == 0.0
+
+
+@pytest.mark.parametrize("fmt", [fp8.E4M3, fp8.E5M2])
+def test_scale_bit_exact(fmt):
+    vals = [0.0, 1.0, 3.0, 448.0, 1e-3, 7.3e4, 1e-44, 3e38, np.inf, np.nan, 0.1234567, 100.0]
+    for a in vals:
+        for margin in (0, 1, -2):
+            s, si = torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda")
+            fog.scale(fscalar(a), fmt, s, si, margin=margin)
+            rho, rinv = scaling.compute_scale(np.float32(a), fmt, margin)
+            assert np.float32(s.item()).tobytes() == rho.tobytes(), (a, margin)
+            assert np.float32(si.item()).tobytes() == rinv.tobytes(), (a, margin)
+
+
+def test_scale_delayed_history():
+    L = 1024                                           # the paper's history length (Appendix E)
+    rng = np.random.default_rng(0)
+    hist = rng.uniform(0.1, 5.0, L).astype(np.float32)
+    h = dev(hist)
+    s, si = torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda")
+    ref = hist.copy()
+    for step in range(5):
+        na = np.float32(7.0 if step == 2 else 0.3)
+        fog.scale_delayed(h, fscalar(na), fp8.E4M3, s, si)
+        ref = scaling.history_update(ref, na)
+        rho, rinv = scaling.history_scale(ref, fp8.E4M3)
+        assert np.array_equal(h.cpu().numpy(), ref)
+        assert np.float32(s.item()) == rho and np.float32(si.item()) == rinv
+    for L2 in (1, 3, 255, 256, 257, 700):
+        hist = rng.uniform(0.1, 5.0, L2).astype(np.float32)
+        h = dev(hist)
+        fog.scale_delayed(h, fscalar(9.5), fp8.E5M2, s, si)
+        ref = scaling.history_update(hist, 9.5)
+        assert np.array_equal(h.cpu().numpy(), ref)
+        assert np.float32(s.item()) == scaling.history_scale(ref, fp8.E5M2)[0]
+
+
+CASES = [  # rows, cols, ldx extra, transpose
+    (512, 1024, 0, False), (512, 1024, 0, True), (4096, 2048, 0, True), (272, 400, 0, True),
+    (272, 400, 16, True), (100, 48, 0, True), (33, 17, 0, True), (33, 17, 3, False), (1, 16, 0, False),
+    (16, 16, 0, True), (129, 144, 0, False), (384, 8192, 32, True),
+]
+
+
+@pytest.mark.parametrize("fmt", [fp8.E4M3, fp8.E5M2])
+@pytest.mark.parametrize("rows,cols,pad,tr", CASES)
+def test_quantize_bit_exact(fmt, rows, cols, pad, tr):
+    rng = np.random.default_rng(rows * 131 + cols)
+    x = rng.standard_normal((rows, cols + pad)).astype(np.float32)
+    x[:, : min(3, cols)] *= 60.0
+    x[0, 0] = 0.0
+    xb = synth.f32_to_bf16_bits(x)
+    view = xb[:, :cols]
+    a = scaling.amax(view)
+    rho, _ = scaling.compute_scale(a, fmt)
+    want = scaling.quantize(view, rho, fmt)
+    xd = dev(xb)[:, :cols]
+    q = torch.full((rows, cols + pad), 0x55, dtype=torch.uint8, device="cuda")[:, :cols]
+    qT = torch.full((cols, rows + pad), 0x55, dtype=torch.uint8, device="cuda")[:, :rows] if tr else None
+    am = torch.full((1,), -1.0, device="cuda")
+    fog.quantize(xd, fmt, fscalar(rho), q=q, qT=qT, amax_out=am)
+    assert np.array_equal(q.cpu().numpy(), want)
+    if tr:
+        assert np.array_equal(qT.cpu().numpy(), want.T)
+        # transposed output alone
+        qT2 = torch.zeros((cols, rows), dtype=torch.uint8, device="cuda")
+        fog.quantize(xd, fmt, fscalar(rho), q=None, qT=qT2)
+        assert np.array_equal(qT2.cpu().numpy(), want.T)
+    assert np.float32(am.item()) == a
+    # padding untouched
+    if pad:
+        full = q._base if q._base is not None else q
+        assert (full.cpu().numpy()[:, cols:] == 0x55).all()
+
+
+def test_quantize_all_bf16_values_and_saturation():
+    """Every finite bf16 value through the kernel at several scales, incl. ones that overflow the format."""
+    allb = np.arange(65536, dtype=np.uint16)
+    fin = np.isfinite(synth.bf16_bits_to_f32(allb))
+    xb = allb[fin]
+    n = (xb.size // 16) * 16
+    xb = xb[:n].reshape(-1, 16)
+    xd = dev(xb)
+    for fmt in (fp8.E4M3, fp8.E5M2):
+        for rho in (1.0, 448.0 / 3.7, 1e-3, 3.1e4, 1e30, 1e-30):
+            q = torch.zeros(xb.shape, dtype=torch.uint8, device="cuda")
+            fog.quantize(xd, fmt, fscalar(rho), q=q)
+            want = scaling.quantize(xb, np.float32(rho), fmt)
+            assert np.array_equal(q.cpu().numpy(), want), (fmt, rho)
+
+
+def test_jit_flow_config1_tensors():
+    """amax -> scale -> cast on config-1 tensors (X with 4 outlier channels x50, W ~ N(0, 0.02))."""
+    cfg = synth.CONFIGS[1]
+    t = synth.linear_tensors(cfg, 0, want=("X", "W"))
+    for name in ("X", "W"):
+        xb = t[name]
+        xd = dev(xb)
+        am, s, si = (torch.zeros(1, device="cuda") for _ in range(3))
+        fog.amax(xd, am)
+        fog.scale(am, fp8.E4M3, s, si)
+        q = torch.zeros(xb.shape, dtype=torch.uint8, device="cuda")
+        fog.quantize(xd, fp8.E4M3, s, q=q)
+        a = scaling.amax(xb)
+        rho, rinv = scaling.compute_scale(a, fp8.E4M3)
+        assert np.float32(am.item()) == a and np.float32(s.item()) == rho and np.float32(si.item()) == rinv
+        assert np.array_equal(q.cpu().numpy(), scaling.quantize(xb, rho, fp8.E4M3))
+
+
+def test_argument_errors():
+    lib = fog.load()
+    st = torch.cuda.current_stream().cuda_stream
+    x = torch.zeros(64, dtype=torch.int16, device="cuda")
+    out = torch.zeros(1, device="cuda")
+    assert lib.fog_amax(x.data_ptr(), 64, None, st) == 1
+    assert lib.fog_amax(x.data_ptr(), -1, out.data_ptr(), st) == 2
+    assert lib.fog_amax(x.data_ptr() + 2, 8, out.data_ptr(), st) == 3
+    q = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    assert lib.fog_quantize(x.data_ptr(), 4, 16, 8, 0, out.data_ptr(), q.data_ptr(), 16, None, 0, None, st) == 2
+    assert lib.fog_quantize(x.data_ptr(), 4, 16, 16, 0, out.data_ptr(), None, 0, None, 0, None, st) == 1
+    assert lib.fog_quantize(x.data_ptr(), 4, 16, 16, 7, out.data_ptr(), q.data_ptr(), 16, None, 0, None, st) == 4
+    assert lib.fog_scale(None, 0, 0, out.data_ptr(), None, st) == 1
