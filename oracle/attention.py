@@ -83,3 +83,54 @@ def attn_bwd_head(Q8, K8, V8, sinv_q, sinv_k, sinv_v, O_bits, dO_bits, dO8, sinv
     dQ = (s * np.float64(sinv_k) / rho_ds) * (dsq @ k)
     dK = (s * np.float64(sinv_q) / rho_ds) * (dsq.T @ q)
     return dQ, dK, dV, np.float32(np.abs(dS).max())
+
+
+# ---------------------------------------------------------------------------------------------
+# Rounding-decision slack.  The casts of P and dS are rounding DECISIONS taken on values that the
+# GPU holds in binary32, produced by matrix instructions whose internal accumulation is not a
+# correctly rounded binary32 sum; this oracle takes the same decisions in float64.  An element
+# whose pre-cast value lies within a relative `eps` of a rounding boundary has two valid codes.
+# The functions below return, for each output element, the exact linear effect of flipping all
+# such elements: |code_hi - code_lo| propagated through the product that consumes the codes.
+# A parity test widens its tolerance by this amount and by nothing else.
+# ---------------------------------------------------------------------------------------------
+def _code_gap(t, eps, fmt, dt=None):
+    """|decode(cast(t + d)) - decode(cast(t - d))| with d = eps |t| (or the given absolute dt)."""
+    d = np.abs(t) * eps if dt is None else dt
+    lo = fp8.decode(fp8.encode_sat((t - d).astype(np.float32), fmt), fmt)
+    hi = fp8.decode(fp8.encode_sat((t + d).astype(np.float32), fmt), fmt)
+    return np.abs(hi - lo)
+
+
+def fwd_cast_slack(Q8, K8, V8, sinv_q, sinv_k, sinv_v, softmax_scale, scale_p, causal, eps):
+    """Slack on O [S,D] from ambiguous casts of P (forward)."""
+    x = _logits(Q8, K8, sinv_q, sinv_k, softmax_scale, causal)
+    M = np.ceil(x.max(axis=1, keepdims=True))
+    p = np.exp2(x - M)
+    l = p.sum(axis=1, keepdims=True)
+    gap = _code_gap(np.float64(scale_p) * p, eps, fp8.E4M3)
+    v = np.abs(fp8.decode(V8, fp8.E4M3))
+    return np.float64(sinv_v) * (gap @ v) / (np.float64(scale_p) * l)
+
+
+def bwd_cast_slack(Q8, K8, V8, sinv_q, sinv_k, sinv_v, O_bits, dO_bits, dO8, sinv_do, lse,
+                   softmax_scale, scale_p, scale_ds, causal, eps):
+    """Slack on (dQ, dK, dV) from ambiguous casts of P (-> dV) and dS (-> dQ, dK)."""
+    x = _logits(Q8, K8, sinv_q, sinv_k, softmax_scale, causal)
+    P = np.exp2(x - np.asarray(lse, dtype=np.float64)[:, None])
+    q = fp8.decode(Q8, fp8.E4M3)
+    k = fp8.decode(K8, fp8.E4M3)
+    v = fp8.decode(V8, fp8.E4M3)
+    do = fp8.decode(dO8, fp8.E5M2)
+    Dv = (bf16.bits_to_f64(dO_bits) * bf16.bits_to_f64(O_bits)).sum(axis=1, keepdims=True)
+    rho_p, rho_ds = np.float64(scale_p), np.float64(scale_ds)
+    gap_p = _code_gap(rho_p * P, eps, fp8.E4M3)
+    s_dv = (np.float64(sinv_do) / rho_p) * (gap_p.T @ np.abs(do))
+    dP = np.float64(sinv_do) * np.float64(sinv_v) * (do @ v.T)
+    dS = P * (dP - Dv)
+    unc = eps * P * (np.abs(dP) + np.abs(Dv))          # dP - D may cancel: uncertainty follows the un-cancelled size
+    gap_ds = _code_gap(rho_ds * dS, eps, fp8.E5M2, dt=rho_ds * unc)
+    s = np.float64(softmax_scale)
+    s_dq = (s * np.float64(sinv_k) / rho_ds) * (gap_ds @ np.abs(k))
+    s_dk = (s * np.float64(sinv_q) / rho_ds) * (gap_ds.T @ np.abs(q))
+    return s_dq, s_dk, s_dv

@@ -1,0 +1,424 @@
+// FP8 dot-product attention, backward (gfx950): dQ, dK, dV with all five products in FP8.
+//
+// The paper runs every GEMM of the block, attention included, in FP8 in both passes (abstract;
+// Appendix E, FP8DPA row), with E5M2 for backward tensors (Section 2).  Per (batch, head):
+//     D_i = sum_d dO_id O_id                        x_ij = s log2(e) sinv_q sinv_k (Q~ K~^T)_ij
+//     P   = 2^(x - lse_i),  P~ = E4M3(rho_p P)      dV = sinv_do / rho_p (P~^T dO~)
+//     dP  = sinv_do sinv_v (dO~ V~^T)               dS = P o (dP - D_i),  dS~ = E5M2(rho_ds dS)
+//     dQ  = s sinv_k / rho_ds (dS~ K~)              dK = s sinv_q / rho_ds (dS~^T Q~)
+//
+// Three kernels.  (0) D_i, one pass over the bf16 tensors.  (1) dK/dV: a workgroup owns 128 keys
+// (32 per wave) and walks the query blocks at or below its diagonal; the score tile is produced
+// with lane = key, which is the B-operand shape of both dV^T += dO^T P and dK^T += Q^T dS.
+// (2) dQ: a workgroup owns 128 queries and walks the key blocks, scores transposed (lane = query),
+// the B-operand shape of dQ^T += K^T dS^T.  Recomputing S and dP in both kernels costs two extra
+// products but keeps every accumulator in registers, needs no atomics and is deterministic.
+// Operands whose contraction index is their row index (dO^T, Q^T, K^T) are gathered from the
+// row-major LDS tiles with the byte-transposing read, in the key/query order the packed
+// probabilities have (see the forward kernel).
+#include "common.h"
+#include "launch.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int HD = 128;
+constexpr int BLK = 128;           // rows owned by a workgroup (keys in kernel 1, queries in kernel 2)
+constexpr int STEP = 64;           // rows of the streamed operand per step
+constexpr int TS = HD + 16;        // LDS tile row stride: conflict-free for 16-byte row reads and transposing reads
+constexpr int TILE = STEP * TS;
+
+typedef __attribute__((address_space(3))) v2i* lds_v2i_ptr;
+
+struct BwdArgs {
+  const uint8_t* Q; const uint8_t* K; const uint8_t* V; const uint8_t* dO8;
+  const uint16_t* O; const uint16_t* dO;
+  const float* sinv_q; const float* sinv_k; const float* sinv_v; const float* sinv_do;
+  const float* lse; const float* scale_p; const float* scale_ds;
+  uint16_t* dQ; uint16_t* dK; uint16_t* dV;
+  uint32_t* amax_ds; float* Dws;
+  float softmax_scale;
+  int BH, S, nblk;
+};
+
+FOG_DEVICE float lane_xor32(float v) { return __shfl_xor(v, 32, 64); }
+
+// 32 rows x 64 contraction bytes from a row-major [rows][TS] tile: lane (row l&31, half l>>5).
+FOG_DEVICE v8i frag_rows(const uint8_t* tile, int row_base, int h) {
+  const int l = threadIdx.x & 63;
+  const uint8_t* p = tile + (row_base + (l & 31)) * TS + 64 * h + 32 * (l >> 5);
+  v4i lo = *reinterpret_cast<const v4i*>(p), hi = *reinterpret_cast<const v4i*>(p + 16);
+  v8i f;
+  f[0] = lo[0]; f[1] = lo[1]; f[2] = lo[2]; f[3] = lo[3];
+  f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3];
+  return f;
+}
+// Same fragment straight from global memory (row-major, stride HD).
+FOG_DEVICE v8i frag_global(const uint8_t* base, int64_t row, int h) {
+  const int l = threadIdx.x & 63;
+  const uint8_t* p = base + row * HD + 64 * h + 32 * (l >> 5);
+  uint4 lo = *reinterpret_cast<const uint4*>(p), hi = *reinterpret_cast<const uint4*>(p + 16);
+  v8i f;
+  f[0] = lo.x; f[1] = lo.y; f[2] = lo.z; f[3] = lo.w;
+  f[4] = hi.x; f[5] = hi.y; f[6] = hi.z; f[7] = hi.w;
+  return f;
+}
+// Transposed fragment: 32 columns [col_base, +32) x the tile's 64 rows as contraction index, rows
+// listed in the order the packed score bytes use: byte 16 t + r  <->  row 32 t + 8 (r/4) + 4 g + (r%4).
+FOG_DEVICE v8i frag_cols(const uint8_t* tile, int col_base) {
+  const int l = threadIdx.x & 63;
+  const int g = l >> 5, i16 = l & 15, jj = i16 >> 1;
+  const uint8_t* p = tile + (8 * (jj >> 2) + 4 * g + (jj & 3)) * TS + col_base + (l & 16) + 8 * (i16 & 1);
+  v8i f;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    v2i v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(p + 16 * r * TS));
+    f[2 * r] = v[0];
+    f[2 * r + 1] = v[1];
+  }
+  return f;
+}
+
+// ------------------------------------------------------------------ kernel 0: D_i = sum_d dO_id O_id
+__global__ __launch_bounds__(kThreads) void attn_bwd_rowdot_kernel(const uint16_t* __restrict__ O, const uint16_t* __restrict__ dO,
+                                                                   float* __restrict__ Dws, int64_t rows) {
+  const int64_t row = (int64_t)blockIdx.x * (kThreads / 16) + (threadIdx.x >> 4);
+  const int part = threadIdx.x & 15;
+  float s = 0.0f;
+  if (row < rows) {
+    uint4 a = *reinterpret_cast<const uint4*>(O + row * HD + part * 8);
+    uint4 b = *reinterpret_cast<const uint4*>(dO + row * HD + part * 8);
+    s = bf16lo(a.x) * bf16lo(b.x) + bf16hi(a.x) * bf16hi(b.x) + bf16lo(a.y) * bf16lo(b.y) + bf16hi(a.y) * bf16hi(b.y) +
+        bf16lo(a.z) * bf16lo(b.z) + bf16hi(a.z) * bf16hi(b.z) + bf16lo(a.w) * bf16lo(b.w) + bf16hi(a.w) * bf16hi(b.w);
+  }
+#pragma unroll
+  for (int o = 8; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+  if (row < rows && part == 0) Dws[row] = s;
+}
+
+// ------------------------------------------------------------------ kernel 1: dK, dV
+template <bool CAUSAL>
+__global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
+  __shared__ __attribute__((aligned(16))) uint8_t smem[2 * 2 * TILE];     // {Q, dO} x 2 stages
+  __shared__ __attribute__((aligned(16))) float srow[2][2][STEP];         // {lse, D} x 2 stages
+  const int bh = blockIdx.x % a.BH;
+  const int kblk = blockIdx.x / a.BH;                  // early key blocks see the most queries: launched first
+  const int t = threadIdx.x, w = t >> 6, l = t & 63, g = l >> 5;
+  const int S = a.S;
+  const int64_t hoff = (int64_t)bh * S;
+  const uint8_t* Qh = a.Q + hoff * HD;
+  const uint8_t* dOh = a.dO8 + hoff * HD;
+  const int key0 = kblk * BLK + 32 * w;
+  const int key = key0 + (l & 31);
+  const bool wave_on = key0 < S;
+
+  v8i kf[2], vf[2];                                    // this wave's 32 keys, both halves of d
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    kf[h] = frag_global(a.K + hoff * HD, wave_on ? key : 0, h);
+    vf[h] = frag_global(a.V + hoff * HD, wave_on ? key : 0, h);
+  }
+  const float rho_p = *a.scale_p, rho_ds = *a.scale_ds;
+  const float c = a.softmax_scale * 1.44269504088896340736f * (*a.sinv_q) * (*a.sinv_k);
+  const float cdp = (*a.sinv_do) * (*a.sinv_v);
+  const float lg_rho_p = __log2f(rho_p);
+
+  v16f dv[4], dk[4];
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dv[d][r] = 0.0f; dk[d][r] = 0.0f; }
+
+  const int qb_first = CAUSAL ? (kblk * BLK) / STEP : 0;
+  const int qb_last = S / STEP;                        // exclusive
+
+  uint4 rq[2], rdo[2];
+  float rl = 0.0f;
+  auto gload = [&](int qb) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {  // 64 rows x 8 chunks = 2 per thread
+      const int ch = t + kThreads * i, row = ch >> 3, cc = ch & 7;
+      const int64_t off = (int64_t)(qb * STEP + row) * HD + cc * 16;
+      rq[i] = *reinterpret_cast<const uint4*>(Qh + off);
+      rdo[i] = *reinterpret_cast<const uint4*>(dOh + off);
+    }
+    if (t < 2 * STEP) rl = t < STEP ? a.lse[hoff + qb * STEP + t] : a.Dws[hoff + qb * STEP + (t - STEP)];
+  };
+  auto swrite = [&](int stage) {
+    uint8_t* sq = smem + stage * 2 * TILE;
+    uint8_t* sdo = sq + TILE;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {  // 64 rows x 8 chunks = 2 per thread
+      const int ch = t + kThreads * i, row = ch >> 3, cc = ch & 7;
+      *reinterpret_cast<uint4*>(sq + row * TS + cc * 16) = rq[i];
+      *reinterpret_cast<uint4*>(sdo + row * TS + cc * 16) = rdo[i];
+    }
+    if (t < 2 * STEP) srow[stage][t >= STEP][t & (STEP - 1)] = rl;
+  };
+
+  if (qb_first < qb_last) {
+    gload(qb_first);
+    swrite(0);
+  }
+  __syncthreads();
+
+  for (int qb = qb_first; qb < qb_last; ++qb) {
+    const int cur = (qb - qb_first) & 1;
+    if (qb + 1 < qb_last) gload(qb + 1);
+    const uint8_t* sq = smem + cur * 2 * TILE;
+    const uint8_t* sdo = sq + TILE;
+    const int qbase = qb * STEP;
+    const bool need = wave_on && (!CAUSAL || qbase + STEP - 1 >= key0);
+    if (need) {
+      // S and dP tiles with lane = key: element r of tile qt is query qbase + 32 qt + 8 (r/4) + 4 g + (r%4)
+      v16f st[2], dp[2];
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { st[qt][r] = 0.0f; dp[qt][r] = 0.0f; }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          v8i qfr = frag_rows(sq, 32 * qt, h);
+          st[qt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qfr, kf[h], st[qt], 0, 0, 0, 0, 0, 0);
+          v8i dof = frag_rows(sdo, 32 * qt, h);
+          dp[qt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(dof, vf[h], dp[qt], 1, 0, 0, 0, 0, 0);
+        }
+      }
+      const bool mask = CAUSAL && qbase < key0 + 31;
+      v8i pf, dsf;
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+          const int qi = 32 * qt + 8 * qd + 4 * g;
+          const float4 ls = *reinterpret_cast<const float4*>(&srow[cur][0][qi]);
+          const float4 dd = *reinterpret_cast<const float4*>(&srow[cur][1][qi]);
+          const float lsv[4] = {ls.x, ls.y, ls.z, ls.w}, ddv[4] = {dd.x, dd.y, dd.z, dd.w};
+          float p[4], pq[4], ds[4];
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            const int r = 4 * qd + b;
+            float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[qt][r], c, -lsv[b]));
+            if (mask && (qbase + qi + b) < key) e = 0.0f;
+            p[b] = e;
+            pq[b] = e * rho_p;
+            ds[b] = (e * __builtin_fmaf(dp[qt][r], cdp, -ddv[b])) * rho_ds;
+          }
+          pf[4 * qt + qd] = (int)cvt4_fp8<FOG_E4M3>(pq[0], pq[1], pq[2], pq[3]);
+          dsf[4 * qt + qd] = (int)cvt4_fp8<FOG_E5M2>(ds[0], ds[1], ds[2], ds[3]);
+        }
+      }
+      // dV^T += dO^T P~ ;  dK^T += Q^T dS~   (contraction over the 64 queries of this step)
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        v8i dot = frag_cols(sdo, 32 * d);
+        dv[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(dot, pf, dv[d], 1, 0, 0, 0, 0, 0);
+        v8i qt_ = frag_cols(sq, 32 * d);
+        dk[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qt_, dsf, dk[d], 0, 1, 0, 0, 0, 0);
+      }
+    }
+    if (qb + 1 < qb_last) swrite(cur ^ 1);
+    __syncthreads();
+  }
+  (void)lg_rho_p;
+  if (!wave_on) return;
+  const float sdv = (*a.sinv_do) / rho_p;
+  const float sdk = a.softmax_scale * (*a.sinv_q) / rho_ds;
+  uint16_t* dvrow = a.dV + (hoff + key) * HD;
+  uint16_t* dkrow = a.dK + (hoff + key) * HD;
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) {
+      const int col = 32 * d + 8 * qd + 4 * g;
+      *reinterpret_cast<uint2*>(dvrow + col) = make_uint2(pack_bf16x2(dv[d][4 * qd] * sdv, dv[d][4 * qd + 1] * sdv),
+                                                          pack_bf16x2(dv[d][4 * qd + 2] * sdv, dv[d][4 * qd + 3] * sdv));
+      *reinterpret_cast<uint2*>(dkrow + col) = make_uint2(pack_bf16x2(dk[d][4 * qd] * sdk, dk[d][4 * qd + 1] * sdk),
+                                                          pack_bf16x2(dk[d][4 * qd + 2] * sdk, dk[d][4 * qd + 3] * sdk));
+    }
+}
+
+// ------------------------------------------------------------------ kernel 2: dQ (and max |dS|)
+template <bool CAUSAL, bool AMAX>
+__global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(BwdArgs a) {
+  __shared__ __attribute__((aligned(16))) uint8_t smem[2 * 2 * TILE];     // {K, V} x 2 stages
+  const int bh = blockIdx.x % a.BH;
+  const int qblk = a.nblk - 1 - blockIdx.x / a.BH;
+  const int t = threadIdx.x, w = t >> 6, l = t & 63, g = l >> 5;
+  const int S = a.S;
+  const int64_t hoff = (int64_t)bh * S;
+  const uint8_t* Kh = a.K + hoff * HD;
+  const uint8_t* Vh = a.V + hoff * HD;
+  const int q0 = qblk * BLK + 32 * w;
+  const int q = q0 + (l & 31);
+  const bool wave_on = q0 < S;
+
+  v8i qf[2], dof[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    qf[h] = frag_global(a.Q + hoff * HD, wave_on ? q : 0, h);
+    dof[h] = frag_global(a.dO8 + hoff * HD, wave_on ? q : 0, h);
+  }
+  const float lse = wave_on ? a.lse[hoff + q] : 0.0f;
+  const float Dq = wave_on ? a.Dws[hoff + q] : 0.0f;
+  const float rho_ds = *a.scale_ds;
+  const float c = a.softmax_scale * 1.44269504088896340736f * (*a.sinv_q) * (*a.sinv_k);
+  const float cdp = (*a.sinv_do) * (*a.sinv_v);
+
+  v16f dq[4];
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dq[d][r] = 0.0f;
+  float ds_max = 0.0f;
+
+  const int kv_end = CAUSAL ? min(S, qblk * BLK + BLK) : S;
+  const int nkb = (kv_end + STEP - 1) / STEP;
+
+  uint4 rk[2], rv[2];
+  auto gload = [&](int kb) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {  // 64 rows x 8 chunks = 2 per thread
+      const int ch = t + kThreads * i, row = ch >> 3, cc = ch & 7;
+      const int64_t off = (int64_t)(kb * STEP + row) * HD + cc * 16;
+      rk[i] = *reinterpret_cast<const uint4*>(Kh + off);
+      rv[i] = *reinterpret_cast<const uint4*>(Vh + off);
+    }
+  };
+  auto swrite = [&](int stage) {
+    uint8_t* sk = smem + stage * 2 * TILE;
+    uint8_t* sv = sk + TILE;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {  // 64 rows x 8 chunks = 2 per thread
+      const int ch = t + kThreads * i, row = ch >> 3, cc = ch & 7;
+      *reinterpret_cast<uint4*>(sk + row * TS + cc * 16) = rk[i];
+      *reinterpret_cast<uint4*>(sv + row * TS + cc * 16) = rv[i];
+    }
+  };
+  gload(0);
+  swrite(0);
+  __syncthreads();
+
+  for (int kb = 0; kb < nkb; ++kb) {
+    const int cur = kb & 1;
+    if (kb + 1 < nkb) gload(kb + 1);
+    const uint8_t* sk = smem + cur * 2 * TILE;
+    const uint8_t* sv = sk + TILE;
+    const int kbase = kb * STEP;
+    const bool need = wave_on && (!CAUSAL || kbase <= q0 + 31);
+    if (need) {
+      // transposed tiles, lane = query: element r of tile kt is key kbase + 32 kt + 8 (r/4) + 4 g + (r%4)
+      v16f st[2], dp[2];
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { st[kt][r] = 0.0f; dp[kt][r] = 0.0f; }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          v8i kfr = frag_rows(sk, 32 * kt, h);
+          st[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kfr, qf[h], st[kt], 0, 0, 0, 0, 0, 0);
+          v8i vfr = frag_rows(sv, 32 * kt, h);
+          dp[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vfr, dof[h], dp[kt], 0, 1, 0, 0, 0, 0);
+        }
+      }
+      const bool mask = CAUSAL && kbase + STEP - 1 > q0;
+      v8i dsf;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+          float ds[4];
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            const int r = 4 * qd + b;
+            float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][r], c, -lse));
+            if (mask && (kbase + 32 * kt + 8 * qd + 4 * g + b) > q) e = 0.0f;
+            const float dsv = e * __builtin_fmaf(dp[kt][r], cdp, -Dq);
+            if (AMAX) ds_max = fmaxf(ds_max, fabsf(dsv));
+            ds[b] = dsv * rho_ds;
+          }
+          dsf[4 * kt + qd] = (int)cvt4_fp8<FOG_E5M2>(ds[0], ds[1], ds[2], ds[3]);
+        }
+      }
+      // dQ^T += K^T dS~^T  (contraction over the 64 keys of this step)
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        v8i kt_ = frag_cols(sk, 32 * d);
+        dq[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kt_, dsf, dq[d], 0, 1, 0, 0, 0, 0);
+      }
+    }
+    if (kb + 1 < nkb) swrite(cur ^ 1);
+    __syncthreads();
+  }
+  if (!wave_on) return;
+  const float sdq = a.softmax_scale * (*a.sinv_k) / rho_ds;
+  uint16_t* dqrow = a.dQ + (hoff + q) * HD;
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) {
+      const int col = 32 * d + 8 * qd + 4 * g;
+      *reinterpret_cast<uint2*>(dqrow + col) = make_uint2(pack_bf16x2(dq[d][4 * qd] * sdq, dq[d][4 * qd + 1] * sdq),
+                                                          pack_bf16x2(dq[d][4 * qd + 2] * sdq, dq[d][4 * qd + 3] * sdq));
+    }
+  if (AMAX) {
+    ds_max = wave_max_f32(ds_max);
+    if (l == 0 && ds_max > 0.0f) atomicMax(a.amax_ds, __float_as_uint(ds_max));
+  }
+}
+
+__global__ void zero_u32b(uint32_t* p) { *p = 0u; }
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+extern "C" size_t fog_fp8_attn_workspace(int B, int H, int S, int D, int is_bwd) {
+  (void)D;
+  if (!is_bwd || B <= 0 || H <= 0 || S <= 0) return 0;
+  return (size_t)B * H * S * sizeof(float);
+}
+
+extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int S, int D, float softmax_scale, int causal,
+                                       const uint8_t* Q, const uint8_t* K, const uint8_t* V,
+                                       const float* sinv_q, const float* sinv_k, const float* sinv_v,
+                                       const void* O_bf16, const void* dO_bf16, const uint8_t* dO_e5m2, const float* sinv_do,
+                                       const float* lse, const float* scale_p, const float* scale_ds,
+                                       void* dQ_bf16, void* dK_bf16, void* dV_bf16, float* amax_ds,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (B < 0 || H < 0 || S < 0 || D < 0) return FOG_ERR_SHAPE;
+  if (!(softmax_scale > 0.0f)) return FOG_ERR_UNSUPPORTED;
+  if (D != HD || S % STEP != 0) return FOG_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  if (B == 0 || H == 0 || S == 0) {
+    if (amax_ds) zero_u32b<<<1, 1, 0, s>>>(reinterpret_cast<uint32_t*>(amax_ds));
+    return fog_launch_status();
+  }
+  if (!Q || !K || !V || !sinv_q || !sinv_k || !sinv_v || !O_bf16 || !dO_bf16 || !dO_e5m2 || !sinv_do || !lse || !scale_p ||
+      !scale_ds || !dQ_bf16 || !dK_bf16 || !dV_bf16)
+    return FOG_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O_bf16) || !aligned16(dO_bf16) || !aligned16(dO_e5m2) ||
+      !aligned16(dQ_bf16) || !aligned16(dK_bf16) || !aligned16(dV_bf16))
+    return FOG_ERR_ALIGN;
+  if (!workspace || workspace_bytes < fog_fp8_attn_workspace(B, H, S, D, 1) || (reinterpret_cast<uintptr_t>(workspace) & 3u))
+    return FOG_ERR_WORKSPACE;
+  if ((int64_t)B * H > 0x7FFFFF || (int64_t)B * H * ((S + BLK - 1) / BLK) > 0x7FFFFFF0) return FOG_ERR_UNSUPPORTED;
+  BwdArgs a;
+  a.Q = Q; a.K = K; a.V = V; a.dO8 = dO_e5m2;
+  a.O = reinterpret_cast<const uint16_t*>(O_bf16); a.dO = reinterpret_cast<const uint16_t*>(dO_bf16);
+  a.sinv_q = sinv_q; a.sinv_k = sinv_k; a.sinv_v = sinv_v; a.sinv_do = sinv_do;
+  a.lse = lse; a.scale_p = scale_p; a.scale_ds = scale_ds;
+  a.dQ = reinterpret_cast<uint16_t*>(dQ_bf16); a.dK = reinterpret_cast<uint16_t*>(dK_bf16); a.dV = reinterpret_cast<uint16_t*>(dV_bf16);
+  a.amax_ds = reinterpret_cast<uint32_t*>(amax_ds); a.Dws = reinterpret_cast<float*>(workspace);
+  a.softmax_scale = softmax_scale;
+  a.BH = B * H; a.S = S; a.nblk = (S + BLK - 1) / BLK;
+  if (amax_ds) zero_u32b<<<1, 1, 0, s>>>(a.amax_ds);
+  const int64_t rows = (int64_t)a.BH * S;
+  attn_bwd_rowdot_kernel<<<(int)((rows + 15) / 16), kThreads, 0, s>>>(a.O, a.dO, a.Dws, rows);
+  const int grid = a.BH * a.nblk;
+  if (causal) attn_bwd_dkdv_kernel<true><<<grid, kThreads, 0, s>>>(a);
+  else        attn_bwd_dkdv_kernel<false><<<grid, kThreads, 0, s>>>(a);
+  if (causal) { if (amax_ds) attn_bwd_dq_kernel<true, true><<<grid, kThreads, 0, s>>>(a); else attn_bwd_dq_kernel<true, false><<<grid, kThreads, 0, s>>>(a); }
+  else        { if (amax_ds) attn_bwd_dq_kernel<false, true><<<grid, kThreads, 0, s>>>(a); else attn_bwd_dq_kernel<false, false><<<grid, kThreads, 0, s>>>(a); }
+  return fog_launch_status();
+}

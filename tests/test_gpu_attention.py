@@ -1,0 +1,167 @@
+"""GPU parity: FP8 attention forward / backward against the float64 oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention, bf16, fp8, scaling
+from paper_2505_20524_amd import fog, synth
+from parity import CAST_EPS, check_bf16, dev, fscalar, host_u16
+
+pytestmark = pytest.mark.gpu
+
+
+def cast_all(q, k, v, do):
+    out = {}
+    for name, t, fmt in (("q", q, fp8.E4M3), ("k", k, fp8.E4M3), ("v", v, fp8.E4M3), ("do", do, fp8.E5M2)):
+        rho, rinv = scaling.compute_scale(scaling.amax(t), fmt)
+        out[name] = (scaling.quantize(t.reshape(-1, t.shape[-1]), rho, fmt).reshape(t.shape), rinv)
+    return out
+
+
+def gpu_fwd(c, B, H, S, s, causal, want_amax=True):
+    O = torch.full((B, H, S, 128), 0x7FC0, dtype=torch.int16, device="cuda")
+    lse = torch.full((B, H, S), float("nan"), device="cuda")
+    am = torch.full((1,), -1.0, device="cuda") if want_amax else None
+    fog.fp8_attn_fwd(B, H, S, 128, s, causal, dev(c["q"][0]), dev(c["k"][0]), dev(c["v"][0]),
+                     fscalar(c["q"][1]), fscalar(c["k"][1]), fscalar(c["v"][1]), fscalar(448.0), O, lse, amax_p=am)
+    torch.cuda.synchronize()
+    return host_u16(O), lse.cpu().numpy(), (am.item() if want_amax else None)
+
+
+def oracle_fwd_heads(c, heads, s, causal):
+    res = {}
+    for (b, h) in heads:
+        res[(b, h)] = attention.attn_fwd_head(c["q"][0][b, h], c["k"][0][b, h], c["v"][0][b, h],
+                                              c["q"][1], c["k"][1], c["v"][1], s, 448.0, causal)
+    return res
+
+
+def check_fwd(c, B, H, S, s, causal, heads):
+    O, lse, am = gpu_fwd(c, B, H, S, s, causal)
+    ref = oracle_fwd_heads(c, heads, s, causal)
+    pmax = 0.0
+    for (b, h), (Or, lr, ap) in ref.items():
+        slack = attention.fwd_cast_slack(c["q"][0][b, h], c["k"][0][b, h], c["v"][0][b, h], c["q"][1], c["k"][1], c["v"][1],
+                                         s, 448.0, causal, CAST_EPS)
+        check_bf16(O[b, h], Or, what="O[%d,%d]" % (b, h), slack=slack, max_flip_frac=1.0)
+        assert np.abs(lse[b, h] - lr).max() < 2e-4, "lse"
+        pmax = max(pmax, float(ap))
+    assert np.isfinite(lse).all()
+    if len(heads) == B * H:
+        assert abs(am - pmax) <= 1e-4 * pmax
+    assert 0.5 < am <= 1.0 + 1e-6
+    return O, lse
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("B,H,S", [(1, 1, 64), (1, 2, 128), (2, 2, 320), (1, 3, 576)])
+def test_forward_parity(B, H, S, causal):
+    q, k, v, do = synth.small_attention(1000 + S, B, H, S)
+    c = cast_all(q, k, v, do)
+    check_fwd(c, B, H, S, 1 / math.sqrt(128), causal, [(b, h) for b in range(B) for h in range(H)])
+
+
+def test_forward_fog_softmax_scale_and_q_zero():
+    B, H, S = 1, 2, 256
+    q, k, v, do = synth.small_attention(77, B, H, S)
+    c = cast_all(q, k, v, do)
+    check_fwd(c, B, H, S, 0.125, True, [(0, 0), (0, 1)])         # FOG's s = gamma_0^2 / sqrt(D) at D = 128
+    # Q = 0: every p is 1 and P~ = 448 exactly, so O_i is the running mean of the decoded V rows
+    c["q"] = (np.zeros_like(c["q"][0]), np.float32(1.0))
+    O, lse, _ = gpu_fwd(c, B, H, S, 0.125, True)
+    for h in range(H):
+        vv = fp8.decode(c["v"][0][0, h], fp8.E4M3) * np.float64(c["v"][1])
+        run = np.cumsum(vv, axis=0) / np.arange(1, S + 1)[:, None]
+        check_bf16(O[0, h], run, rel=1e-5, what="running mean")
+        assert np.abs(lse[0, h] - np.log2(np.arange(1, S + 1))).max() < 1e-5
+
+
+def run_bwd(c, B, H, S, s, causal, heads, do_bits):
+    """Feeds the ORACLE's forward results (O rounded to bf16, lse rounded to binary32) to both sides."""
+    O_bits = np.zeros((B, H, S, 128), np.uint16)
+    lse = np.zeros((B, H, S), np.float32)
+    fw = {}
+    for (b, h) in heads:
+        Or, lr, _ = attention.attn_fwd_head(c["q"][0][b, h], c["k"][0][b, h], c["v"][0][b, h], c["q"][1], c["k"][1], c["v"][1], s, 448.0, causal)
+        O_bits[b, h] = bf16.f64_to_bits_rne(Or)
+        lse[b, h] = lr.astype(np.float32)
+        fw[(b, h)] = (O_bits[b, h], lse[b, h])
+    # calibrate rho_dS from one oracle pass without the dS cast (delayed-style scale)
+    amax_ds = 0.0
+    for (b, h) in heads:
+        r = attention.attn_bwd_head(c["q"][0][b, h], c["k"][0][b, h], c["v"][0][b, h], c["q"][1], c["k"][1], c["v"][1],
+                                    O_bits[b, h], do_bits[b, h], c["do"][0][b, h], c["do"][1], lse[b, h], s, 448.0, 1.0, causal, True, False)
+        amax_ds = max(amax_ds, float(r[3]))
+    rho_ds, _ = scaling.compute_scale(np.float32(amax_ds), fp8.E5M2)
+    dQ, dK, dV = (torch.full((B, H, S, 128), 0x7FC0, dtype=torch.int16, device="cuda") for _ in range(3))
+    am = torch.full((1,), -1.0, device="cuda")
+    ws = torch.empty(fog.fp8_attn_workspace(B, H, S, 128, True), dtype=torch.uint8, device="cuda")
+    fog.fp8_attn_bwd(B, H, S, 128, s, causal, dev(c["q"][0]), dev(c["k"][0]), dev(c["v"][0]),
+                     fscalar(c["q"][1]), fscalar(c["k"][1]), fscalar(c["v"][1]), dev(O_bits), dev(do_bits), dev(c["do"][0]),
+                     fscalar(c["do"][1]), dev(lse), fscalar(448.0), fscalar(rho_ds), dQ, dK, dV, amax_ds=am, workspace=ws)
+    torch.cuda.synchronize()
+    dQ, dK, dV = host_u16(dQ), host_u16(dK), host_u16(dV)
+    for (b, h) in heads:
+        r = attention.attn_bwd_head(c["q"][0][b, h], c["k"][0][b, h], c["v"][0][b, h], c["q"][1], c["k"][1], c["v"][1],
+                                    O_bits[b, h], do_bits[b, h], c["do"][0][b, h], c["do"][1], lse[b, h], s, 448.0, rho_ds, causal)
+        sl = attention.bwd_cast_slack(c["q"][0][b, h], c["k"][0][b, h], c["v"][0][b, h], c["q"][1], c["k"][1], c["v"][1],
+                                      O_bits[b, h], do_bits[b, h], c["do"][0][b, h], c["do"][1], lse[b, h], s, 448.0, rho_ds,
+                                      causal, CAST_EPS)
+        check_bf16(dQ[b, h], r[0], what="dQ[%d,%d]" % (b, h), max_flip_frac=1.0, slack=sl[0])
+        check_bf16(dK[b, h], r[1], what="dK[%d,%d]" % (b, h), max_flip_frac=1.0, slack=sl[1])
+        check_bf16(dV[b, h], r[2], what="dV[%d,%d]" % (b, h), max_flip_frac=1.0, slack=sl[2])
+    if len(heads) == B * H:
+        assert abs(am.item() - amax_ds) <= 1e-4 * amax_ds
+    return dQ, dK, dV
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("B,H,S", [(1, 1, 64), (1, 2, 128), (2, 2, 320), (1, 2, 576)])
+def test_backward_parity(B, H, S, causal):
+    q, k, v, do = synth.small_attention(2000 + S, B, H, S)
+    c = cast_all(q, k, v, do)
+    run_bwd(c, B, H, S, 1 / math.sqrt(128), causal, [(b, h) for b in range(B) for h in range(H)], do)
+
+
+def test_config3_full_size_sampled_heads():
+    """Config 3 whole on the GPU (B 4, H 16, S 2048, D 128, causal); the oracle checks 4 (batch, head)
+    pairs in full (first, last, two seeded), forward and backward; every head is checked for sanity."""
+    cfg = synth.CONFIGS[3]
+    a = cfg.attn
+    t = synth.attention_tensors(cfg)
+    c = cast_all(t["Q"], t["K"], t["V"], t["dO"])
+    rng = np.random.default_rng(3)
+    heads = [(0, 0), (a.B - 1, a.H - 1)] + [(int(rng.integers(a.B)), int(rng.integers(a.H))) for _ in range(2)]
+    s = 1 / math.sqrt(128)
+    O, lse = check_fwd(c, a.B, a.H, a.S, s, True, heads)
+    Of = bf16.bits_to_f64(O)
+    assert np.isfinite(Of).all()
+    # every output row is a convex combination of decoded V rows (up to the cast of P): bounded by max |V|
+    vmax = np.abs(fp8.decode(c["v"][0], fp8.E4M3)).max() * float(c["v"][1])
+    assert np.abs(Of).max() <= vmax * 1.07
+    run_bwd(c, a.B, a.H, a.S, s, True, heads, t["dO"])
+
+
+def test_attention_argument_errors():
+    lib = fog.load()
+    st = torch.cuda.current_stream().cuda_stream
+    x = torch.zeros(64 * 128, dtype=torch.uint8, device="cuda")
+    o = torch.zeros(64 * 128, dtype=torch.int16, device="cuda")
+    f = fscalar(1.0)
+    l = torch.zeros(64, device="cuda")
+    p, fp = x.data_ptr(), f.data_ptr()
+    args = lambda D, S, q=p: (1, 1, S, D, 0.1, 1, q, p, p, fp, fp, fp, fp, o.data_ptr(), l.data_ptr(), None, None, 0, st)
+    assert lib.fog_fp8_attn_fwd(*args(64, 64)) == 4
+    assert lib.fog_fp8_attn_fwd(*args(128, 48)) == 4
+    assert lib.fog_fp8_attn_fwd(*args(128, 64, None)) == 1
+    assert lib.fog_fp8_attn_fwd(*args(128, 64, p + 4)) == 3
+    assert lib.fog_fp8_attn_fwd(*args(128, 64)) == 0
+    b = (1, 1, 64, 128, 0.1, 1, p, p, p, fp, fp, fp, o.data_ptr(), o.data_ptr(), p, fp, l.data_ptr(), fp, fp,
+         o.data_ptr(), o.data_ptr(), o.data_ptr(), None)
+    assert lib.fog_fp8_attn_bwd(*b, None, 0, st) == 5
+    ws = torch.zeros(64, device="cuda")
+    assert lib.fog_fp8_attn_bwd(*b, ws.data_ptr(), 100, st) == 5
+    assert lib.fog_fp8_attn_bwd(*b, ws.data_ptr(), 256, st) == 0
+    torch.cuda.synchronize()

@@ -217,3 +217,21 @@ def test_backward_with_casts_stays_within_fp8_error_and_q_zero_closed_form():
     want = np.stack([(pt[j:, None] * do[j:]).sum(0) for j in range(S)])
     assert np.allclose(dV, want, rtol=1e-12, atol=1e-18)
     assert np.array_equal(dK, np.zeros_like(dK))             # dK = s dS^T Q with Q = 0
+
+
+def test_cast_slack_bounds_the_effect_of_perturbed_logits():
+    """The slack must cover what a relative perturbation of the pre-cast values (inside eps) does to O,
+    and must vanish with eps."""
+    h = make_head(41, 64, 16)
+    s = 0.25
+    args = (h["q"][0], h["k"][0], h["v"][0], h["q"][1], h["k"][1], h["v"][1], s, 448.0, True)
+    O, _, _ = attention.attn_fwd_head(*args)
+    eps = 2.0 ** -8
+    slack = attention.fwd_cast_slack(*args, eps)
+    assert np.all(attention.fwd_cast_slack(*args, 0.0) == 0)
+    assert slack.max() > 0
+    # perturb rho_P by factors inside (1 - eps, 1 + eps): the codes of rho_P p move only where ambiguous,
+    # while O = (P~ V) / (rho_P l) sees the scale change cancel up to that factor
+    for f in (1 - 0.9 * eps, 1 + 0.9 * eps):
+        Of, _, _ = attention.attn_fwd_head(*args[:7], 448.0 * f, True)
+        assert np.all(np.abs(Of * f - O) <= slack + 1e-12)
