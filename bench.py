@@ -1,0 +1,129 @@
+"""Benchmark of the FP8 hot path on one MI355X.
+
+A "step" is one pass of the whole path over one synthetic batch of a BASELINE config (default:
+config 5, the 8B-scale block): for every linear layer the just-in-time casts of X, W, dY
+(abs-max -> scale -> cast, fused with the transpose for the weight gradient) and the forward /
+data-gradient / weight-gradient FP8 GEMMs, then the casts of Q, K, V, dO and FP8 causal
+attention forward and backward.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: metric = FP8 TFLOP/s of the whole step (GEMM + attention FLOPs over the
+step's wall time, casts included in the time), plus
+  roofline      -- the dominant kernel (the FP8 GEMM), timed per launch with HIP events on the
+                   launch stream inside the timed region,
+  cpu_baseline  -- the CPU oracle timed on a bounded sample of the same workload,
+  kernels       -- the same per-class figures for attention, cast and abs-max.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP8_TFLOPS = 5033.0     # 256 CU x 4 SIMD x 2048 FLOP/clk x 2.4 GHz (dense FP8 MFMA)
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(cfg):
+    """The oracle, as it stands, on a bounded sample: output rows of the first linear's forward GEMM."""
+    import numpy as np
+    from oracle import fp8, gemm, scaling
+    from paper_2505_20524_amd import synth
+    lin = cfg.linears[0] if cfg.linears else None
+    if lin is None:
+        return None
+    t = synth.linear_tensors(cfg, 0, want=("X", "W"))
+    q = {}
+    for name in ("X", "W"):
+        rho, rinv = scaling.compute_scale(scaling.amax(t[name]), fp8.E4M3)
+        q[name] = (scaling.quantize(t[name], rho, fp8.E4M3), rinv)
+    rows = np.arange(0, lin.M, max(1, lin.M // 256))[:256]
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        gemm.fp8_gemm_rows(gemm.NT, q["X"][0], fp8.E4M3, q["X"][1], q["W"][0], fp8.E4M3, q["W"][1], rows)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt > 10.0 or reps >= 50:
+            break
+    flops = 2.0 * len(rows) * lin.N * lin.K * reps
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": "%d of %d output rows of the %s forward GEMM (N=%d, K=%d), decode + float64 matmul, %d repeats, %.1f s"
+                      % (len(rows), lin.M, lin.name, lin.N, lin.K, reps, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives are on the path); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2505_20524_amd import block, fog, synth
+    fog.load()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    blk = block.Block(cfg)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        blk.step()
+    torch.cuda.synchronize()
+    # Timed region: exactly `steps` passes; HIP events around every launch (recorded on the launch
+    # stream, torch's current stream) give the per-kernel-class durations of this same region.
+    timer = block.EventTimer()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        blk.step(timer)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    value = blk.flops / (ms_per_step * 1e-3) / 1e12
+    summ = timer.summary()
+    kernels = {}
+    for kind, (n, work, ms) in summ.items():
+        if kind in ("gemm", "attn_fwd", "attn_bwd"):
+            ach = work / (ms * 1e-3) / 1e12
+            kernels[kind] = {"launches_per_step": n // args.steps, "avg_launch_ms": ms / n, "achieved": ach,
+                             "unit": "TFLOP/s", "frac": ach / PEAK_FP8_TFLOPS}
+        else:
+            ach = work / (ms * 1e-3) / 1e9
+            kernels[kind] = {"launches_per_step": n // args.steps, "avg_launch_ms": ms / n, "achieved": ach,
+                             "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
+    g = kernels.get("gemm") or kernels.get("attn_fwd")
+    roofline = {"bound": "mfma", "kernel": "fp8_gemm_kernel" if "gemm" in kernels else "attn_fwd_kernel",
+                "achieved": g["achieved"], "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": g["frac"],
+                "traffic": None, "launches_per_step": g["launches_per_step"], "avg_launch_ms": g["avg_launch_ms"]}
+
+    out = {
+        "metric": "FP8 TFLOP/s (block GEMMs fwd+dgrad+wgrad + FP8 causal attention fwd+bwd, casts in the timed step)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp8_e4m3_e5m2", "data": "synthetic",
+        "config": {"workload": "config %d: %s" % (cfg.cid, cfg.label), "gflop_per_step": blk.flops / 1e9},
+        "frac_of_fp8_peak": value / PEAK_FP8_TFLOPS,
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,175 @@
+"""Host-side driver of one pass of the hot path over a transformer block's GEMMs and attention.
+
+For every linear layer Y = X W^T of the block: just-in-time per-tensor scaling (abs-max -> scale ->
+cast) of X, W (E4M3) and dY (E5M2), the casts of X and dY fused with the transpose the
+weight-gradient product wants, then the three FP8 GEMMs (forward, data gradient, weight gradient).
+For attention: casts of Q, K, V (E4M3) and dO (E5M2), FP8 attention forward and backward.
+All arithmetic happens in the library's HIP kernels; this module only owns device buffers
+(torch tensors) and the order of calls.  The elementwise operators between the GEMMs
+(normalisation, activation, rotary embedding, residuals) are not part of the path: each GEMM
+gets its own input tensors.
+"""
+import math
+
+import numpy as np
+import torch
+
+from . import fog, synth
+
+E4M3, E5M2 = fog.E4M3, fog.E5M2
+
+
+def _dev_bits(a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+
+
+class Cast:
+    """A bf16 tensor with its FP8 cast(s) and scalars, all resident in device memory."""
+
+    def __init__(self, bits_dev, fmt, transpose):
+        self.x = bits_dev
+        self.fmt = fmt
+        rows, cols = bits_dev.shape
+        self.q = torch.empty((rows, cols), dtype=torch.uint8, device="cuda")
+        self.qT = torch.empty((cols, rows), dtype=torch.uint8, device="cuda") if transpose else None
+        self.amax = torch.zeros(1, device="cuda")
+        self.scale = torch.ones(1, device="cuda")
+        self.sinv = torch.ones(1, device="cuda")
+        self.bytes_amax = 2 * rows * cols
+        self.bytes_cast = (3 + (1 if transpose else 0)) * rows * cols
+
+    def run(self, timer=None):
+        if timer:
+            timer.begin("amax", self.bytes_amax)
+        fog.amax(self.x, self.amax)
+        if timer:
+            timer.end()
+        fog.scale(self.amax, self.fmt, self.scale, self.sinv)
+        if timer:
+            timer.begin("cast", self.bytes_cast)
+        fog.quantize(self.x, self.fmt, self.scale, q=self.q, qT=self.qT)
+        if timer:
+            timer.end()
+
+
+class LinearStep:
+    def __init__(self, lin, tensors):
+        self.lin = lin
+        M, N, K = lin.M, lin.N, lin.K
+        self.X = Cast(_dev_bits(tensors["X"]), E4M3, transpose=True)
+        self.W = Cast(_dev_bits(tensors["W"]), E4M3, transpose=False)
+        self.dY = Cast(_dev_bits(tensors["dY"]), E5M2, transpose=True)
+        self.Y = torch.empty((M, N), dtype=torch.int16, device="cuda")
+        self.dX = torch.empty((M, K), dtype=torch.int16, device="cuda")
+        self.dW = torch.empty((N, K), dtype=torch.int16, device="cuda")
+        self.flops = 3 * 2 * M * N * K
+
+    def run(self, timer=None):
+        lin = self.lin
+        M, N, K = lin.M, lin.N, lin.K
+        for c in (self.X, self.W, self.dY):
+            c.run(timer)
+        f = 2 * M * N * K
+        # forward  Y = X~ W~^T
+        if timer:
+            timer.begin("gemm", f)
+        fog.fp8_gemm(fog.NT, M, N, K, self.X.q, E4M3, self.X.sinv, self.W.q, E4M3, self.W.sinv, self.Y)
+        if timer:
+            timer.end()
+        # data gradient  dX = dY~ W~  (W~ is [N, K]: the contraction index N is its row index)
+        if timer:
+            timer.begin("gemm", f)
+        fog.fp8_gemm(fog.NN, M, K, N, self.dY.q, E5M2, self.dY.sinv, self.W.q, E4M3, self.W.sinv, self.dX)
+        if timer:
+            timer.end()
+        # weight gradient  dW = dY~^T X~, as NT on the transposed copies the cast kernel emitted
+        if timer:
+            timer.begin("gemm", f)
+        fog.fp8_gemm(fog.NT, N, K, M, self.dY.qT, E5M2, self.dY.sinv, self.X.qT, E4M3, self.X.sinv, self.dW)
+        if timer:
+            timer.end()
+
+
+class AttentionStep:
+    def __init__(self, attn, tensors, softmax_scale=None):
+        a = self.attn = attn
+        n = a.B * a.H * a.S
+        self.s = softmax_scale if softmax_scale is not None else 1.0 / math.sqrt(a.D)
+        self.c = {name: Cast(_dev_bits(tensors[name].reshape(n, a.D)), E5M2 if name == "dO" else E4M3, False)
+                  for name in ("Q", "K", "V", "dO")}
+        self.O = torch.empty((n, a.D), dtype=torch.int16, device="cuda")
+        self.lse = torch.empty(n, device="cuda")
+        self.dQ, self.dK, self.dV = (torch.empty((n, a.D), dtype=torch.int16, device="cuda") for _ in range(3))
+        self.scale_p = torch.full((1,), 448.0, device="cuda")
+        self.amax_ds = torch.zeros(1, device="cuda")
+        self.scale_ds = torch.ones(1, device="cuda")
+        self.ws = torch.empty(max(fog.fp8_attn_workspace(a.B, a.H, a.S, a.D, True), 16), dtype=torch.uint8, device="cuda")
+        self.flops_fwd = 4 * a.S * a.S * a.D // 2 * a.B * a.H      # causal: blocks at or below the diagonal
+        self.flops_bwd = self.flops_fwd * 5 // 2
+        self.flops = self.flops_fwd + self.flops_bwd
+        self.calibrated = False
+
+    def run(self, timer=None):
+        a, c = self.attn, self.c
+        for name in ("Q", "K", "V"):
+            c[name].run(timer)
+        if timer:
+            timer.begin("attn_fwd", self.flops_fwd)
+        fog.fp8_attn_fwd(a.B, a.H, a.S, a.D, self.s, True, c["Q"].q, c["K"].q, c["V"].q, c["Q"].sinv, c["K"].sinv,
+                         c["V"].sinv, self.scale_p, self.O, self.lse)
+        if timer:
+            timer.end()
+        c["dO"].run(timer)
+        if timer:
+            timer.begin("attn_bwd", self.flops_bwd)
+        # delayed-style scale for dS: the abs-max this call reports sets the scale of the next call
+        fog.fp8_attn_bwd(a.B, a.H, a.S, a.D, self.s, True, c["Q"].q, c["K"].q, c["V"].q, c["Q"].sinv, c["K"].sinv,
+                         c["V"].sinv, self.O, c["dO"].x, c["dO"].q, c["dO"].sinv, self.lse, self.scale_p, self.scale_ds,
+                         self.dQ, self.dK, self.dV, amax_ds=self.amax_ds, workspace=self.ws)
+        if timer:
+            timer.end()
+        fog.scale(self.amax_ds, E5M2, self.scale_ds, None)
+
+
+class Block:
+    """All linears and the attention of one synthetic config, resident on the GPU."""
+
+    def __init__(self, cfg):
+        self.cfg = cfg
+        self.linears = [LinearStep(lin, synth.linear_tensors(cfg, i)) for i, lin in enumerate(cfg.linears)]
+        self.attn = AttentionStep(cfg.attn, synth.attention_tensors(cfg)) if cfg.attn is not None else None
+        self.flops = sum(l.flops for l in self.linears) + (self.attn.flops if self.attn else 0)
+
+    def step(self, timer=None):
+        for l in self.linears:
+            l.run(timer)
+        if self.attn:
+            self.attn.run(timer)
+
+
+class EventTimer:
+    """Per-kernel-class HIP-event timing on the stream the library launches on (torch's current stream)."""
+
+    def __init__(self):
+        self.spans = []
+        self._open = None
+
+    def begin(self, kind, work):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        self._open = (kind, work, e0)
+
+    def end(self):
+        kind, work, e0 = self._open
+        e1 = torch.cuda.Event(enable_timing=True)
+        e1.record()
+        self.spans.append((kind, work, e0, e1))
+        self._open = None
+
+    def summary(self):
+        """kind -> (launches, total work, total milliseconds); call after a synchronize."""
+        out = {}
+        for kind, work, e0, e1 in self.spans:
+            n, w, ms = out.get(kind, (0, 0, 0.0))
+            out[kind] = (n + 1, w + work, ms + e0.elapsed_time(e1))
+        return out
