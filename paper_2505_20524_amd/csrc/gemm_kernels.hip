@@ -2,20 +2,26 @@
 // (the end-to-end FP8 product of Appendix E of the paper), in the three layouts a linear layer
 // needs: NT (forward), NN (data gradient), TN (weight gradient).
 //
-// Design: one workgroup of 4 waves owns a 256 x 256 tile of C and walks K in steps of 128 bytes.
-// Each wave owns a 128 x 128 quadrant = 4 x 4 MFMA tiles of v_mfma_f32_32x32x64_f8f6f4
-// (256 accumulator registers), so every 32-byte operand fragment read from LDS feeds four MFMAs.
-// Operand tiles are double buffered in LDS; the next K-step's global loads are issued before the
-// current step's MFMAs and written to the other buffer afterwards (one barrier per step).
+// Design: one workgroup of 4 waves owns a 256 x 256 tile of C and walks K in steps of 64 bytes, one
+// v_mfma_f32_32x32x64_f8f6f4 deep.  Each wave owns a 128 x 128 quadrant = 4 x 4 MFMA tiles (256
+// accumulator registers), so every 32-byte operand fragment read from LDS feeds four MFMAs.
 //
-// Operand storage in LDS, chosen so that fragment reads are bank-conflict free:
-//   * "K-contiguous" operands (A of NT/NN, B of NT): [256 rows][128 bytes], 16-byte chunks
-//     XOR-swizzled with (row & 7); a lane reads its 32 contraction bytes with two 16-byte reads.
-//   * "K-major" operands (B of NN, A and B of TN): [128 k][256 + 16 bytes]; a lane gathers 8
-//     contraction bytes of its own column with the byte-transposing LDS read
-//     (ds_read_b64_tr_b8), four of them per 32-byte fragment.
-// Both give byte j of a lane's fragment the contraction index 32 * (lane / 32) + j within a
-// 64-wide half step, which is what the MFMA expects of both operands.
+// Memory pipeline: operand tiles go from global memory straight into LDS (buffer_load ... lds, no
+// register staging) through a ring of 4 stages of 32 KB; three K-steps are in flight while the fragments of a
+// fourth are consumed from registers, which covers HBM/L2 latency with a single workgroup per CU.  Out-of-range rows, columns
+// and K tails are zero-filled by the buffer bounds check.  Fragments are double buffered in
+// registers: the LDS reads of step k+1 are issued before the 16 MFMAs of step k.
+//
+// Operand storage in LDS, chosen so that the direct loads (which write 64 lanes x 16 bytes
+// contiguously) and the fragment reads are both bank-conflict free:
+//   * "K-contiguous" operands (A of NT/NN, B of NT): [256 rows][64 bytes]; the four 16-byte chunks of
+//     a row are XOR-swizzled with (row >> 2) & 3 by choosing which global chunk each lane fetches;
+//     a lane reads its 32 contraction bytes with two 16-byte reads.
+//   * "K-major" operands (B of NN, A and B of TN): [64 k][256 bytes], the sixteen chunks of a row
+//     swizzled with k & 7; a lane gathers 8 contraction bytes of its own column with the
+//     byte-transposing LDS read (ds_read_b64_tr_b8), four of them per 32-byte fragment.
+// Both give byte j of a lane's fragment the contraction index 32 * (lane / 32) + j of the step,
+// which is what the MFMA expects of both operands.
 //
 // The MFMA is issued with the B fragment as first operand so that a lane ends up with four
 // consecutive output columns per register quad and can store 8 bytes of bf16 at a time.
@@ -24,14 +30,16 @@
 
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 128;
+constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kThreads = 256;
-constexpr int KC_BYTES = 256 * BK;          // K-contiguous operand tile
-constexpr int KM_STRIDE = 256 + 16;         // K-major operand tile row stride
-constexpr int KM_BYTES = BK * KM_STRIDE;
-constexpr int OPERAND_BYTES = KM_BYTES;     // slot size (the larger of the two)
+constexpr int NSTAGE = 4;
+constexpr int OPERAND_BYTES = 256 * BK;      // 16 KB, both storage forms
 constexpr int STAGE_BYTES = 2 * OPERAND_BYTES;
-constexpr int LDS_BYTES = 2 * STAGE_BYTES;  // 139264
+constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;  // 131072
+constexpr int EPI_STRIDE = 128 + 16;          // epilogue staging: 32 rows x 64 bf16 per wave, padded rows
+constexpr int EPI_BYTES = 32 * EPI_STRIDE;    // per wave
+constexpr int LDS_BYTES = RING_BYTES + 4 * EPI_BYTES;  // 149504
+constexpr uint32_t OOB = 0x80000000u;        // a buffer offset past any operand (spans are < 2^31 bytes)
 
 struct GemmArgs {
   const uint8_t* A;
@@ -42,116 +50,197 @@ struct GemmArgs {
   int64_t lda, ldb, ldc;
   int M, N, K;
   int tiles_m, tiles_n;
-  int vec_store;  // C rows allow 8-byte stores
+  int vec_store;  // C rows allow 16-byte stores
+  uint32_t a_bytes, b_bytes;  // addressable span of each operand
 };
 
 typedef __attribute__((address_space(3))) v2i* lds_v2i_ptr;
 
-// ---- global -> registers, one K-step of one operand (8 x 16 bytes per thread) ----
-// K-contiguous: tile rows are matrix rows [row0, row0+256), bytes [k0, k0+128).
-FOG_DEVICE void gload_kc(const uint8_t* __restrict__ base, int64_t ld, int row0, int rows, int k0, int K, uint4* r) {
-  const int t = threadIdx.x;
-  const int cc = t & 7;
-  const int k = k0 + cc * 16;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    int row = row0 + (t >> 3) + 32 * i;
-    row = row < rows ? row : rows - 1;  // clamp: rows past the edge are computed but never stored
-    if (k < K)
-      r[i] = *reinterpret_cast<const uint4*>(base + (int64_t)row * ld + k);
-    else
-      r[i] = make_uint4(0, 0, 0, 0);
-  }
+// 16 bytes per lane from buffer `rsrc` at byte offset `voff` (zero when out of range) to
+// LDS[m0 + 16 * lane].  Issued as inline assembly so that the compiler's own wait-count
+// insertion does not serialise the LDS reads of other stages behind these loads; completion is
+// awaited explicitly with s_waitcnt vmcnt + barrier in the main loop.
+FOG_DEVICE void load_to_lds(v4i rsrc, uint32_t voff, uint32_t lds_addr_uniform) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
+               :
+               : "v"(voff), "s"(rsrc), "s"(lds_addr_uniform)
+               : "memory", "m0");
 }
-FOG_DEVICE void swrite_kc(uint8_t* lds, const uint4* r) {
-  const int t = threadIdx.x;
-  const int cc = t & 7;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int row = (t >> 3) + 32 * i;
-    *reinterpret_cast<uint4*>(lds + row * BK + ((cc ^ (row & 7)) << 4)) = r[i];
-  }
+
+// Raw buffer descriptor (stride 0): 48-bit base, byte count for the bounds check, dword-format flags.
+FOG_DEVICE v4i make_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t b = reinterpret_cast<uint64_t>(base);
+  v4i r;
+  r[0] = (int)(uint32_t)b;
+  r[1] = (int)((uint32_t)(b >> 32) & 0xFFFFu);
+  r[2] = (int)bytes;
+  r[3] = 0x00020000;
+  return r;
 }
-// K-major: tile rows are contraction indices [k0, k0+128), bytes are columns [col0, col0+256).
-FOG_DEVICE void gload_km(const uint8_t* __restrict__ base, int64_t ld, int col0, int cols, int k0, int K, uint4* r) {
-  const int t = threadIdx.x;
-  const int cc = t & 15;
-  const int c = col0 + cc * 16;
+
+// Per-thread state of one operand's direct loads: 4 pieces of 1 KB per wave and K-step.
+struct LoadPlan {
+  uint32_t off[4];   // byte offset of the NEXT step to issue, or >= OOB when the row / column chunk is outside the matrix
+  uint32_t kpos[4];  // contraction index this lane's chunk starts at within a step (for the K tail)
+  uint32_t step;     // offset increment per K-step
+};
+
+// K-contiguous operand: piece p covers tile rows 16 p .. 16 p + 15; lane -> (row, LDS chunk position).
+FOG_DEVICE LoadPlan plan_kc(int64_t ld, int row0, int rows) {
+  const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+  LoadPlan p;
+  p.step = BK;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int k = k0 + (t >> 4) + 16 * i;
-    if (k < K && c < cols)  // cols % 16 == 0: a chunk is inside or outside as a whole
-      r[i] = *reinterpret_cast<const uint4*>(base + (int64_t)k * ld + c);
-    else
-      r[i] = make_uint4(0, 0, 0, 0);
+  for (int j = 0; j < 4; ++j) {
+    const int row = 16 * (4 * w + j) + (l >> 2);
+    const int c = (l & 3) ^ ((row >> 2) & 3);  // global chunk that lives at LDS position (l & 3) of this row
+    p.kpos[j] = 16 * c;
+    p.off[j] = (row0 + row < rows) ? (uint32_t)((int64_t)(row0 + row) * ld + 16 * c) : OOB;
   }
+  return p;
 }
-FOG_DEVICE void swrite_km(uint8_t* lds, const uint4* r) {
-  const int t = threadIdx.x;
-  const int cc = t & 15;
+// K-major operand: piece p covers contraction rows 4 p .. 4 p + 3; lane -> (k, LDS chunk position).
+FOG_DEVICE LoadPlan plan_km(int64_t ld, int col0, int cols) {
+  const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+  LoadPlan p;
+  p.step = (uint32_t)(BK * ld);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int k = (t >> 4) + 16 * i;
-    *reinterpret_cast<uint4*>(lds + k * KM_STRIDE + cc * 16) = r[i];
+  for (int j = 0; j < 4; ++j) {
+    const int k = 4 * (4 * w + j) + (l >> 4);
+    const int c = (l & 15) ^ (k & 7);
+    p.kpos[j] = k;
+    p.off[j] = (col0 + 16 * c < cols) ? (uint32_t)((int64_t)k * ld + col0 + 16 * c) : OOB;  // cols % 16 == 0
+  }
+  return p;
+}
+// Issue the next K-step (number kt) of one operand into LDS at `lds_wave_base` (+ 1 KB per piece) and
+// advance the plan.  Steps that reach past K take the checked path: lanes whose contraction index
+// is >= K fetch zeros.  Offsets that start at OOB stay >= OOB (spans are < 2^31 bytes).
+FOG_DEVICE void issue_loads(LoadPlan& p, v4i rsrc, int kt, int K, uint32_t lds_wave_base) {
+  if ((kt + 1) * BK <= K) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      load_to_lds(rsrc, p.off[j], lds_wave_base + 1024u * j);
+      p.off[j] += p.step;
+    }
+  } else {
+    const int k0 = kt * BK;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      load_to_lds(rsrc, (k0 + (int)p.kpos[j] >= K) ? OOB : p.off[j], lds_wave_base + 1024u * j);
+      p.off[j] += p.step;
+    }
   }
 }
 
-// ---- LDS -> MFMA operand fragment (32 rows x 64 contraction bytes; 32 bytes per lane) ----
-FOG_DEVICE v8i frag_kc(const uint8_t* lds, int row_base, int h) {
+// ---- LDS -> MFMA operand fragments (32 rows x 64 contraction bytes; 32 bytes per lane) ----
+// Per-lane byte offsets inside an operand tile, computed once; tile i / read r / stage are added as
+// compile-time constants so that they fold into the instructions' immediate offsets.
+struct FragAddr {
+  uint32_t a[4];
+};
+// K-contiguous: a[0], a[1] = the two 16-byte chunks of row (l & 31); row tile i adds 2048 i.
+FOG_DEVICE FragAddr fragaddr_kc(int row_base) {
   const int l = threadIdx.x & 63;
-  const int row = row_base + (l & 31);
-  const int chunk = 4 * h + 2 * (l >> 5);
-  const uint8_t* p = lds + row * BK;
-  v4i lo = *reinterpret_cast<const v4i*>(p + ((chunk ^ (row & 7)) << 4));
-  v4i hi = *reinterpret_cast<const v4i*>(p + (((chunk + 1) ^ (row & 7)) << 4));
-  v8i f;
-  f[0] = lo[0]; f[1] = lo[1]; f[2] = lo[2]; f[3] = lo[3];
-  f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3];
+  const int row = row_base + (l & 31);   // row_base is a multiple of 32: the swizzle key is tile-independent
+  const int s = (row >> 2) & 3;
+  const int c = 2 * (l >> 5);
+  FragAddr f;
+  f.a[0] = row * BK + ((c ^ s) << 4);
+  f.a[1] = row * BK + (((c + 1) ^ s) << 4);
+  f.a[2] = f.a[3] = 0;
   return f;
 }
-FOG_DEVICE v8i frag_km(const uint8_t* lds, int col_base, int h) {
+// K-major: a[j] = address of this lane's 8-byte piece for column tile j, read 0; read r adds 2048 r.
+// Within a block of 16 lanes the transposing read hands lane i the bytes (i & 7) of the rows addressed
+// by lanes 2 jj + (i >> 3), jj = 0..7.  Lane p therefore points at contraction row kbase + p / 2 and at
+// the 8-byte column group p % 2, which gives lane i column col + i.
+FOG_DEVICE FragAddr fragaddr_km(int col_base) {
   const int l = threadIdx.x & 63;
   const int i = l & 15;
-  // Within a block of 16 lanes the transposing read hands lane i the bytes (i & 7) of the rows
-  // addressed by lanes 2j + (i >> 3), j = 0..7.  Lane p therefore points at contraction row
-  // kbase + p / 2 and at the 8-byte column group p % 2, which gives lane i column col + i.
-  const int col = col_base + (l & 16) + 8 * (i & 1);
-  const int kb = 64 * h + 32 * (l >> 5) + (i >> 1);
-  v8i f;
+  const int k = 32 * (l >> 5) + (i >> 1);   // + 8 r: the swizzle key k & 7 does not depend on r
+  FragAddr f;
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    v2i v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + (kb + 8 * r) * KM_STRIDE + col));
-    f[2 * r] = v[0];
-    f[2 * r + 1] = v[1];
+  for (int j = 0; j < 4; ++j) {
+    const int col = col_base + 32 * j + (l & 16) + 8 * (i & 1);
+    f.a[j] = k * 256 + (((col >> 4) ^ (k & 7)) << 4) + (col & 8);
   }
   return f;
+}
+template <bool KM>
+FOG_DEVICE v8i read_frag(const uint8_t* tile, const FragAddr& fa, int i) {
+  v8i f;
+  if (KM) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      v2i v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(tile + fa.a[i] + 2048 * r));
+      f[2 * r] = v[0];
+      f[2 * r + 1] = v[1];
+    }
+  } else {
+    v4i lo = *reinterpret_cast<const v4i*>(tile + fa.a[0] + 2048 * i);
+    v4i hi = *reinterpret_cast<const v4i*>(tile + fa.a[1] + 2048 * i);
+    f[0] = lo[0]; f[1] = lo[1]; f[2] = lo[2]; f[3] = lo[3];
+    f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3];
+  }
+  return f;
+}
+
+// Tile order.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Every XCD
+// owns one contiguous run of logical tile numbers and its workgroups walk that run together, so that
+// the tiles in flight on an XCD at any time are neighbours (groups of 8 tile rows, column by
+// column) and share a few A and B panels.
+struct TileWalk {
+  int first, end, stride;  // logical tile numbers of this workgroup: first, first + stride, ... < end
+};
+FOG_DEVICE TileWalk tile_walk(int total) {
+  const int per_xcd = (total + 7) >> 3;
+  const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3, n_in_xcd = gridDim.x >> 3;
+  TileWalk t;
+  t.first = xcd * per_xcd + idx;
+  t.end = min(total, (xcd + 1) * per_xcd);
+  t.stride = n_in_xcd;
+  return t;
+}
+FOG_DEVICE void tile_origin(int logical, int tiles_m, int tiles_n, int& m0, int& n0) {
+  constexpr int GM = 8;
+  const int width = GM * tiles_n;
+  const int group = logical / width;
+  const int first_m = group * GM;
+  const int gsz = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+  const int rem = logical - group * width;
+  m0 = (first_m + rem % gsz) * BM;
+  n0 = (rem / gsz) * BN;
+}
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+// Two floats -> packed bf16 with the hardware convert (round to nearest even).
+FOG_DEVICE uint32_t cvt_pk_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 template <int LAYOUT, int FA, int FB>
 __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
-  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   constexpr bool A_KM = LAYOUT == FOG_TN;
   constexpr bool B_KM = LAYOUT != FOG_NT;
 
-  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD one
-  // contiguous run of tiles, walked in groups of 8 tile rows, so that the tiles resident on an
-  // XCD at any time share a few A and B panels.
-  const int total = g.tiles_m * g.tiles_n;
-  const int per_xcd = (total + 7) >> 3;
-  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (logical >= total) return;
-  constexpr int GM = 8;
-  const int width = GM * g.tiles_n;
-  const int group = logical / width;
-  const int first_m = group * GM;
-  const int gsz = (g.tiles_m - first_m) < GM ? (g.tiles_m - first_m) : GM;
-  const int rem = logical - group * width;
-  const int tm = first_m + rem % gsz;
-  const int tn = rem / gsz;
-  const int m0 = tm * BM, n0 = tn * BN;
+  const TileWalk walk = tile_walk(g.tiles_m * g.tiles_n);
+  if (walk.first >= walk.end) return;
 
   const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
   const int wm = (w >> 1) * 128, wn = (w & 1) * 128;
+
+  const v4i rsrc_a = make_rsrc(g.A, g.a_bytes), rsrc_b = make_rsrc(g.B, g.b_bytes);
+  // LDS byte address of this wave's first piece in stage 0 (wave-uniform, kept in a scalar register)
+  const uint32_t lds_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(uintptr_t)smem + 4096u * w));
+  const FragAddr fa_addr = A_KM ? fragaddr_km(wm) : fragaddr_kc(wm);
+  const FragAddr fb_addr = B_KM ? fragaddr_km(wn) : fragaddr_kc(wn);
+  // Second base 64 KB up: keeps every fragment read's constant part inside the 16-bit immediate.
+  const uint8_t* smem_hi = smem + 2 * STAGE_BYTES;
+  const float alpha = (*g.sinv_a) * (*g.sinv_b);
 
   v16f acc[4][4];
 #pragma unroll
@@ -162,75 +251,163 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   const int nk = (g.K + BK - 1) / BK;
-  uint4 ra[8], rb[8];
+  const int nk4 = (nk + 3) & ~3;  // steps are handled four at a time (one per LDS stage); steps past K multiply zeros
 
-  auto gload = [&](int kt) {
-    if (A_KM) gload_km(g.A, g.lda, m0, g.M, kt * BK, g.K, ra); else gload_kc(g.A, g.lda, m0, g.M, kt * BK, g.K, ra);
-    if (B_KM) gload_km(g.B, g.ldb, n0, g.N, kt * BK, g.K, rb); else gload_kc(g.B, g.ldb, n0, g.N, kt * BK, g.K, rb);
-  };
-  auto swrite = [&](int stage) {
-    uint8_t* sa = smem + stage * STAGE_BYTES;
-    uint8_t* sb = sa + OPERAND_BYTES;
-    if (A_KM) swrite_km(sa, ra); else swrite_kc(sa, ra);
-    if (B_KM) swrite_km(sb, rb); else swrite_kc(sb, rb);
-  };
+#define FOG_ISSUE(kt, STAGE)                                                            \
+  do {                                                                                  \
+    issue_loads(pa, rsrc_a, (kt), g.K, lds_w + (STAGE) * STAGE_BYTES);                  \
+    issue_loads(pb, rsrc_b, (kt), g.K, lds_w + (STAGE) * STAGE_BYTES + OPERAND_BYTES);  \
+  } while (0)
+#define FOG_READ(STAGE, FA_, FB_)                                                                        \
+  do {                                                                                                   \
+    const uint8_t* sa_ = ((STAGE) < 2 ? smem : smem_hi) + ((STAGE) & 1) * STAGE_BYTES;                   \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) FA_[i] = read_frag<A_KM>(sa_, fa_addr, i);             \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) FB_[j] = read_frag<B_KM>(sa_ + OPERAND_BYTES, fb_addr, j); \
+  } while (0)
+#define FOG_MFMAS(FA_, FB_)                                                                              \
+  do {                                                                                                   \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                        \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                        \
+      acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(FB_[j], FA_[i], acc[i][j], FB, FA, 0, 0, 0, 0); \
+  } while (0)
+  // Wait until at most N of this thread's vector-memory operations are outstanding and its own
+  // fragment reads have returned, then synchronise: the awaited step is visible to every wave and
+  // the stage whose fragments were read during the previous step is free to be overwritten.
+  // The counter is decremented in issue order, so N = 16 (two K-steps of 8 loads) means "the step
+  // after the current one has landed".  Right after an epilogue the 32 output stores of the
+  // finished tile are outstanding too and younger than the loads that matter, so N = 48 for the
+  // first three steps of the next tile: the stores drain while that tile computes.
+  // s_waitcnt immediates: lgkmcnt = 0, expcnt unbounded, vmcnt = 16 (0x4070) or 48 (0xC070).
+#define FOG_WAIT_STEP(LAX)                                  \
+  do {                                                      \
+    if (LAX) __builtin_amdgcn_s_waitcnt(0xC070);            \
+    else     __builtin_amdgcn_s_waitcnt(0x4070);            \
+    __syncthreads();                                        \
+  } while (0)
+  // One K-step: wait for the next step's data; past the barrier the stage of the step whose
+  // fragments are already in registers is free, so the load four steps ahead goes there (three
+  // K-steps stay in flight); fetch the next step's fragments; run this step's 16 MFMAs.
+#define FOG_STEP(kt_issue, ST_ISSUE, ST_READ, FA_IN, FB_IN, FA_CUR, FB_CUR, LAX) \
+  do {                                                                      \
+    FOG_WAIT_STEP(LAX);                                                     \
+    FOG_ISSUE(kt_issue, ST_ISSUE);                                          \
+    FOG_READ(ST_READ, FA_IN, FB_IN);                                        \
+    FOG_MFMAS(FA_CUR, FB_CUR);                                              \
+  } while (0)
 
-  if (nk > 0) {
-    gload(0);
-    swrite(0);
-  }
+  // The load stream runs ahead of the MFMAs across tile boundaries: during the last four steps of a
+  // tile the first four steps of the workgroup's next tile are already being fetched, so a new tile
+  // starts with its data in LDS and its first fragments in registers, and the epilogue's stores
+  // drain while the next tile computes.
+  int m0, n0;
+  tile_origin(walk.first, g.tiles_m, g.tiles_n, m0, n0);
+  LoadPlan pa = A_KM ? plan_km(g.lda, m0, g.M) : plan_kc(g.lda, m0, g.M);
+  LoadPlan pb = B_KM ? plan_km(g.ldb, n0, g.N) : plan_kc(g.ldb, n0, g.N);
+  v8i xa[4], xb[4], ya[4], yb[4];
+  FOG_ISSUE(0, 0);
+  FOG_ISSUE(1, 1);
+  FOG_ISSUE(2, 2);
+  FOG_ISSUE(3, 3);
+  __builtin_amdgcn_s_waitcnt(0x4F78);  // vmcnt = 24: step 0 has landed
   __syncthreads();
+  FOG_READ(0, xa, xb);
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) gload(kt + 1);
-    const uint8_t* sa = smem + cur * STAGE_BYTES;
-    const uint8_t* sb = sa + OPERAND_BYTES;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      v8i fa[4], fb[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) fa[i] = A_KM ? frag_km(sa, wm + 32 * i, h) : frag_kc(sa, wm + 32 * i, h);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) fb[j] = B_KM ? frag_km(sb, wn + 32 * j, h) : frag_kc(sb, wn + 32 * j, h);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j], fa[i], acc[i][j], FB, FA, 0, 0, 0, 0);
-    }
-    if (kt + 1 < nk) swrite(cur ^ 1);
-    __syncthreads();
-  }
-
-  // Epilogue.  With B as the first MFMA operand, lane l holds for tile (i, j), register r:
-  //   row    m = m0 + wm + 32 i + (l & 31)
-  //   column n = n0 + wn + 32 j + 8 (r / 4) + 4 (l / 32) + (r % 4)
-  const float alpha = (*g.sinv_a) * (*g.sinv_b);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int m = m0 + wm + 32 * i + (l & 31);
-    if (m >= g.M) continue;
-    uint16_t* crow = g.C + (int64_t)m * g.ldc;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-#pragma unroll
-      for (int qd = 0; qd < 4; ++qd) {
-        const int n = n0 + wn + 32 * j + 8 * qd + 4 * (l >> 5);
-        const float v0 = acc[i][j][4 * qd + 0] * alpha, v1 = acc[i][j][4 * qd + 1] * alpha;
-        const float v2 = acc[i][j][4 * qd + 2] * alpha, v3 = acc[i][j][4 * qd + 3] * alpha;
-        if (g.vec_store && n + 3 < g.N) {
-          uint2 o = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
-          *reinterpret_cast<uint2*>(crow + n) = o;
+  uint8_t* epi = smem + RING_BYTES + w * EPI_BYTES;  // this wave's private staging area
+  bool stores_pending = false;                        // uniform: an epilogue's stores may still be in flight
+  for (int tile = walk.first; tile < walk.end; tile += walk.stride) {
+    const int m_cur = m0, n_cur = n0;
+    const int next = tile + walk.stride;
+    for (int kt = 0; kt < nk4; kt += 4) {
+      if (kt == nk4 - 4) {
+        // last four steps of this tile: the loads issued now belong to the next tile (all
+        // zero-fill if there is none, which keeps the outstanding-load count the waits assume)
+        if (next < walk.end) {
+          tile_origin(next, g.tiles_m, g.tiles_n, m0, n0);
+          pa = A_KM ? plan_km(g.lda, m0, g.M) : plan_kc(g.lda, m0, g.M);
+          pb = B_KM ? plan_km(g.ldb, n0, g.N) : plan_kc(g.ldb, n0, g.N);
         } else {
-          if (n + 0 < g.N) crow[n + 0] = (uint16_t)f32_to_bf16(v0);
-          if (n + 1 < g.N) crow[n + 1] = (uint16_t)f32_to_bf16(v1);
-          if (n + 2 < g.N) crow[n + 2] = (uint16_t)f32_to_bf16(v2);
-          if (n + 3 < g.N) crow[n + 3] = (uint16_t)f32_to_bf16(v3);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) pa.off[j] = pb.off[j] = OOB;
+        }
+      }
+      const int ki = kt == nk4 - 4 ? 0 : kt + 4;  // K-step number (within its tile) of the first load issued below
+      FOG_STEP(ki + 0, 0, 1, ya, yb, xa, xb, stores_pending);
+      FOG_STEP(ki + 1, 1, 2, xa, xb, ya, yb, stores_pending);
+      FOG_STEP(ki + 2, 2, 3, ya, yb, xa, xb, stores_pending);
+      FOG_STEP(ki + 3, 3, 0, xa, xb, ya, yb, false);
+      stores_pending = false;
+    }
+    // xa, xb now hold step 0 of the next tile.
+
+    // Epilogue.  With B as the first MFMA operand, lane l holds for tile (i, j), register r:
+    //   row    m = m_cur + wm + 32 i + (l & 31)
+    //   column n = n_cur + wn + 32 j + 8 (r / 4) + 4 (l / 32) + (r % 4)
+    // Each 32 x 64 block is scaled, converted to bf16, parked in the wave's LDS area and written out
+    // as 16-byte pieces, eight lanes per 128-byte row segment: 32 fully coalesced stores per lane.
+    const bool fast = g.vec_store != 0 && m_cur + BM <= g.M && n_cur + BN <= g.N;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          const int j = 2 * half + jj;
+#pragma unroll
+          for (int qd = 0; qd < 4; ++qd) {
+            const float v0 = acc[i][j][4 * qd + 0] * alpha, v1 = acc[i][j][4 * qd + 1] * alpha;
+            const float v2 = acc[i][j][4 * qd + 2] * alpha, v3 = acc[i][j][4 * qd + 3] * alpha;
+            acc[i][j][4 * qd + 0] = 0.0f; acc[i][j][4 * qd + 1] = 0.0f;
+            acc[i][j][4 * qd + 2] = 0.0f; acc[i][j][4 * qd + 3] = 0.0f;
+            const int ncol = 32 * jj + 8 * qd + 4 * (l >> 5);  // column inside the 64-wide block
+            *reinterpret_cast<uint2*>(epi + (l & 31) * EPI_STRIDE + 2 * ncol) = make_uint2(cvt_pk_bf16(v0, v1), cvt_pk_bf16(v2, v3));
+          }
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int row = 8 * t + (l >> 3), piece = l & 7;  // 8 lanes cover one 128-byte row segment
+          const uint4 v = *reinterpret_cast<const uint4*>(epi + row * EPI_STRIDE + 16 * piece);
+          const int m = m_cur + wm + 32 * i + row;
+          const int n = n_cur + wn + 64 * half + 8 * piece;
+          uint16_t* dst = g.C + (int64_t)m * g.ldc + n;
+          if (fast) {
+            *reinterpret_cast<uint4*>(dst) = v;
+          } else if (m < g.M) {
+            const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (n + e < g.N) dst[e] = (uint16_t)(wv[e >> 1] >> (16 * (e & 1)));
+          }
         }
       }
     }
+    stores_pending = fast;  // the slow path is only taken by edge tiles; its stores are simply waited for
+    if (!fast) __builtin_amdgcn_s_waitcnt(0x0F70);
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
+#undef FOG_ISSUE
+#undef FOG_READ
+#undef FOG_MFMAS
+#undef FOG_WAIT_STEP
+#undef FOG_STEP
+}
+
+// C = 0 for K == 0 (no contraction): bf16 zeros.
+__global__ __launch_bounds__(256) void gemm_zero_kernel(uint16_t* C, int64_t ldc, int M, int N) {
+  const int64_t total = (int64_t)M * N;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256)
+    C[(i / N) * ldc + (i % N)] = 0;
+}
+
+// Number of compute units of the current device (the persistent grid size), queried once per process.
+int compute_units() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    cus = n;
+  }
+  return cus;
 }
 
 template <int LAYOUT, int FA, int FB>
@@ -242,8 +419,13 @@ fog_status launch(const GemmArgs& g, hipStream_t s) {
       return FOG_ERR_HIP;
     configured = true;
   }
+  // Persistent grid: one workgroup per compute unit (a multiple of 8 so that every XCD gets the
+  // same number), fewer when there are fewer tiles.
   const int total = g.tiles_m * g.tiles_n;
-  const int grid = ((total + 7) / 8) * 8;
+  int grid = (compute_units() / 8) * 8;
+  if (grid < 8) grid = 8;
+  const int need = ((total + 7) / 8) * 8;
+  if (grid > need) grid = need;
   kern<<<grid, kThreads, LDS_BYTES, s>>>(g);
   return fog_launch_status();
 }
@@ -288,8 +470,19 @@ extern "C" fog_status fog_fp8_gemm(fog_layout layout, int64_t M, int64_t N, int6
   g.tiles_m = (int)((M + BM - 1) / BM);
   g.tiles_n = (int)((N + BN - 1) / BN);
   if ((int64_t)g.tiles_m * g.tiles_n > 0x7FFFFFF0) return FOG_ERR_UNSUPPORTED;
-  g.vec_store = aligned(C_bf16, 8) && ldc % 4 == 0;
+  g.vec_store = aligned(C_bf16, 16) && ldc % 8 == 0;
+  // addressable span of each operand (last row may be shorter than the leading dimension)
+  const int64_t a_rows = layout == FOG_TN ? K : M, b_rows = layout == FOG_NT ? N : K;
+  const int64_t a_span = K > 0 ? (a_rows - 1) * lda + a_cols : 0, b_span = K > 0 ? (b_rows - 1) * ldb + b_cols : 0;
+  if (a_span >= 0x7FFFFFFF || b_span >= 0x7FFFFFFF) return FOG_ERR_UNSUPPORTED;  // 32-bit buffer offsets
+  g.a_bytes = (uint32_t)a_span; g.b_bytes = (uint32_t)b_span;
   hipStream_t s = (hipStream_t)stream;
+  if (K == 0) {
+    int64_t blocks = (M * N + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    gemm_zero_kernel<<<(int)blocks, 256, 0, s>>>(g.C, ldc, g.M, g.N);
+    return fog_launch_status();
+  }
   switch (layout) {
     case FOG_NT: return launch_fmt<FOG_NT>(g, fmtA, fmtB, s);
     case FOG_NN: return launch_fmt<FOG_NN>(g, fmtA, fmtB, s);
