@@ -17,6 +17,13 @@
 // keys is a permutation of 0..63, and the V^T fragments are gathered from LDS in the same order
 // with the byte-transposing read (ds_read_b64_tr_b8) from the row-major V tile.
 // Row statistics are per lane (a lane owns one query) plus one exchange with lane ^ 32.
+//
+// Pipeline.  K and V blocks stream from global memory straight into a 4-stage LDS ring
+// (buffer_load ... lds), two blocks in flight.  The scores of block j+1 are issued to the matrix
+// core before the softmax of block j runs on the vector ALU, so the two overlap inside a wave; two
+// workgroups per CU (two waves per SIMD) overlap the rest.  The softmax costs about 4 vector
+// instructions per score (max3, fma, exp2, add, half a convert): with FP8 the kernel is bound by
+// the vector ALU, not by the matrix core.
 #include "common.h"
 #include "launch.h"
 
@@ -26,10 +33,10 @@ constexpr int kThreads = 256;
 constexpr int BQ = 128;        // queries per workgroup
 constexpr int BKV = 64;        // keys per step
 constexpr int HD = 128;        // head dimension
-constexpr int K_BYTES = BKV * HD;            // K tile, 16-byte chunks swizzled by (row & 7)
-constexpr int V_STRIDE = HD + 16;            // V tile row stride (padding spreads the transposing reads over banks)
-constexpr int V_BYTES = BKV * V_STRIDE;
-constexpr int STAGE = K_BYTES + V_BYTES;
+constexpr int TILE_BYTES = BKV * HD;         // 8 KB: one K or V block, 16-byte chunks swizzled (see below)
+constexpr int STAGE = 2 * TILE_BYTES;        // K then V
+constexpr int NSTAGE = 4;
+constexpr uint32_t OOB = 0x80000000u;
 
 typedef __attribute__((address_space(3))) v2i* lds_v2i_ptr;
 
@@ -43,16 +50,37 @@ struct FwdArgs {
 
 FOG_DEVICE float lane_xor32(float v) { return __shfl_xor(v, 32, 64); }
 
+// LDS chunk swizzles (16-byte chunks inside a 128-byte row), applied by choosing which global chunk
+// a lane of the direct load fetches.  K rows are read 32 consecutive rows at a time (same chunk):
+// key (row & 7).  V rows are read by the transposing read 8 rows {r..r+3, r+8..r+11} at a time:
+// key (row & 3) | ((row >> 3) & 1) << 2.
+FOG_DEVICE int swz_k(int row) { return row & 7; }
+FOG_DEVICE int swz_v(int row) { return (row & 3) | (((row >> 3) & 1) << 2); }
+
+FOG_DEVICE void load_to_lds(v4i rsrc, uint32_t voff, uint32_t lds_addr_uniform) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
+               :
+               : "v"(voff), "s"(rsrc), "s"(lds_addr_uniform)
+               : "memory", "m0");
+}
+FOG_DEVICE v4i make_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t b = reinterpret_cast<uint64_t>(base);
+  v4i r;
+  r[0] = (int)(uint32_t)b;
+  r[1] = (int)((uint32_t)(b >> 32) & 0xFFFFu);
+  r[2] = (int)bytes;
+  r[3] = 0x00020000;
+  return r;
+}
+
 template <bool CAUSAL>
-__global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdArgs a) {
-  __shared__ __attribute__((aligned(16))) uint8_t smem[2 * STAGE];
+__global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
+  __shared__ __attribute__((aligned(1024))) uint8_t smem[NSTAGE * STAGE];
   const int bh = blockIdx.x % a.BH;
   const int qb = a.nqb - 1 - blockIdx.x / a.BH;   // long rows (late query blocks) are launched first
   const int t = threadIdx.x, w = t >> 6, l = t & 63, g = l >> 5;
   const int S = a.S;
   const uint8_t* Qh = a.Q + (int64_t)bh * S * HD;
-  const uint8_t* Kh = a.K + (int64_t)bh * S * HD;
-  const uint8_t* Vh = a.V + (int64_t)bh * S * HD;
 
   const int q0 = qb * BQ + 32 * w;           // first query of this wave
   const int q = q0 + (l & 31);
@@ -74,9 +102,52 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdArgs a) {
   const float lg_rho_p = __log2f(rho_p);
   const float c = a.softmax_scale * 1.44269504088896340736f * (*a.sinv_q) * (*a.sinv_k);
 
-  // keys needed by the workgroup / by this wave
+  // key blocks needed by the workgroup / by this wave
   const int kv_end_wg = CAUSAL ? min(S, qb * BQ + BQ) : S;
   const int nkb = (kv_end_wg + BKV - 1) / BKV;
+  const int nkb_wave = !wave_on ? 0 : (CAUSAL ? min(nkb, (q0 + 31) / BKV + 1) : nkb);
+
+  // ---- direct loads: 2 pieces of K and 2 of V (1 KB = 8 rows each) per wave and block
+  const uint32_t head_bytes = (uint32_t)S * HD;
+  const v4i rsrc_k = make_rsrc(a.K + (int64_t)bh * S * HD, head_bytes);
+  const v4i rsrc_v = make_rsrc(a.V + (int64_t)bh * S * HD, head_bytes);
+  uint32_t off_k[2], off_v[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int row = 8 * (2 * w + j) + (l >> 3), cpos = l & 7;
+    off_k[j] = (uint32_t)(row * HD + ((cpos ^ swz_k(row)) << 4));
+    off_v[j] = (uint32_t)(row * HD + ((cpos ^ swz_v(row)) << 4));
+  }
+  const uint32_t lds_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(uintptr_t)smem + 2048u * w));
+  auto issue = [&](int kb) {   // block kb -> stage kb % 4; blocks past the end fetch zeros (keeps the wait counts uniform)
+    const uint32_t adv = kb < nkb ? (uint32_t)kb * (BKV * HD) : OOB;
+    const uint32_t base = lds_w + (uint32_t)(kb & (NSTAGE - 1)) * STAGE;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      load_to_lds(rsrc_k, off_k[j] + adv, base + 1024u * j);
+      load_to_lds(rsrc_v, off_v[j] + adv, base + TILE_BYTES + 1024u * j);
+    }
+  };
+
+  // ---- fragment addresses (bytes inside a K / V tile), computed once
+  // K (A operand of S^T): row 32 kt + (l & 31), chunks 4 h + 2 g, + 1
+  uint32_t ka[2][2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int row = l & 31;   // + 32 kt: swizzle key unchanged
+    ka[h][0] = (uint32_t)(row * HD + (((4 * h + 2 * g) ^ swz_k(row)) << 4));
+    ka[h][1] = (uint32_t)(row * HD + (((4 * h + 2 * g + 1) ^ swz_k(row)) << 4));
+  }
+  // V^T (A operand of O^T += V^T P^T): lane p of a 16-lane block addresses row 16 r + vrow (r = read
+  // number) and the 8-byte column group (p & 1) of chunk 2 d + ((l & 16) >> 4) of head-dim tile d.
+  uint32_t va[4];
+  {
+    const int i16 = l & 15, jj = i16 >> 1;
+    const int vrow = 8 * (jj >> 2) + 4 * g + (jj & 3);   // + 16 r per read: leaves the swizzle key unchanged
+    const int cbase = (l & 16) >> 4;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) va[d] = (uint32_t)(vrow * HD + (((2 * d + cbase) ^ swz_v(vrow)) << 4) + 8 * (i16 & 1));
+  }
 
   v16f o[4];
 #pragma unroll
@@ -87,75 +158,57 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdArgs a) {
   float l_run = 0.0f;         // this lane's share of sum_j rho_p p_ij
   float raw_max = -INFINITY;  // this lane's share of max_j (Q K^T)_ij, before scaling
 
-  // global -> LDS staging: 2 chunks of K and 2 of V per thread and step
-  uint4 rk[2], rv[2];
-  auto gload = [&](int kb) {
+  auto scores = [&](int kb, v16f* st) {   // st[kt][r] = sum_d K[key][d] Q[q][d], key = 64 kb + 32 kt + 8 (r/4) + 4 g + (r%4)
+    const uint8_t* sk = smem + (kb & (NSTAGE - 1)) * STAGE;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int ch = t + kThreads * i, row = ch >> 3, cc = ch & 7;
-      const int64_t off = (int64_t)(kb * BKV + row) * HD + cc * 16;
-      rk[i] = *reinterpret_cast<const uint4*>(Kh + off);
-      rv[i] = *reinterpret_cast<const uint4*>(Vh + off);
-    }
-  };
-  auto swrite = [&](int stage) {
-    uint8_t* sk = smem + stage * STAGE;
-    uint8_t* sv = sk + K_BYTES;
+    for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int ch = t + kThreads * i, row = ch >> 3, cc = ch & 7;
-      *reinterpret_cast<uint4*>(sk + row * HD + ((cc ^ (row & 7)) << 4)) = rk[i];
-      *reinterpret_cast<uint4*>(sv + row * V_STRIDE + cc * 16) = rv[i];
-    }
-  };
-
-  gload(0);
-  swrite(0);
-  __syncthreads();
-
-  for (int kb = 0; kb < nkb; ++kb) {
-    const int cur = kb & 1;
-    if (kb + 1 < nkb) gload(kb + 1);
-    const uint8_t* sk = smem + cur * STAGE;
-    const uint8_t* sv = sk + K_BYTES;
-    const int key0 = kb * BKV;
-    const bool need = wave_on && (!CAUSAL || key0 <= q0 + 31);
-    if (need) {
-      // ---- S^T tiles: st[kt][r] = sum_d K[key][d] Q[q][d], key = key0 + 32 kt + 8 (r/4) + 4 g + (r%4)
-      v16f st[2];
+      for (int r = 0; r < 16; ++r) st[kt][r] = 0.0f;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) st[kt][r] = 0.0f;
-        const int row = 32 * kt + (l & 31);
-        const uint8_t* pr = sk + row * HD;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const int chunk = 4 * h + 2 * g;
-          v4i lo = *reinterpret_cast<const v4i*>(pr + ((chunk ^ (row & 7)) << 4));
-          v4i hi = *reinterpret_cast<const v4i*>(pr + (((chunk + 1) ^ (row & 7)) << 4));
-          v8i kf;
-          kf[0] = lo[0]; kf[1] = lo[1]; kf[2] = lo[2]; kf[3] = lo[3];
-          kf[4] = hi[0]; kf[5] = hi[1]; kf[6] = hi[2]; kf[7] = hi[3];
-          st[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf, qf[h], st[kt], 0, 0, 0, 0, 0, 0);
-        }
+      for (int h = 0; h < 2; ++h) {
+        v4i lo = *reinterpret_cast<const v4i*>(sk + ka[h][0] + 4096 * kt);
+        v4i hi = *reinterpret_cast<const v4i*>(sk + ka[h][1] + 4096 * kt);
+        v8i kf;
+        kf[0] = lo[0]; kf[1] = lo[1]; kf[2] = lo[2]; kf[3] = lo[3];
+        kf[4] = hi[0]; kf[5] = hi[1]; kf[6] = hi[2]; kf[7] = hi[3];
+        st[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf, qf[h], st[kt], 0, 0, 0, 0, 0, 0);
       }
-      // ---- causal mask on blocks that reach past the wave's first query
-      if (CAUSAL && key0 + BKV - 1 > q0) {
+    }
+  };
+
+  issue(0);
+  issue(1);
+  issue(2);
+  __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt = 8: block 0 has landed (4 direct loads per thread and block)
+  __syncthreads();
+  v16f sc[2], sn[2];
+  if (nkb_wave > 0) scores(0, sc);
+
+  // One key block: SC holds this block's scores, SN receives the next block's.
+  auto block = [&](int kb, v16f* sc, v16f* sn) {
+    // block kb + 1 landed (blocks kb + 2 may be in flight: vmcnt = 4), own LDS reads done (lgkmcnt = 0)
+    __builtin_amdgcn_s_waitcnt(0x0074);
+    __syncthreads();
+    issue(kb + 3);   // into the stage of block kb - 1, which every wave finished reading before the barrier
+    const bool cur = kb < nkb_wave, nxt = kb + 1 < nkb_wave;
+    if (nxt) scores(kb + 1, sn);       // matrix core works on the next block's scores ...
+    if (cur) {                         // ... while the vector ALU does this block's softmax
+      const int key0 = kb * BKV;
+      if (CAUSAL && key0 + BKV - 1 > q0) {   // causal mask on blocks that reach past the wave's first query
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int key = key0 + 32 * kt + 8 * (r >> 2) + 4 * g + (r & 3);
-            if (key > q) st[kt][r] = -INFINITY;
+            if (key > q) sc[kt][r] = -INFINITY;
           }
       }
-      // ---- running integer reference
-      float bm = st[0][0];
+      float bm = fmaxf(fmaxf(sc[0][0], sc[0][1]), sc[1][0]);
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+      for (int r = 2; r < 16; r += 2) bm = fmaxf(fmaxf(bm, sc[0][r]), sc[0][r + 1]);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) bm = fmaxf(bm, st[kt][r]);
+      for (int r = 1; r < 15; r += 2) bm = fmaxf(fmaxf(bm, sc[1][r]), sc[1][r + 1]);
+      bm = fmaxf(bm, sc[1][15]);
       raw_max = fmaxf(raw_max, bm);
       bm = fmaxf(bm, lane_xor32(bm));
       const float m_new = fmaxf(m_run, ceilf(bm * c));
@@ -168,42 +221,45 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdArgs a) {
           for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
         m_run = m_new;
       }
-      // ---- t = rho_p 2^(x - m), summed in binary32 and cast to E4M3; 32 codes per lane = one B operand
+      // t = rho_p 2^(x - m) <= rho_p (1 + eps): summed in binary32 and cast to E4M3 (no clamp needed
+      // below the format's overflow threshold); 32 codes per lane = one B operand.
       const float shift = lg_rho_p - m_run;
       v8i pf;
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
-          float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][4 * qd + 0], c, shift));
-          float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][4 * qd + 1], c, shift));
-          float e2 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][4 * qd + 2], c, shift));
-          float e3 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][4 * qd + 3], c, shift));
+          const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 0], c, shift));
+          const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 1], c, shift));
+          const float e2 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 2], c, shift));
+          const float e3 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 3], c, shift));
           l_run += (e0 + e1) + (e2 + e3);
-          pf[4 * kt + qd] = (int)cvt4_fp8<FOG_E4M3>(e0, e1, e2, e3);
+          uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(e0, e1, 0u, false);
+          pk = __builtin_amdgcn_cvt_pk_fp8_f32(e2, e3, pk, true);
+          pf[4 * kt + qd] = (int)pk;
         }
       }
-      // ---- O^T += V^T P^T.  Byte 4 qd' + b of dword (4 kt + qd') of pf is key
-      //      key0 + 32 kt + 8 qd' + 4 g + b; the V^T fragment lists its 32 keys in the same order.
-      const int i16 = l & 15;
-      const int jj = i16 >> 1;                         // row this lane addresses inside a transposing read
-      const int vrow = 8 * (jj >> 2) + 4 * g + (jj & 3);
-      const int vcol = (l & 16) + 8 * (i16 & 1);
+      // O^T += V^T P^T.  Byte 4 qd' + b of dword (4 kt + qd') of pf is key key0 + 32 kt + 8 qd' + 4 g + b;
+      // the V^T fragment lists its 32 keys in the same order (read r covers rows 16 r + vrow).
+      const uint8_t* sv = smem + (kb & (NSTAGE - 1)) * STAGE + TILE_BYTES;
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
         v8i vf;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          v2i v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(sv + (16 * r + vrow) * V_STRIDE + 32 * d + vcol));
+          v2i v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(sv + va[d] + 16 * r * HD));
           vf[2 * r] = v[0];
           vf[2 * r + 1] = v[1];
         }
         o[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vf, pf, o[d], 0, 0, 0, 0, 0, 0);
       }
     }
-    if (kb + 1 < nkb) swrite(cur ^ 1);
-    __syncthreads();
+  };
+  for (int kb = 0; kb < nkb; kb += 2) {   // two blocks per trip so that the score registers just swap roles
+    block(kb, sc, sn);
+    if (kb + 1 < nkb) block(kb + 1, sn, sc);
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
 
   if (!wave_on) return;
   // ---- epilogue: O = sinv_v O^T / (rho_p l);  lse = m + log2 l  (l_run holds rho_p l, split over two lanes)
@@ -248,6 +304,7 @@ extern "C" fog_status fog_fp8_attn_fwd(int B, int H, int S, int D, float softmax
   if (B == 0 || H == 0 || S == 0) return fog_launch_status();
   if (!Q || !K || !V || !sinv_q || !sinv_k || !sinv_v || !scale_p || !O_bf16 || !lse) return FOG_ERR_NULL;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O_bf16)) return FOG_ERR_ALIGN;
+  if ((int64_t)S * HD >= 0x7FFFFFFF) return FOG_ERR_UNSUPPORTED;
   if ((int64_t)B * H > 0x7FFFFF || (int64_t)B * H * ((S + BQ - 1) / BQ) > 0x7FFFFFF0) return FOG_ERR_UNSUPPORTED;
   FwdArgs a;
   a.Q = Q; a.K = K; a.V = V;
