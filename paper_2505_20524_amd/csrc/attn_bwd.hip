@@ -24,9 +24,10 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int HD = 128;
 constexpr int BLK = 128;           // rows owned by a workgroup (keys in kernel 1, queries in kernel 2)
-constexpr int STEP = 64;           // rows of the streamed operand per step
-constexpr int TS = HD + 16;        // LDS tile row stride: conflict-free for 16-byte row reads and transposing reads
-constexpr int TILE = STEP * TS;
+constexpr int STEP = 64;           // rows of the streamed operands per step
+constexpr int TILE = STEP * HD;    // 8 KB, 16-byte chunks swizzled by swz(row)
+constexpr int NSTAGE = 4;
+constexpr uint32_t OOB = 0x80000000u;
 
 typedef __attribute__((address_space(3))) v2i* lds_v2i_ptr;
 
@@ -41,19 +42,78 @@ struct BwdArgs {
   int BH, S, nblk;
 };
 
-FOG_DEVICE float lane_xor32(float v) { return __shfl_xor(v, 32, 64); }
+// LDS tiles are [64 rows][128 bytes]; the 16-byte chunks of a row sit at position chunk ^ swz(row).
+// The key is a Gray code of the row: it is injective on any 8 (and, per row parity, 16) consecutive
+// rows (16-byte row reads of 32 consecutive rows) and on the row sets {r..r+3, r+8..r+11} that one
+// byte-transposing read touches, so both kinds of fragment read are bank-conflict free.
+FOG_DEVICE int swz(int row) { return (row ^ (row >> 1)) & 7; }
 
-// 32 rows x 64 contraction bytes from a row-major [rows][TS] tile: lane (row l&31, half l>>5).
-FOG_DEVICE v8i frag_rows(const uint8_t* tile, int row_base, int h) {
-  const int l = threadIdx.x & 63;
-  const uint8_t* p = tile + (row_base + (l & 31)) * TS + 64 * h + 32 * (l >> 5);
-  v4i lo = *reinterpret_cast<const v4i*>(p), hi = *reinterpret_cast<const v4i*>(p + 16);
-  v8i f;
-  f[0] = lo[0]; f[1] = lo[1]; f[2] = lo[2]; f[3] = lo[3];
-  f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3];
+FOG_DEVICE void load16_to_lds(v4i rsrc, uint32_t voff, uint32_t lds_addr_uniform) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
+               :
+               : "v"(voff), "s"(rsrc), "s"(__builtin_amdgcn_readfirstlane((int)lds_addr_uniform))
+               : "memory", "m0");
+}
+FOG_DEVICE void load4_to_lds(v4i rsrc, uint32_t voff, uint32_t lds_addr_uniform) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dword %0, %1, 0 offen lds"
+               :
+               : "v"(voff), "s"(rsrc), "s"(__builtin_amdgcn_readfirstlane((int)lds_addr_uniform))
+               : "memory", "m0");
+}
+FOG_DEVICE v4i make_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t b = reinterpret_cast<uint64_t>(base);
+  v4i r;
+  r[0] = (int)(uint32_t)b;
+  r[1] = (int)((uint32_t)(b >> 32) & 0xFFFFu);
+  r[2] = (int)bytes;
+  r[3] = 0x00020000;
+  return r;
+}
+
+// Per-lane byte offsets inside a tile, computed once per kernel.
+struct RowFrag { uint32_t a[2][2]; };   // [h][chunk]: row (l & 31) (+ 32 per row tile: + 4096 bytes), chunks 4 h + 2 g, + 1
+struct ColFrag { uint32_t a[4]; };      // [d]: transposing read 0 of head-dim tile d (+ 16 rows = 2048 bytes per read)
+FOG_DEVICE RowFrag rowfrag_addr() {
+  const int l = threadIdx.x & 63, g = l >> 5, row = l & 31;
+  RowFrag f;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    f.a[h][0] = (uint32_t)(row * HD + (((4 * h + 2 * g) ^ swz(row)) << 4));
+    f.a[h][1] = (uint32_t)(row * HD + (((4 * h + 2 * g + 1) ^ swz(row)) << 4));
+  }
   return f;
 }
-// Same fragment straight from global memory (row-major, stride HD).
+// Lane p of a 16-lane block addresses row 16 r + vrow (r = read number) and the 8-byte half (p & 1)
+// of chunk 2 d + ((l & 16) >> 4); lane i of the block then receives column 32 d + (l & 16) + i of the
+// rows 16 r + 8 (jj / 4) + 4 g + (jj % 4), jj = 0..7: the order in which the packed score bytes list them.
+FOG_DEVICE ColFrag colfrag_addr() {
+  const int l = threadIdx.x & 63, g = l >> 5, i16 = l & 15, jj = i16 >> 1;
+  const int vrow = 8 * (jj >> 2) + 4 * g + (jj & 3);
+  const int cbase = (l & 16) >> 4;
+  ColFrag f;
+#pragma unroll
+  for (int d = 0; d < 4; ++d) f.a[d] = (uint32_t)(vrow * HD + (((2 * d + cbase) ^ swz(vrow)) << 4) + 8 * (i16 & 1));
+  return f;
+}
+FOG_DEVICE v8i read_rowfrag(const uint8_t* tile, const RowFrag& f, int rt, int h) {
+  v4i lo = *reinterpret_cast<const v4i*>(tile + f.a[h][0] + 4096 * rt);
+  v4i hi = *reinterpret_cast<const v4i*>(tile + f.a[h][1] + 4096 * rt);
+  v8i r;
+  r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+  r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+  return r;
+}
+FOG_DEVICE v8i read_colfrag(const uint8_t* tile, const ColFrag& f, int d) {
+  v8i r;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    v2i v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(tile + f.a[d] + 2048 * k));
+    r[2 * k] = v[0];
+    r[2 * k + 1] = v[1];
+  }
+  return r;
+}
+// Fragment of rows straight from global memory (row-major, stride HD): row, contraction bytes 64 h + 32 g.
 FOG_DEVICE v8i frag_global(const uint8_t* base, int64_t row, int h) {
   const int l = threadIdx.x & 63;
   const uint8_t* p = base + row * HD + 64 * h + 32 * (l >> 5);
@@ -63,21 +123,17 @@ FOG_DEVICE v8i frag_global(const uint8_t* base, int64_t row, int h) {
   f[4] = hi.x; f[5] = hi.y; f[6] = hi.z; f[7] = hi.w;
   return f;
 }
-// Transposed fragment: 32 columns [col_base, +32) x the tile's 64 rows as contraction index, rows
-// listed in the order the packed score bytes use: byte 16 t + r  <->  row 32 t + 8 (r/4) + 4 g + (r%4).
-FOG_DEVICE v8i frag_cols(const uint8_t* tile, int col_base) {
-  const int l = threadIdx.x & 63;
-  const int g = l >> 5, i16 = l & 15, jj = i16 >> 1;
-  const uint8_t* p = tile + (8 * (jj >> 2) + 4 * g + (jj & 3)) * TS + col_base + (l & 16) + 8 * (i16 & 1);
-  v8i f;
+// Direct-load offsets of a [64][128] tile: 2 pieces of 1 KB (8 rows) per wave; lane -> (row, global chunk).
+FOG_DEVICE void tile_load_offsets(uint32_t* off) {
+  const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    v2i v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(p + 16 * r * TS));
-    f[2 * r] = v[0];
-    f[2 * r + 1] = v[1];
+  for (int j = 0; j < 2; ++j) {
+    const int row = 8 * (2 * w + j) + (l >> 3), cpos = l & 7;
+    off[j] = (uint32_t)(row * HD + ((cpos ^ swz(row)) << 4));
   }
-  return f;
 }
+
+FOG_DEVICE float lane_xor32(float v) { return __shfl_xor(v, 32, 64); }
 
 // ------------------------------------------------------------------ kernel 0: D_i = sum_d dO_id O_id
 __global__ __launch_bounds__(kThreads) void attn_bwd_rowdot_kernel(const uint16_t* __restrict__ O, const uint16_t* __restrict__ dO,
@@ -97,17 +153,16 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_rowdot_kernel(const uint16_
 }
 
 // ------------------------------------------------------------------ kernel 1: dK, dV
+// Ring stage: Q tile, dO tile, then 64 lse and 64 D values.  Five direct loads per thread and stage.
+constexpr int KV_STAGE = 2 * TILE + 512;
 template <bool CAUSAL>
 __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
-  __shared__ __attribute__((aligned(16))) uint8_t smem[2 * 2 * TILE];     // {Q, dO} x 2 stages
-  __shared__ __attribute__((aligned(16))) float srow[2][2][STEP];         // {lse, D} x 2 stages
+  __shared__ __attribute__((aligned(1024))) uint8_t smem[NSTAGE * KV_STAGE];
   const int bh = blockIdx.x % a.BH;
   const int kblk = blockIdx.x / a.BH;                  // early key blocks see the most queries: launched first
   const int t = threadIdx.x, w = t >> 6, l = t & 63, g = l >> 5;
   const int S = a.S;
   const int64_t hoff = (int64_t)bh * S;
-  const uint8_t* Qh = a.Q + hoff * HD;
-  const uint8_t* dOh = a.dO8 + hoff * HD;
   const int key0 = kblk * BLK + 32 * w;
   const int key = key0 + (l & 31);
   const bool wave_on = key0 < S;
@@ -121,7 +176,6 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
   const float rho_p = *a.scale_p, rho_ds = *a.scale_ds;
   const float c = a.softmax_scale * 1.44269504088896340736f * (*a.sinv_q) * (*a.sinv_k);
   const float cdp = (*a.sinv_do) * (*a.sinv_v);
-  const float lg_rho_p = __log2f(rho_p);
 
   v16f dv[4], dk[4];
 #pragma unroll
@@ -130,60 +184,67 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
     for (int r = 0; r < 16; ++r) { dv[d][r] = 0.0f; dk[d][r] = 0.0f; }
 
   const int qb_first = CAUSAL ? (kblk * BLK) / STEP : 0;
-  const int qb_last = S / STEP;                        // exclusive
+  const int nqb = S / STEP - qb_first;                 // query blocks this workgroup walks
+  // first block (relative) this wave needs: blocks whose last query is below the wave's first key are skipped
+  const int skip = !wave_on ? nqb : (CAUSAL ? max(0, key0 / STEP - qb_first) : 0);
 
-  uint4 rq[2], rdo[2];
-  float rl = 0.0f;
-  auto gload = [&](int qb) {
+  const uint32_t head_bytes = (uint32_t)S * HD;
+  const v4i rsrc_q = make_rsrc(a.Q + hoff * HD, head_bytes), rsrc_do = make_rsrc(a.dO8 + hoff * HD, head_bytes);
+  const v4i rsrc_lse = make_rsrc(a.lse + hoff, (uint32_t)S * 4), rsrc_d = make_rsrc(a.Dws + hoff, (uint32_t)S * 4);
+  uint32_t off[2];
+  tile_load_offsets(off);
+  const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)smem);
+  const uint32_t lds_w = lds0 + 2048u * (uint32_t)__builtin_amdgcn_readfirstlane(w);
+  const bool rows_d = __builtin_amdgcn_readfirstlane(w) & 1;   // odd waves fetch D, even waves lse (two copies each: identical bytes)
+  auto issue = [&](int i) {   // relative block i -> stage i % 4; blocks past the end fetch zeros
+    const uint32_t adv = i < nqb ? (uint32_t)(qb_first + i) * (STEP * HD) : OOB;
+    const uint32_t radv = i < nqb ? (uint32_t)(qb_first + i) * (STEP * 4) : OOB;
+    const uint32_t base = (uint32_t)(i & (NSTAGE - 1)) * KV_STAGE;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {  // 64 rows x 8 chunks = 2 per thread
-      const int ch = t + kThreads * i, row = ch >> 3, cc = ch & 7;
-      const int64_t off = (int64_t)(qb * STEP + row) * HD + cc * 16;
-      rq[i] = *reinterpret_cast<const uint4*>(Qh + off);
-      rdo[i] = *reinterpret_cast<const uint4*>(dOh + off);
+    for (int j = 0; j < 2; ++j) {
+      load16_to_lds(rsrc_q, off[j] + adv, lds_w + base + 1024u * j);
+      load16_to_lds(rsrc_do, off[j] + adv, lds_w + base + TILE + 1024u * j);
     }
-    if (t < 2 * STEP) rl = t < STEP ? a.lse[hoff + qb * STEP + t] : a.Dws[hoff + qb * STEP + (t - STEP)];
+    load4_to_lds(rows_d ? rsrc_d : rsrc_lse, (uint32_t)(4 * l) + radv, lds0 + base + 2 * TILE + (rows_d ? 256u : 0u));
   };
-  auto swrite = [&](int stage) {
-    uint8_t* sq = smem + stage * 2 * TILE;
-    uint8_t* sdo = sq + TILE;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {  // 64 rows x 8 chunks = 2 per thread
-      const int ch = t + kThreads * i, row = ch >> 3, cc = ch & 7;
-      *reinterpret_cast<uint4*>(sq + row * TS + cc * 16) = rq[i];
-      *reinterpret_cast<uint4*>(sdo + row * TS + cc * 16) = rdo[i];
-    }
-    if (t < 2 * STEP) srow[stage][t >= STEP][t & (STEP - 1)] = rl;
-  };
+  const RowFrag rf = rowfrag_addr();
+  const ColFrag cf = colfrag_addr();
 
-  if (qb_first < qb_last) {
-    gload(qb_first);
-    swrite(0);
-  }
-  __syncthreads();
-
-  for (int qb = qb_first; qb < qb_last; ++qb) {
-    const int cur = (qb - qb_first) & 1;
-    if (qb + 1 < qb_last) gload(qb + 1);
-    const uint8_t* sq = smem + cur * 2 * TILE;
+  // S and dP tiles with lane = key: element r of tile qt is query qbase + 32 qt + 8 (r/4) + 4 g + (r%4)
+  auto scores = [&](int i, v16f* st, v16f* dp) {
+    const uint8_t* sq = smem + (i & (NSTAGE - 1)) * KV_STAGE;
     const uint8_t* sdo = sq + TILE;
-    const int qbase = qb * STEP;
-    const bool need = wave_on && (!CAUSAL || qbase + STEP - 1 >= key0);
-    if (need) {
-      // S and dP tiles with lane = key: element r of tile qt is query qbase + 32 qt + 8 (r/4) + 4 g + (r%4)
-      v16f st[2], dp[2];
 #pragma unroll
-      for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < 2; ++qt) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { st[qt][r] = 0.0f; dp[qt][r] = 0.0f; }
+      for (int r = 0; r < 16; ++r) { st[qt][r] = 0.0f; dp[qt][r] = 0.0f; }
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          v8i qfr = frag_rows(sq, 32 * qt, h);
-          st[qt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qfr, kf[h], st[qt], 0, 0, 0, 0, 0, 0);
-          v8i dof = frag_rows(sdo, 32 * qt, h);
-          dp[qt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(dof, vf[h], dp[qt], 1, 0, 0, 0, 0, 0);
-        }
+      for (int h = 0; h < 2; ++h) {
+        st[qt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_rowfrag(sq, rf, qt, h), kf[h], st[qt], 0, 0, 0, 0, 0, 0);
+        dp[qt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_rowfrag(sdo, rf, qt, h), vf[h], dp[qt], 1, 0, 0, 0, 0, 0);
       }
+    }
+  };
+
+  issue(0);
+  issue(1);
+  issue(2);
+  __builtin_amdgcn_s_waitcnt(0x0F7A);  // vmcnt = 10: block 0 has landed (5 direct loads per thread and block)
+  __syncthreads();
+  v16f sa[2], da[2], sb[2], db[2];
+  if (skip == 0 && nqb > 0) scores(0, sa, da);
+
+  auto block = [&](int i, v16f* st, v16f* dp, v16f* stn, v16f* dpn) {
+    __builtin_amdgcn_s_waitcnt(0x0075);  // vmcnt = 5: block i + 1 landed; lgkmcnt = 0: own LDS reads done
+    __syncthreads();
+    issue(i + 3);
+    const bool cur = i >= skip, nxt = i + 1 >= skip && i + 1 < nqb;
+    if (nxt) scores(i + 1, stn, dpn);
+    if (cur) {
+      const uint8_t* sq = smem + (i & (NSTAGE - 1)) * KV_STAGE;
+      const uint8_t* sdo = sq + TILE;
+      const float* srow = reinterpret_cast<const float*>(sq + 2 * TILE);   // [0..63] lse, [64..127] D
+      const int qbase = (qb_first + i) * STEP;
       const bool mask = CAUSAL && qbase < key0 + 31;
       v8i pf, dsf;
 #pragma unroll
@@ -191,16 +252,15 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
           const int qi = 32 * qt + 8 * qd + 4 * g;
-          const float4 ls = *reinterpret_cast<const float4*>(&srow[cur][0][qi]);
-          const float4 dd = *reinterpret_cast<const float4*>(&srow[cur][1][qi]);
+          const float4 ls = *reinterpret_cast<const float4*>(srow + qi);
+          const float4 dd = *reinterpret_cast<const float4*>(srow + 64 + qi);
           const float lsv[4] = {ls.x, ls.y, ls.z, ls.w}, ddv[4] = {dd.x, dd.y, dd.z, dd.w};
-          float p[4], pq[4], ds[4];
+          float pq[4], ds[4];
 #pragma unroll
           for (int b = 0; b < 4; ++b) {
             const int r = 4 * qd + b;
             float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[qt][r], c, -lsv[b]));
             if (mask && (qbase + qi + b) < key) e = 0.0f;
-            p[b] = e;
             pq[b] = e * rho_p;
             ds[b] = (e * __builtin_fmaf(dp[qt][r], cdp, -ddv[b])) * rho_ds;
           }
@@ -211,16 +271,16 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
       // dV^T += dO^T P~ ;  dK^T += Q^T dS~   (contraction over the 64 queries of this step)
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
-        v8i dot = frag_cols(sdo, 32 * d);
-        dv[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(dot, pf, dv[d], 1, 0, 0, 0, 0, 0);
-        v8i qt_ = frag_cols(sq, 32 * d);
-        dk[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qt_, dsf, dk[d], 0, 1, 0, 0, 0, 0);
+        dv[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_colfrag(sdo, cf, d), pf, dv[d], 1, 0, 0, 0, 0, 0);
+        dk[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_colfrag(sq, cf, d), dsf, dk[d], 0, 1, 0, 0, 0, 0);
       }
     }
-    if (qb + 1 < qb_last) swrite(cur ^ 1);
-    __syncthreads();
+  };
+  for (int i = 0; i < nqb; i += 2) {   // two blocks per trip so that the score registers just swap roles
+    block(i, sa, da, sb, db);
+    if (i + 1 < nqb) block(i + 1, sb, db, sa, da);
   }
-  (void)lg_rho_p;
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
   if (!wave_on) return;
   const float sdv = (*a.sinv_do) / rho_p;
   const float sdk = a.softmax_scale * (*a.sinv_q) / rho_ds;
@@ -240,15 +300,13 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
 
 // ------------------------------------------------------------------ kernel 2: dQ (and max |dS|)
 template <bool CAUSAL, bool AMAX>
-__global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(BwdArgs a) {
-  __shared__ __attribute__((aligned(16))) uint8_t smem[2 * 2 * TILE];     // {K, V} x 2 stages
+__global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(BwdArgs a) {
+  __shared__ __attribute__((aligned(1024))) uint8_t smem[NSTAGE * 2 * TILE];     // {K, V} x 4 stages
   const int bh = blockIdx.x % a.BH;
   const int qblk = a.nblk - 1 - blockIdx.x / a.BH;
   const int t = threadIdx.x, w = t >> 6, l = t & 63, g = l >> 5;
   const int S = a.S;
   const int64_t hoff = (int64_t)bh * S;
-  const uint8_t* Kh = a.K + hoff * HD;
-  const uint8_t* Vh = a.V + hoff * HD;
   const int q0 = qblk * BLK + 32 * w;
   const int q = q0 + (l & 31);
   const bool wave_on = q0 < S;
@@ -274,82 +332,78 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(BwdArgs a) {
 
   const int kv_end = CAUSAL ? min(S, qblk * BLK + BLK) : S;
   const int nkb = (kv_end + STEP - 1) / STEP;
+  const int nkb_wave = !wave_on ? 0 : (CAUSAL ? min(nkb, (q0 + 31) / STEP + 1) : nkb);
 
-  uint4 rk[2], rv[2];
-  auto gload = [&](int kb) {
+  const uint32_t head_bytes = (uint32_t)S * HD;
+  const v4i rsrc_k = make_rsrc(a.K + hoff * HD, head_bytes), rsrc_v = make_rsrc(a.V + hoff * HD, head_bytes);
+  uint32_t off[2];
+  tile_load_offsets(off);
+  const uint32_t lds_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(uintptr_t)smem + 2048u * w));
+  auto issue = [&](int kb) {
+    const uint32_t adv = kb < nkb ? (uint32_t)kb * (STEP * HD) : OOB;
+    const uint32_t base = lds_w + (uint32_t)(kb & (NSTAGE - 1)) * (2 * TILE);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {  // 64 rows x 8 chunks = 2 per thread
-      const int ch = t + kThreads * i, row = ch >> 3, cc = ch & 7;
-      const int64_t off = (int64_t)(kb * STEP + row) * HD + cc * 16;
-      rk[i] = *reinterpret_cast<const uint4*>(Kh + off);
-      rv[i] = *reinterpret_cast<const uint4*>(Vh + off);
+    for (int j = 0; j < 2; ++j) {
+      load16_to_lds(rsrc_k, off[j] + adv, base + 1024u * j);
+      load16_to_lds(rsrc_v, off[j] + adv, base + TILE + 1024u * j);
     }
   };
-  auto swrite = [&](int stage) {
-    uint8_t* sk = smem + stage * 2 * TILE;
-    uint8_t* sv = sk + TILE;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {  // 64 rows x 8 chunks = 2 per thread
-      const int ch = t + kThreads * i, row = ch >> 3, cc = ch & 7;
-      *reinterpret_cast<uint4*>(sk + row * TS + cc * 16) = rk[i];
-      *reinterpret_cast<uint4*>(sv + row * TS + cc * 16) = rv[i];
-    }
-  };
-  gload(0);
-  swrite(0);
+  const RowFrag rf = rowfrag_addr();
+  const ColFrag cf = colfrag_addr();
+
+  issue(0);
+  issue(1);
+  issue(2);
+  __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt = 8: block 0 has landed (4 direct loads per thread and block)
   __syncthreads();
 
   for (int kb = 0; kb < nkb; ++kb) {
-    const int cur = kb & 1;
-    if (kb + 1 < nkb) gload(kb + 1);
-    const uint8_t* sk = smem + cur * 2 * TILE;
+    if (kb > 0) {
+      __builtin_amdgcn_s_waitcnt(0x0078);  // vmcnt = 8: block kb landed (two younger blocks may be in flight); lgkmcnt = 0
+      __syncthreads();
+    }
+    issue(kb + 3);                         // into the stage of block kb - 1
+    if (kb >= nkb_wave) continue;
+    const uint8_t* sk = smem + (kb & (NSTAGE - 1)) * (2 * TILE);
     const uint8_t* sv = sk + TILE;
     const int kbase = kb * STEP;
-    const bool need = wave_on && (!CAUSAL || kbase <= q0 + 31);
-    if (need) {
-      // transposed tiles, lane = query: element r of tile kt is key kbase + 32 kt + 8 (r/4) + 4 g + (r%4)
-      v16f st[2], dp[2];
+    // transposed tiles, lane = query: element r of tile kt is key kbase + 32 kt + 8 (r/4) + 4 g + (r%4)
+    v16f st[2], dp[2];
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
+    for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { st[kt][r] = 0.0f; dp[kt][r] = 0.0f; }
+      for (int r = 0; r < 16; ++r) { st[kt][r] = 0.0f; dp[kt][r] = 0.0f; }
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          v8i kfr = frag_rows(sk, 32 * kt, h);
-          st[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kfr, qf[h], st[kt], 0, 0, 0, 0, 0, 0);
-          v8i vfr = frag_rows(sv, 32 * kt, h);
-          dp[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vfr, dof[h], dp[kt], 0, 1, 0, 0, 0, 0);
-        }
-      }
-      const bool mask = CAUSAL && kbase + STEP - 1 > q0;
-      v8i dsf;
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) {
-          float ds[4];
-#pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            const int r = 4 * qd + b;
-            float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][r], c, -lse));
-            if (mask && (kbase + 32 * kt + 8 * qd + 4 * g + b) > q) e = 0.0f;
-            const float dsv = e * __builtin_fmaf(dp[kt][r], cdp, -Dq);
-            if (AMAX) ds_max = fmaxf(ds_max, fabsf(dsv));
-            ds[b] = dsv * rho_ds;
-          }
-          dsf[4 * kt + qd] = (int)cvt4_fp8<FOG_E5M2>(ds[0], ds[1], ds[2], ds[3]);
-        }
-      }
-      // dQ^T += K^T dS~^T  (contraction over the 64 keys of this step)
-#pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        v8i kt_ = frag_cols(sk, 32 * d);
-        dq[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kt_, dsf, dq[d], 0, 1, 0, 0, 0, 0);
+      for (int h = 0; h < 2; ++h) {
+        st[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_rowfrag(sk, rf, kt, h), qf[h], st[kt], 0, 0, 0, 0, 0, 0);
+        dp[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_rowfrag(sv, rf, kt, h), dof[h], dp[kt], 0, 1, 0, 0, 0, 0);
       }
     }
-    if (kb + 1 < nkb) swrite(cur ^ 1);
-    __syncthreads();
+    const bool mask = CAUSAL && kbase + STEP - 1 > q0;
+    v8i dsf;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        float ds[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const int r = 4 * qd + b;
+          float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][r], c, -lse));
+          if (mask && (kbase + 32 * kt + 8 * qd + 4 * g + b) > q) e = 0.0f;
+          const float dsv = e * __builtin_fmaf(dp[kt][r], cdp, -Dq);
+          if (AMAX) ds_max = fmaxf(ds_max, fabsf(dsv));
+          ds[b] = dsv * rho_ds;
+        }
+        dsf[4 * kt + qd] = (int)cvt4_fp8<FOG_E5M2>(ds[0], ds[1], ds[2], ds[3]);
+      }
+    }
+    // dQ^T += K^T dS~^T  (contraction over the 64 keys of this step)
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+      dq[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_colfrag(sk, cf, d), dsf, dq[d], 0, 1, 0, 0, 0, 0);
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
   if (!wave_on) return;
   const float sdq = a.softmax_scale * (*a.sinv_k) / rho_ds;
   uint16_t* dqrow = a.dQ + (hoff + q) * HD;
@@ -402,6 +456,7 @@ extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int S, int D, float softmax
     return FOG_ERR_ALIGN;
   if (!workspace || workspace_bytes < fog_fp8_attn_workspace(B, H, S, D, 1) || (reinterpret_cast<uintptr_t>(workspace) & 3u))
     return FOG_ERR_WORKSPACE;
+  if ((int64_t)S * HD >= 0x7FFFFFFF) return FOG_ERR_UNSUPPORTED;
   if ((int64_t)B * H > 0x7FFFFF || (int64_t)B * H * ((S + BLK - 1) / BLK) > 0x7FFFFFF0) return FOG_ERR_UNSUPPORTED;
   BwdArgs a;
   a.Q = Q; a.K = K; a.V = V; a.dO8 = dO_e5m2;
