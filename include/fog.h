@@ -159,7 +159,8 @@ fog_status fog_fp8_attn_fwd(int B, int H, int S, int D, float softmax_scale, int
  *   dO_e5m2 : dO cast to E5M2 with reciprocal scale sinv_do;  dO_bf16, O_bf16: the bf16 tensors.
  *   lse : from the forward.  scale_ds : one float (delayed-style: amax_ds of a previous call).
  *   dQ, dK, dV : [B, H, S, D] bfloat16, overwritten.   amax_ds : NULL or one float, max |dS|.
- *   workspace : fog_fp8_attn_workspace(B, H, S, D, 1) bytes (holds D_i).
+ *   workspace : fog_fp8_attn_workspace(B, H, S, D, 1) bytes (three floats per row: D_i and two
+ *               per-row constants with the scales folded in), 4-byte aligned.
  * Same shape rules and errors as the forward; WORKSPACE when the workspace is too small.
  */
 fog_status fog_fp8_attn_bwd(int B, int H, int S, int D, float softmax_scale, int causal,

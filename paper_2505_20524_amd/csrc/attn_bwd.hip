@@ -135,9 +135,15 @@ FOG_DEVICE void tile_load_offsets(uint32_t* off) {
 
 FOG_DEVICE float lane_xor32(float v) { return __shfl_xor(v, 32, 64); }
 
-// ------------------------------------------------------------------ kernel 0: D_i = sum_d dO_id O_id
+// ------------------------------------------------------------------ kernel 0: per-row constants
+// ws[0][row] = D_i = sum_d dO_id O_id                (used by the dQ kernel)
+// ws[1][row] = D_i * rho_ds / rho_p                  (dK/dV kernel: its probabilities carry the factor rho_p)
+// ws[2][row] = lse_i - log2 rho_p                    (dK/dV kernel: 2^(x - that) = rho_p P)
+// Folding the scales into per-row constants once saves three vector instructions per score later.
 __global__ __launch_bounds__(kThreads) void attn_bwd_rowdot_kernel(const uint16_t* __restrict__ O, const uint16_t* __restrict__ dO,
-                                                                   float* __restrict__ Dws, int64_t rows) {
+                                                                   const float* __restrict__ lse, const float* __restrict__ scale_p,
+                                                                   const float* __restrict__ scale_ds, float* __restrict__ ws,
+                                                                   int64_t rows) {
   const int64_t row = (int64_t)blockIdx.x * (kThreads / 16) + (threadIdx.x >> 4);
   const int part = threadIdx.x & 15;
   float s = 0.0f;
@@ -149,7 +155,12 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_rowdot_kernel(const uint16_
   }
 #pragma unroll
   for (int o = 8; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
-  if (row < rows && part == 0) Dws[row] = s;
+  if (row < rows && part == 0) {
+    const float rp = *scale_p, rds = *scale_ds;
+    ws[row] = s;
+    ws[rows + row] = s * (rds / rp);
+    ws[2 * rows + row] = lse[row] - __log2f(rp);
+  }
 }
 
 // ------------------------------------------------------------------ kernel 1: dK, dV
@@ -175,7 +186,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
   }
   const float rho_p = *a.scale_p, rho_ds = *a.scale_ds;
   const float c = a.softmax_scale * 1.44269504088896340736f * (*a.sinv_q) * (*a.sinv_k);
-  const float cdp = (*a.sinv_do) * (*a.sinv_v);
+  const float cdpk = (*a.sinv_do) * (*a.sinv_v) * (rho_ds / rho_p);   // dP scale times rho_ds / rho_p
+  const bool clamp_p = !(rho_p <= 448.0f);   // rho_p P <= rho_p: the cast of P can only overflow for a scale above the format's maximum
 
   v16f dv[4], dk[4];
 #pragma unroll
@@ -190,7 +202,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
 
   const uint32_t head_bytes = (uint32_t)S * HD;
   const v4i rsrc_q = make_rsrc(a.Q + hoff * HD, head_bytes), rsrc_do = make_rsrc(a.dO8 + hoff * HD, head_bytes);
-  const v4i rsrc_lse = make_rsrc(a.lse + hoff, (uint32_t)S * 4), rsrc_d = make_rsrc(a.Dws + hoff, (uint32_t)S * 4);
+  const int64_t nrows = (int64_t)a.BH * S;
+  const v4i rsrc_lse = make_rsrc(a.Dws + 2 * nrows + hoff, (uint32_t)S * 4), rsrc_d = make_rsrc(a.Dws + nrows + hoff, (uint32_t)S * 4);
   uint32_t off[2];
   tile_load_offsets(off);
   const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)smem);
@@ -243,9 +256,15 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
     if (cur) {
       const uint8_t* sq = smem + (i & (NSTAGE - 1)) * KV_STAGE;
       const uint8_t* sdo = sq + TILE;
-      const float* srow = reinterpret_cast<const float*>(sq + 2 * TILE);   // [0..63] lse, [64..127] D
+      const float* srow = reinterpret_cast<const float*>(sq + 2 * TILE);   // [0..63] lse - log2 rho_p, [64..127] D rho_ds / rho_p
       const int qbase = (qb_first + i) * STEP;
-      const bool mask = CAUSAL && qbase < key0 + 31;
+      if (CAUSAL && qbase < key0 + 31) {   // diagonal blocks: queries before the key see nothing of it
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (qbase + 32 * qt + 8 * (r >> 2) + 4 * g + (r & 3) < key) st[qt][r] = -INFINITY;
+      }
       v8i pf, dsf;
 #pragma unroll
       for (int qt = 0; qt < 2; ++qt) {
@@ -259,12 +278,15 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
           for (int b = 0; b < 4; ++b) {
             const int r = 4 * qd + b;
-            float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[qt][r], c, -lsv[b]));
-            if (mask && (qbase + qi + b) < key) e = 0.0f;
-            pq[b] = e * rho_p;
-            ds[b] = (e * __builtin_fmaf(dp[qt][r], cdp, -ddv[b])) * rho_ds;
+            pq[b] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[qt][r], c, -lsv[b]));   // rho_p P
+            ds[b] = pq[b] * __builtin_fmaf(dp[qt][r], cdpk, -ddv[b]);                 // rho_ds dS
           }
-          pf[4 * qt + qd] = (int)cvt4_fp8<FOG_E4M3>(pq[0], pq[1], pq[2], pq[3]);
+          if (clamp_p) {
+            pf[4 * qt + qd] = (int)cvt4_fp8<FOG_E4M3>(pq[0], pq[1], pq[2], pq[3]);
+          } else {
+            uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(pq[0], pq[1], 0u, false);
+            pf[4 * qt + qd] = (int)__builtin_amdgcn_cvt_pk_fp8_f32(pq[2], pq[3], pk, true);
+          }
           dsf[4 * qt + qd] = (int)cvt4_fp8<FOG_E5M2>(ds[0], ds[1], ds[2], ds[3]);
         }
       }
@@ -317,9 +339,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(BwdArgs a) {
     qf[h] = frag_global(a.Q + hoff * HD, wave_on ? q : 0, h);
     dof[h] = frag_global(a.dO8 + hoff * HD, wave_on ? q : 0, h);
   }
-  const float lse = wave_on ? a.lse[hoff + q] : 0.0f;
-  const float Dq = wave_on ? a.Dws[hoff + q] : 0.0f;
   const float rho_ds = *a.scale_ds;
+  const float lse = (wave_on ? a.lse[hoff + q] : 0.0f) - __log2f(rho_ds);   // 2^(x - this) = rho_ds P
+  const float Dq = wave_on ? a.Dws[hoff + q] : 0.0f;
   const float c = a.softmax_scale * 1.44269504088896340736f * (*a.sinv_q) * (*a.sinv_k);
   const float cdp = (*a.sinv_do) * (*a.sinv_v);
 
@@ -379,7 +401,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(BwdArgs a) {
         dp[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_rowfrag(sv, rf, kt, h), dof[h], dp[kt], 0, 1, 0, 0, 0, 0);
       }
     }
-    const bool mask = CAUSAL && kbase + STEP - 1 > q0;
+    if (CAUSAL && kbase + STEP - 1 > q0) {   // diagonal blocks: keys after the query are masked
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (kbase + 32 * kt + 8 * (r >> 2) + 4 * g + (r & 3) > q) st[kt][r] = -INFINITY;
+    }
     v8i dsf;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
@@ -389,11 +417,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(BwdArgs a) {
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
           const int r = 4 * qd + b;
-          float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][r], c, -lse));
-          if (mask && (kbase + 32 * kt + 8 * qd + 4 * g + b) > q) e = 0.0f;
-          const float dsv = e * __builtin_fmaf(dp[kt][r], cdp, -Dq);
-          if (AMAX) ds_max = fmaxf(ds_max, fabsf(dsv));
-          ds[b] = dsv * rho_ds;
+          const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][r], c, -lse));   // rho_ds P
+          ds[b] = e * __builtin_fmaf(dp[kt][r], cdp, -Dq);                                // rho_ds dS
+          if (AMAX) ds_max = fmaxf(ds_max, fabsf(ds[b]));
         }
         dsf[4 * kt + qd] = (int)cvt4_fp8<FOG_E5M2>(ds[0], ds[1], ds[2], ds[3]);
       }
@@ -416,7 +442,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(BwdArgs a) {
                                                           pack_bf16x2(dq[d][4 * qd + 2] * sdq, dq[d][4 * qd + 3] * sdq));
     }
   if (AMAX) {
-    ds_max = wave_max_f32(ds_max);
+    ds_max = wave_max_f32(ds_max) / rho_ds;   // the running maximum was taken on rho_ds dS
     if (l == 0 && ds_max > 0.0f) atomicMax(a.amax_ds, __float_as_uint(ds_max));
   }
 }
@@ -430,7 +456,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 extern "C" size_t fog_fp8_attn_workspace(int B, int H, int S, int D, int is_bwd) {
   (void)D;
   if (!is_bwd || B <= 0 || H <= 0 || S <= 0) return 0;
-  return (size_t)B * H * S * sizeof(float);
+  return (size_t)3 * B * H * S * sizeof(float);
 }
 
 extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int S, int D, float softmax_scale, int causal,
@@ -469,7 +495,7 @@ extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int S, int D, float softmax
   a.BH = B * H; a.S = S; a.nblk = (S + BLK - 1) / BLK;
   if (amax_ds) zero_u32b<<<1, 1, 0, s>>>(a.amax_ds);
   const int64_t rows = (int64_t)a.BH * S;
-  attn_bwd_rowdot_kernel<<<(int)((rows + 15) / 16), kThreads, 0, s>>>(a.O, a.dO, a.Dws, rows);
+  attn_bwd_rowdot_kernel<<<(int)((rows + 15) / 16), kThreads, 0, s>>>(a.O, a.dO, a.lse, a.scale_p, a.scale_ds, a.Dws, rows);
   const int grid = a.BH * a.nblk;
   if (causal) attn_bwd_dkdv_kernel<true><<<grid, kThreads, 0, s>>>(a);
   else        attn_bwd_dkdv_kernel<false><<<grid, kThreads, 0, s>>>(a);

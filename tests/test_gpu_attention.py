@@ -161,7 +161,7 @@ def test_attention_argument_errors():
     b = (1, 1, 64, 128, 0.1, 1, p, p, p, fp, fp, fp, o.data_ptr(), o.data_ptr(), p, fp, l.data_ptr(), fp, fp,
          o.data_ptr(), o.data_ptr(), o.data_ptr(), None)
     assert lib.fog_fp8_attn_bwd(*b, None, 0, st) == 5
-    ws = torch.zeros(64, device="cuda")
+    ws = torch.zeros(3 * 64, device="cuda")
     assert lib.fog_fp8_attn_bwd(*b, ws.data_ptr(), 100, st) == 5
-    assert lib.fog_fp8_attn_bwd(*b, ws.data_ptr(), 256, st) == 0
+    assert lib.fog_fp8_attn_bwd(*b, ws.data_ptr(), 3 * 64 * 4, st) == 0
     torch.cuda.synchronize()
