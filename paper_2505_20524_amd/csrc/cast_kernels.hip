@@ -22,23 +22,24 @@ __global__ __launch_bounds__(kThreads) void amax_kernel(const uint4* __restrict_
                                                         uint32_t* __restrict__ out) {
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  uint32_t m0 = 0, m1 = 0, m2 = 0, m3 = 0;
-  for (; i + 3 * stride < nvec; i += 4 * stride) {
-    uint4 a = ld_nt16(x + i);
-    uint4 b = ld_nt16(x + i + stride);
-    uint4 c = ld_nt16(x + i + 2 * stride);
-    uint4 d = ld_nt16(x + i + 3 * stride);
-    m0 = pkmax_abs_bf16(pkmax_abs_bf16(m0, a.x), a.y); m1 = pkmax_abs_bf16(pkmax_abs_bf16(m1, a.z), a.w);
-    m2 = pkmax_abs_bf16(pkmax_abs_bf16(m2, b.x), b.y); m3 = pkmax_abs_bf16(pkmax_abs_bf16(m3, b.z), b.w);
-    m0 = pkmax_abs_bf16(pkmax_abs_bf16(m0, c.x), c.y); m1 = pkmax_abs_bf16(pkmax_abs_bf16(m1, c.z), c.w);
-    m2 = pkmax_abs_bf16(pkmax_abs_bf16(m2, d.x), d.y); m3 = pkmax_abs_bf16(pkmax_abs_bf16(m3, d.z), d.w);
+  uint32_t m[4] = {0, 0, 0, 0};
+  for (; i + 7 * stride < nvec; i += 8 * stride) {   // eight 16-byte loads in flight per thread
+    uint4 v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = ld_nt16(x + i + k * stride);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      m[0] = pkmax_abs_bf16(m[0], v[k].x); m[1] = pkmax_abs_bf16(m[1], v[k].y);
+      m[2] = pkmax_abs_bf16(m[2], v[k].z); m[3] = pkmax_abs_bf16(m[3], v[k].w);
+    }
   }
   for (; i < nvec; i += stride) {
-    uint4 a = x[i];
-    m0 = pkmax_abs_bf16(pkmax_abs_bf16(m0, a.x), a.y); m1 = pkmax_abs_bf16(pkmax_abs_bf16(m1, a.z), a.w);
+    uint4 a = ld_nt16(x + i);
+    m[0] = pkmax_abs_bf16(m[0], a.x); m[1] = pkmax_abs_bf16(m[1], a.y);
+    m[2] = pkmax_abs_bf16(m[2], a.z); m[3] = pkmax_abs_bf16(m[3], a.w);
   }
-  uint32_t m = pkmax_abs_bf16(pkmax_abs_bf16(m0, m1), pkmax_abs_bf16(m2, m3));
-  uint32_t h = (m >> 16) > (m & 0xFFFFu) ? (m >> 16) : (m & 0xFFFFu);
+  uint32_t mm = pkmax_abs_bf16(pkmax_abs_bf16(m[0], m[1]), pkmax_abs_bf16(m[2], m[3]));
+  uint32_t h = (mm >> 16) > (mm & 0xFFFFu) ? (mm >> 16) : (mm & 0xFFFFu);
   if (blockIdx.x == 0 && (int)threadIdx.x < ntail) {
     uint32_t t = tail[threadIdx.x] & 0x7FFFu;
     h = h > t ? h : t;
@@ -109,7 +110,8 @@ FOG_DEVICE uint2 cast8(uint4 v, float rho) {
   return o;
 }
 
-// Each thread turns 16 bf16 (two 16-byte loads) into 16 FP8 codes (one 16-byte store).
+// Each thread turns 16 bf16 (two 16-byte loads) into 16 FP8 codes (one 16-byte store), two such
+// chunks per trip so that four loads are in flight.
 template <int FMT, bool AMAX>
 __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t* __restrict__ x, int64_t rows,
                                                                  int64_t chunks_per_row, int64_t ldx,
@@ -119,23 +121,48 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t*
   const int64_t total = rows * chunks_per_row;
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   uint32_t m = 0;
-  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
-    int64_t r = i / chunks_per_row, c = i - r * chunks_per_row;
-    const uint4* src = reinterpret_cast<const uint4*>(x + r * ldx + c * 16);
-    uint4 a = ld_nt16(src);
-    uint4 b = ld_nt16(src + 1);
+  auto src_of = [&](int64_t i) {
+    if (rows == 1) return x + i * 16;
+    const int64_t r = i / chunks_per_row, c = i - r * chunks_per_row;
+    return x + r * ldx + c * 16;
+  };
+  auto dst_of = [&](int64_t i) {
+    if (rows == 1) return q + i * 16;
+    const int64_t r = i / chunks_per_row, c = i - r * chunks_per_row;
+    return q + r * ldq + c * 16;
+  };
+  auto emit = [&](uint4 a, uint4 b, uint8_t* dst) {
     if (AMAX) {
       m = pkmax_abs_bf16(pkmax_abs_bf16(pkmax_abs_bf16(pkmax_abs_bf16(m, a.x), a.y), a.z), a.w);
       m = pkmax_abs_bf16(pkmax_abs_bf16(pkmax_abs_bf16(pkmax_abs_bf16(m, b.x), b.y), b.z), b.w);
     }
     uint2 lo = cast8<FMT>(a, rho), hi = cast8<FMT>(b, rho);
-    uint4 o = make_uint4(lo.x, lo.y, hi.x, hi.y);
-    st_nt16(q + r * ldq + c * 16, o);
+    st_nt16(dst, make_uint4(lo.x, lo.y, hi.x, hi.y));
+  };
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  for (; i + stride < total; i += 2 * stride) {
+    const uint16_t* s0 = src_of(i);
+    const uint16_t* s1 = src_of(i + stride);
+    uint4 a0 = ld_nt16(s0), b0 = ld_nt16(s0 + 8), a1 = ld_nt16(s1), b1 = ld_nt16(s1 + 8);
+    emit(a0, b0, dst_of(i));
+    emit(a1, b1, dst_of(i + stride));
+  }
+  if (i < total) {
+    const uint16_t* s0 = src_of(i);
+    emit(ld_nt16(s0), ld_nt16(s0 + 8), dst_of(i));
   }
   if (AMAX) {
     uint32_t h = (m >> 16) > (m & 0xFFFFu) ? (m >> 16) : (m & 0xFFFFu);
     h = wave_max_u32(h);
-    if ((threadIdx.x & 63) == 0 && h) atomicMax(amax_out, h << 16);
+    __shared__ uint32_t part[kThreads / 64];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = h;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint32_t r = part[0];
+#pragma unroll
+      for (int w = 1; w < kThreads / 64; ++w) r = r > part[w] ? r : part[w];
+      if (r) atomicMax(amax_out, r << 16);
+    }
   }
 }
 
@@ -216,7 +243,15 @@ __global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const uint
   if (AMAX) {
     uint32_t h = (m >> 16) > (m & 0xFFFFu) ? (m >> 16) : (m & 0xFFFFu);
     h = wave_max_u32(h);
-    if ((threadIdx.x & 63) == 0 && h) atomicMax(amax_out, h << 16);
+    __shared__ uint32_t part[kThreads / 64];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = h;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint32_t r = part[0];
+#pragma unroll
+      for (int w = 1; w < kThreads / 64; ++w) r = r > part[w] ? r : part[w];
+      if (r) atomicMax(amax_out, r << 16);
+    }
   }
 }
 
@@ -260,8 +295,8 @@ extern "C" fog_status fog_amax(const void* x_bf16, int64_t n, float* amax, void*
   if (n > 0) {
     const int64_t nvec = n / 8;
     const int ntail = (int)(n - nvec * 8);
-    int64_t blocks = (nvec + kThreads * 4 - 1) / (kThreads * 4);
-    if (blocks > 2048) blocks = 2048;
+    int64_t blocks = (nvec + kThreads * 8 - 1) / (kThreads * 8);
+    if (blocks > 1024) blocks = 1024;   // 4 workgroups per CU; one atomic per workgroup
     if (blocks < 1) blocks = 1;
     amax_kernel<<<(int)blocks, kThreads, 0, s>>>(reinterpret_cast<const uint4*>(x_bf16), nvec,
                                                  reinterpret_cast<const uint16_t*>(x_bf16) + nvec * 8, ntail,
@@ -295,8 +330,9 @@ static void launch_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64
     int64_t r = rows, cpr = cols / 16, lx = ldx, lq = ldq;
     if (ldx == cols && ldq == cols) { cpr = rows * cpr; r = 1; }  // contiguous: one long row
     int64_t total = r * cpr;
-    int64_t blocks = (total + kThreads - 1) / kThreads;
-    if (blocks > 4096) blocks = 4096;
+    int64_t blocks = (total + 2 * kThreads - 1) / (2 * kThreads);
+    if (blocks > 2048) blocks = 2048;
+    if (blocks < 1) blocks = 1;
     if (amax_out)
       quantize_rows_kernel<FMT, true><<<(int)blocks, kThreads, 0, s>>>(x, r, cpr, lx, scale, q, lq, amax_out);
     else
