@@ -7,7 +7,7 @@
 // accumulator registers), so every 32-byte operand fragment read from LDS feeds four MFMAs.
 //
 // Memory pipeline: operand tiles go from global memory straight into LDS (buffer_load ... lds, no
-// register staging) through a ring of 4 stages of 32 KB; three K-steps are in flight while the fragments of a
+// register staging) through a ring of 4 stages of 32 KB (16 KB per operand); three K-steps are in flight while the fragments of a
 // fourth are consumed from registers, which covers HBM/L2 latency with a single workgroup per CU.  Out-of-range rows, columns
 // and K tails are zero-filled by the buffer bounds check.  Fragments are double buffered in
 // registers: the LDS reads of step k+1 are issued before the 16 MFMAs of step k.
@@ -34,8 +34,11 @@ constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kThreads = 256;
 constexpr int NSTAGE = 4;
 constexpr int OPERAND_BYTES = 256 * BK;      // 16 KB, both storage forms
-constexpr int STAGE_BYTES = 2 * OPERAND_BYTES;
-constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;  // 131072
+// LDS map: the four stages of the A operand first (64 KB), then the four stages of B (64 KB), so that
+// "stage * 16 KB + tile row offset" of any fragment read fits the 16-bit immediate of the LDS
+// instructions and one address register per operand serves all four stages.
+constexpr int RING_A = 0, RING_B = NSTAGE * OPERAND_BYTES;
+constexpr int RING_BYTES = 2 * NSTAGE * OPERAND_BYTES;  // 131072
 constexpr int EPI_STRIDE = 128 + 16;          // epilogue staging: 32 rows x 64 bf16 per wave, padded rows
 constexpr int EPI_BYTES = 32 * EPI_STRIDE;    // per wave
 constexpr int LDS_BYTES = RING_BYTES + 4 * EPI_BYTES;  // 149504
@@ -81,26 +84,29 @@ FOG_DEVICE v4i make_rsrc(const void* base, uint32_t bytes) {
 // Per-thread state of one operand's direct loads: 4 pieces of 1 KB per wave and K-step.
 struct LoadPlan {
   uint32_t off[4];   // byte offset of the NEXT step to issue, or >= OOB when the row / column chunk is outside the matrix
-  uint32_t kpos[4];  // contraction index this lane's chunk starts at within a step (for the K tail)
+  int klim;          // K minus the contraction index this lane's chunk of piece 0 starts at within a step;
+  int kdelta;        // pieces j > 0 start kdelta * j further on: the chunk of piece j of the step that
+                     // starts at k0 is inside the matrix iff k0 + kdelta * j < klim
   uint32_t step;     // offset increment per K-step
 };
 
 // K-contiguous operand: piece p covers tile rows 16 p .. 16 p + 15; lane -> (row, LDS chunk position).
-FOG_DEVICE LoadPlan plan_kc(int64_t ld, int row0, int rows) {
+FOG_DEVICE LoadPlan plan_kc(int64_t ld, int row0, int rows, int K) {
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
   LoadPlan p;
   p.step = BK;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int row = 16 * (4 * w + j) + (l >> 2);
-    const int c = (l & 3) ^ ((row >> 2) & 3);  // global chunk that lives at LDS position (l & 3) of this row
-    p.kpos[j] = 16 * c;
+    const int c = (l & 3) ^ ((row >> 2) & 3);  // global chunk that lives at LDS position (l & 3) of this row; same for every j
+    p.klim = K - 16 * c;
+    p.kdelta = 0;
     p.off[j] = (row0 + row < rows) ? (uint32_t)((int64_t)(row0 + row) * ld + 16 * c) : OOB;
   }
   return p;
 }
 // K-major operand: piece p covers contraction rows 4 p .. 4 p + 3; lane -> (k, LDS chunk position).
-FOG_DEVICE LoadPlan plan_km(int64_t ld, int col0, int cols) {
+FOG_DEVICE LoadPlan plan_km(int64_t ld, int col0, int cols, int K) {
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
   LoadPlan p;
   p.step = (uint32_t)(BK * ld);
@@ -108,29 +114,18 @@ FOG_DEVICE LoadPlan plan_km(int64_t ld, int col0, int cols) {
   for (int j = 0; j < 4; ++j) {
     const int k = 4 * (4 * w + j) + (l >> 4);
     const int c = (l & 15) ^ (k & 7);
-    p.kpos[j] = k;
+    if (j == 0) p.klim = K - k;
+    p.kdelta = 4;
     p.off[j] = (col0 + 16 * c < cols) ? (uint32_t)((int64_t)k * ld + col0 + 16 * c) : OOB;  // cols % 16 == 0
   }
   return p;
 }
-// Issue the next K-step (number kt) of one operand into LDS at `lds_wave_base` (+ 1 KB per piece) and
-// advance the plan.  Steps that reach past K take the checked path: lanes whose contraction index
-// is >= K fetch zeros.  Offsets that start at OOB stay >= OOB (spans are < 2^31 bytes).
-FOG_DEVICE void issue_loads(LoadPlan& p, v4i rsrc, int kt, int K, uint32_t lds_wave_base) {
-  if ((kt + 1) * BK <= K) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      load_to_lds(rsrc, p.off[j], lds_wave_base + 1024u * j);
-      p.off[j] += p.step;
-    }
-  } else {
-    const int k0 = kt * BK;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      load_to_lds(rsrc, (k0 + (int)p.kpos[j] >= K) ? OOB : p.off[j], lds_wave_base + 1024u * j);
-      p.off[j] += p.step;
-    }
-  }
+// Issue piece j of the K-step that starts at contraction index k0 and advance the plan.  Lanes whose
+// chunk lies at or past K (K tail, or steps past the end) fetch zeros.  Offsets that start at OOB
+// stay >= OOB (spans are < 2^31 bytes).  Branch-free: one compare and one select per load.
+FOG_DEVICE void issue_piece(LoadPlan& p, int j, v4i rsrc, int k0, uint32_t lds_piece_addr) {
+  load_to_lds(rsrc, k0 + p.kdelta * j < p.klim ? p.off[j] : OOB, lds_piece_addr);
+  p.off[j] += p.step;
 }
 
 // ---- LDS -> MFMA operand fragments (32 rows x 64 contraction bytes; 32 bytes per lane) ----
@@ -238,8 +233,8 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
   const uint32_t lds_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(uintptr_t)smem + 4096u * w));
   const FragAddr fa_addr = A_KM ? fragaddr_km(wm) : fragaddr_kc(wm);
   const FragAddr fb_addr = B_KM ? fragaddr_km(wn) : fragaddr_kc(wn);
-  // Second base 64 KB up: keeps every fragment read's constant part inside the 16-bit immediate.
-  const uint8_t* smem_hi = smem + 2 * STAGE_BYTES;
+  const uint8_t* ring_a = smem + RING_A;
+  const uint8_t* ring_b = smem + RING_B;
   const float alpha = (*g.sinv_a) * (*g.sinv_b);
 
   v16f acc[4][4];
@@ -253,23 +248,23 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
   const int nk = (g.K + BK - 1) / BK;
   const int nk4 = (nk + 3) & ~3;  // steps are handled four at a time (one per LDS stage); steps past K multiply zeros
 
-#define FOG_ISSUE(kt, STAGE)                                                            \
-  do {                                                                                  \
-    issue_loads(pa, rsrc_a, (kt), g.K, lds_w + (STAGE) * STAGE_BYTES);                  \
-    issue_loads(pb, rsrc_b, (kt), g.K, lds_w + (STAGE) * STAGE_BYTES + OPERAND_BYTES);  \
+#define FOG_ISSUE(kt, STAGE)                                                                       \
+  do {                                                                                             \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                \
+      issue_piece(pa, j, rsrc_a, (kt) * BK, lds_w + RING_A + (STAGE) * OPERAND_BYTES + 1024u * j); \
+      issue_piece(pb, j, rsrc_b, (kt) * BK, lds_w + RING_B + (STAGE) * OPERAND_BYTES + 1024u * j); \
+    }                                                                                              \
   } while (0)
 #define FOG_READ(STAGE, FA_, FB_)                                                                        \
   do {                                                                                                   \
-    const uint8_t* sa_ = ((STAGE) < 2 ? smem : smem_hi) + ((STAGE) & 1) * STAGE_BYTES;                   \
+    const uint8_t* sa_ = ring_a + (STAGE) * OPERAND_BYTES;                                               \
+    const uint8_t* sb_ = ring_b + (STAGE) * OPERAND_BYTES;                                               \
     _Pragma("unroll") for (int i = 0; i < 4; ++i) FA_[i] = read_frag<A_KM>(sa_, fa_addr, i);             \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j) FB_[j] = read_frag<B_KM>(sa_ + OPERAND_BYTES, fb_addr, j); \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) FB_[j] = read_frag<B_KM>(sb_, fb_addr, j);             \
   } while (0)
-#define FOG_MFMAS(FA_, FB_)                                                                              \
-  do {                                                                                                   \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                        \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                        \
-      acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(FB_[j], FA_[i], acc[i][j], FB, FA, 0, 0, 0, 0); \
-  } while (0)
+#define FOG_MFMA(j, FAI_, FB_, i) \
+  acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(FB_[j], FAI_, acc[i][j], FB, FA, 0, 0, 0, 0)
+#define FOG_FENCE() __builtin_amdgcn_sched_barrier(0)
   // Wait until at most N of this thread's vector-memory operations are outstanding and its own
   // fragment reads have returned, then synchronise: the awaited step is visible to every wave and
   // the stage whose fragments were read during the previous step is free to be overwritten.
@@ -284,15 +279,46 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
     else     __builtin_amdgcn_s_waitcnt(0x4070);            \
     __syncthreads();                                        \
   } while (0)
-  // One K-step: wait for the next step's data; past the barrier the stage of the step whose
-  // fragments are already in registers is free, so the load four steps ahead goes there (three
-  // K-steps stay in flight); fetch the next step's fragments; run this step's 16 MFMAs.
-#define FOG_STEP(kt_issue, ST_ISSUE, ST_READ, FA_IN, FB_IN, FA_CUR, FB_CUR, LAX) \
-  do {                                                                      \
-    FOG_WAIT_STEP(LAX);                                                     \
-    FOG_ISSUE(kt_issue, ST_ISSUE);                                          \
-    FOG_READ(ST_READ, FA_IN, FB_IN);                                        \
-    FOG_MFMAS(FA_CUR, FB_CUR);                                              \
+  // One K-step.  Past the barrier the stage of the step whose fragments are already in registers is
+  // free, so the loads four steps ahead go there (three K-steps stay in flight); the next step's
+  // fragments are fetched; this step's 16 MFMAs run on the fragments fetched one step earlier.
+  // The matrix core must not idle while the wave issues the 8 loads and 16 LDS reads, so they are
+  // dealt out between the MFMAs (each occupies the pipe for 64 cycles) and the order is pinned.
+  // Registers: the B fragments are double buffered (FB_CUR / FB_IN); the A fragments of rows 0..2
+  // are refreshed in place as soon as their row of MFMAs has been issued, only row 3 has a second
+  // copy (A3_CUR / A3_IN), so that every read is issued at least four MFMAs before the step ends.
+#define FOG_STEP(kt_issue, ST_ISSUE, ST_READ, FB_IN, FB_CUR, A3_IN, A3_CUR, LAX)                                   \
+  do {                                                                                                             \
+    const uint8_t* sa_ = ring_a + (ST_READ) * OPERAND_BYTES;                                                        \
+    const uint8_t* sb_ = ring_b + (ST_READ) * OPERAND_BYTES;                                                        \
+    const uint32_t la_ = lds_w + RING_A + (ST_ISSUE) * OPERAND_BYTES, lb_ = lds_w + RING_B + (ST_ISSUE) * OPERAND_BYTES; \
+    const int k0_ = (kt_issue) * BK;                                                                                \
+    FOG_WAIT_STEP(LAX);                                                                                             \
+    FOG_FENCE(); FOG_MFMA(0, fa[0], FB_CUR, 0); FOG_FENCE();                                                        \
+    issue_piece(pa, 0, rsrc_a, k0_, la_); issue_piece(pa, 1, rsrc_a, k0_, la_ + 1024u);                             \
+    FOG_FENCE(); FOG_MFMA(1, fa[0], FB_CUR, 0); FOG_FENCE();                                                        \
+    issue_piece(pa, 2, rsrc_a, k0_, la_ + 2048u); issue_piece(pa, 3, rsrc_a, k0_, la_ + 3072u);                     \
+    FOG_FENCE(); FOG_MFMA(2, fa[0], FB_CUR, 0); FOG_FENCE();                                                        \
+    issue_piece(pb, 0, rsrc_b, k0_, lb_); issue_piece(pb, 1, rsrc_b, k0_, lb_ + 1024u);                             \
+    FOG_FENCE(); FOG_MFMA(3, fa[0], FB_CUR, 0); FOG_FENCE();                                                        \
+    issue_piece(pb, 2, rsrc_b, k0_, lb_ + 2048u); issue_piece(pb, 3, rsrc_b, k0_, lb_ + 3072u);                     \
+    fa[0] = read_frag<A_KM>(sa_, fa_addr, 0);                                                                       \
+    FOG_FENCE(); FOG_MFMA(0, fa[1], FB_CUR, 1); FOG_FENCE();                                                        \
+    FB_IN[0] = read_frag<B_KM>(sb_, fb_addr, 0);                                                    \
+    FOG_FENCE(); FOG_MFMA(1, fa[1], FB_CUR, 1); FOG_FENCE();                                                        \
+    FB_IN[1] = read_frag<B_KM>(sb_, fb_addr, 1);                                                    \
+    FOG_FENCE(); FOG_MFMA(2, fa[1], FB_CUR, 1); FOG_FENCE();                                                        \
+    FB_IN[2] = read_frag<B_KM>(sb_, fb_addr, 2);                                                    \
+    FOG_FENCE(); FOG_MFMA(3, fa[1], FB_CUR, 1); FOG_FENCE();                                                        \
+    FB_IN[3] = read_frag<B_KM>(sb_, fb_addr, 3);                                                    \
+    fa[1] = read_frag<A_KM>(sa_, fa_addr, 1);                                                                       \
+    FOG_FENCE(); FOG_MFMA(0, fa[2], FB_CUR, 2); FOG_MFMA(1, fa[2], FB_CUR, 2); FOG_FENCE();                         \
+    A3_IN = read_frag<A_KM>(sa_, fa_addr, 3);                                                                       \
+    FOG_FENCE(); FOG_MFMA(2, fa[2], FB_CUR, 2); FOG_MFMA(3, fa[2], FB_CUR, 2); FOG_FENCE();                         \
+    fa[2] = read_frag<A_KM>(sa_, fa_addr, 2);                                                                       \
+    FOG_FENCE();                                                                                                    \
+    FOG_MFMA(0, A3_CUR, FB_CUR, 3); FOG_MFMA(1, A3_CUR, FB_CUR, 3); FOG_MFMA(2, A3_CUR, FB_CUR, 3); FOG_MFMA(3, A3_CUR, FB_CUR, 3); \
+    FOG_FENCE();                                                                                                    \
   } while (0)
 
   // The load stream runs ahead of the MFMAs across tile boundaries: during the last four steps of a
@@ -301,16 +327,16 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
   // drain while the next tile computes.
   int m0, n0;
   tile_origin(walk.first, g.tiles_m, g.tiles_n, m0, n0);
-  LoadPlan pa = A_KM ? plan_km(g.lda, m0, g.M) : plan_kc(g.lda, m0, g.M);
-  LoadPlan pb = B_KM ? plan_km(g.ldb, n0, g.N) : plan_kc(g.ldb, n0, g.N);
-  v8i xa[4], xb[4], ya[4], yb[4];
+  LoadPlan pa = A_KM ? plan_km(g.lda, m0, g.M, g.K) : plan_kc(g.lda, m0, g.M, g.K);
+  LoadPlan pb = B_KM ? plan_km(g.ldb, n0, g.N, g.K) : plan_kc(g.ldb, n0, g.N, g.K);
+  v8i fa[4], fa3, xb[4], yb[4];   // A fragments (row 3 twice), B fragments twice
   FOG_ISSUE(0, 0);
   FOG_ISSUE(1, 1);
   FOG_ISSUE(2, 2);
   FOG_ISSUE(3, 3);
   __builtin_amdgcn_s_waitcnt(0x4F78);  // vmcnt = 24: step 0 has landed
   __syncthreads();
-  FOG_READ(0, xa, xb);
+  FOG_READ(0, fa, xb);
 
   uint8_t* epi = smem + RING_BYTES + w * EPI_BYTES;  // this wave's private staging area
   bool stores_pending = false;                        // uniform: an epilogue's stores may still be in flight
@@ -323,21 +349,21 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
         // zero-fill if there is none, which keeps the outstanding-load count the waits assume)
         if (next < walk.end) {
           tile_origin(next, g.tiles_m, g.tiles_n, m0, n0);
-          pa = A_KM ? plan_km(g.lda, m0, g.M) : plan_kc(g.lda, m0, g.M);
-          pb = B_KM ? plan_km(g.ldb, n0, g.N) : plan_kc(g.ldb, n0, g.N);
+          pa = A_KM ? plan_km(g.lda, m0, g.M, g.K) : plan_kc(g.lda, m0, g.M, g.K);
+          pb = B_KM ? plan_km(g.ldb, n0, g.N, g.K) : plan_kc(g.ldb, n0, g.N, g.K);
         } else {
 #pragma unroll
           for (int j = 0; j < 4; ++j) pa.off[j] = pb.off[j] = OOB;
         }
       }
       const int ki = kt == nk4 - 4 ? 0 : kt + 4;  // K-step number (within its tile) of the first load issued below
-      FOG_STEP(ki + 0, 0, 1, ya, yb, xa, xb, stores_pending);
-      FOG_STEP(ki + 1, 1, 2, xa, xb, ya, yb, stores_pending);
-      FOG_STEP(ki + 2, 2, 3, ya, yb, xa, xb, stores_pending);
-      FOG_STEP(ki + 3, 3, 0, xa, xb, ya, yb, false);
+      FOG_STEP(ki + 0, 0, 1, yb, xb, fa3, fa[3], stores_pending);
+      FOG_STEP(ki + 1, 1, 2, xb, yb, fa[3], fa3, stores_pending);
+      FOG_STEP(ki + 2, 2, 3, yb, xb, fa3, fa[3], stores_pending);
+      FOG_STEP(ki + 3, 3, 0, xb, yb, fa[3], fa3, false);
       stores_pending = false;
     }
-    // xa, xb now hold step 0 of the next tile.
+    // fa, xb now hold step 0 of the next tile.
 
     // Epilogue.  With B as the first MFMA operand, lane l holds for tile (i, j), register r:
     //   row    m = m_cur + wm + 32 i + (l & 31)
@@ -386,7 +412,8 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
 #undef FOG_ISSUE
 #undef FOG_READ
-#undef FOG_MFMAS
+#undef FOG_MFMA
+#undef FOG_FENCE
 #undef FOG_WAIT_STEP
 #undef FOG_STEP
 }
