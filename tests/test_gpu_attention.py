@@ -7,7 +7,7 @@ import torch
 
 from oracle import attention, bf16, fp8, scaling
 from paper_2505_20524_amd import fog, synth
-from parity import CAST_EPS, check_bf16, dev, fscalar, host_u16
+from parity import check_bf16, dev, fscalar, host_u16
 
 pytestmark = pytest.mark.gpu
 
@@ -43,10 +43,12 @@ def check_fwd(c, B, H, S, s, causal, heads):
     ref = oracle_fwd_heads(c, heads, s, causal)
     pmax = 0.0
     for (b, h), (Or, lr, ap) in ref.items():
+        dx = attention.logit_uncertainty(c["q"][0][b, h], c["k"][0][b, h], c["q"][1], c["k"][1], s, causal)
         slack = attention.fwd_cast_slack(c["q"][0][b, h], c["k"][0][b, h], c["v"][0][b, h], c["q"][1], c["k"][1], c["v"][1],
-                                         s, 448.0, causal, CAST_EPS)
+                                         s, 448.0, causal, dx=dx)
         check_bf16(O[b, h], Or, what="O[%d,%d]" % (b, h), slack=slack, max_flip_frac=1.0)
-        assert np.abs(lse[b, h] - lr).max() < 2e-4, "lse"
+        lunc = attention.lse_uncertainty(c["q"][0][b, h], c["k"][0][b, h], c["q"][1], c["k"][1], s, causal, dx=dx)
+        assert np.all(np.abs(lse[b, h] - lr) <= 2e-4 + lunc), "lse"
         pmax = max(pmax, float(ap))
     assert np.isfinite(lse).all()
     if len(heads) == B * H:
@@ -108,7 +110,7 @@ def run_bwd(c, B, H, S, s, causal, heads, do_bits):
                                     O_bits[b, h], do_bits[b, h], c["do"][0][b, h], c["do"][1], lse[b, h], s, 448.0, rho_ds, causal)
         sl = attention.bwd_cast_slack(c["q"][0][b, h], c["k"][0][b, h], c["v"][0][b, h], c["q"][1], c["k"][1], c["v"][1],
                                       O_bits[b, h], do_bits[b, h], c["do"][0][b, h], c["do"][1], lse[b, h], s, 448.0, rho_ds,
-                                      causal, CAST_EPS)
+                                      causal)
         check_bf16(dQ[b, h], r[0], what="dQ[%d,%d]" % (b, h), max_flip_frac=1.0, slack=sl[0])
         check_bf16(dK[b, h], r[1], what="dK[%d,%d]" % (b, h), max_flip_frac=1.0, slack=sl[1])
         check_bf16(dV[b, h], r[2], what="dV[%d,%d]" % (b, h), max_flip_frac=1.0, slack=sl[2])
@@ -126,14 +128,14 @@ def test_backward_parity(B, H, S, causal):
 
 
 def test_config3_full_size_sampled_heads():
-    """Config 3 whole on the GPU (B 4, H 16, S 2048, D 128, causal); the oracle checks 4 (batch, head)
-    pairs in full (first, last, two seeded), forward and backward; every head is checked for sanity."""
+    """Config 3 whole on the GPU (B 4, H 16, S 2048, D 128, causal); the oracle checks 3 (batch, head)
+    pairs in full (first, last, one seeded), forward and backward; every head is checked for sanity."""
     cfg = synth.CONFIGS[3]
     a = cfg.attn
     t = synth.attention_tensors(cfg)
     c = cast_all(t["Q"], t["K"], t["V"], t["dO"])
     rng = np.random.default_rng(3)
-    heads = [(0, 0), (a.B - 1, a.H - 1)] + [(int(rng.integers(a.B)), int(rng.integers(a.H))) for _ in range(2)]
+    heads = [(0, 0), (a.B - 1, a.H - 1), (int(rng.integers(a.B)), int(rng.integers(a.H)))]
     s = 1 / math.sqrt(128)
     O, lse = check_fwd(c, a.B, a.H, a.S, s, True, heads)
     Of = bf16.bits_to_f64(O)
