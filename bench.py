@@ -24,6 +24,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_FP8_TFLOPS = 5033.0     # 256 CU x 4 SIMD x 2048 FLOP/clk x 2.4 GHz (dense FP8 MFMA)
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per fp8_gemm_kernel launch (average over the step's 15 launches), from two rocprofv3 --pmc
+# runs of this script (FETCH_SIZE, WRITE_SIZE), each scaled by the reading of a plain 1 GiB copy:
+# 626 MB read + 131 MB written.  Only measured for the default workload.
+MEASURED_GEMM_TRAFFIC_BYTES = {5: 7.575e8}
 
 
 def cpu_baseline(cfg):
@@ -66,6 +70,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no collectives are on the path); use --gpus 1", file=sys.stderr)
@@ -82,6 +88,12 @@ def main():
     blk = block.Block(cfg)
     torch.cuda.synchronize()
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         blk.step()
     torch.cuda.synchronize()
@@ -109,7 +121,7 @@ def main():
     g = kernels.get("gemm") or kernels.get("attn_fwd")
     roofline = {"bound": "mfma", "kernel": "fp8_gemm_kernel" if "gemm" in kernels else "attn_fwd_kernel",
                 "achieved": g["achieved"], "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": g["frac"],
-                "traffic": None, "launches_per_step": g["launches_per_step"], "avg_launch_ms": g["avg_launch_ms"]}
+                "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(cfg.cid) if "gemm" in kernels else None, "launches_per_step": g["launches_per_step"], "avg_launch_ms": g["avg_launch_ms"]}
 
     out = {
         "metric": "FP8 TFLOP/s (block GEMMs fwd+dgrad+wgrad + FP8 causal attention fwd+bwd, casts in the timed step)",
