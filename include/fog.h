@@ -108,6 +108,19 @@ fog_status fog_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t 
                         float* amax_out, void* stream);
 
 /*
+ * Activation kurtosis, the paper's outlier diagnostic (Section 4): for each token vector x (a row),
+ * kurt(x) = mu[x^4] / (mu[x^2])^2 (element-wise powers, x not centred); the result is the mean over
+ * the rows.  The denominator is read as the squared un-centred second moment (1 for a constant
+ * vector, cols for a one-hot vector, 3 for Gaussian data).  Rows of zeros contribute 0.
+ *   x_bf16 : [rows, cols] bfloat16, leading dimension ldx; one pass, binary32 sums.
+ *   kurt   : one float, overwritten.  Rows are summed with float atomics: the last bits may vary
+ *            from run to run.
+ * The fast path needs a 16-byte aligned x and cols, ldx multiples of 8; other shapes take a scalar path.
+ * Errors: NULL, negative sizes or ldx < cols (SHAPE), odd address (ALIGN).
+ */
+fog_status fog_kurtosis(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, float* kurt, void* stream);
+
+/*
  * Scaled FP8 product (Appendix E): C = scale_inv_A * scale_inv_B * (decode(A) x decode(B)) in
  * the given layout, FP8 products accumulated in binary32, result rounded once to bfloat16.
  *   A, B   : FP8 codes (fmtA / fmtB may differ: E5M2 gradients times E4M3 weights), lda / ldb.

@@ -1,0 +1,85 @@
+// Activation kurtosis (Section 4 of the paper): kurt(x) = mu[x^4] / (mu[x^2])^2 per token vector,
+// averaged over the token vectors of a tensor.  The denominator is read as the squared un-centred
+// second moment (the printed sigma^2[x^2] cannot be the variance of x^2: that would fall as an
+// outlier grows).  HBM-bound: every element is read once with 16-byte loads; one wave per row,
+// binary32 sums of x^2 and x^4, one float atomic per workgroup.
+#include "common.h"
+#include "launch.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__global__ void zero_f32_kernel(float* p) { *p = 0.0f; }
+
+FOG_DEVICE void acc_pair(uint32_t w, float& s2, float& s4) {
+  const float a = bf16lo(w), b = bf16hi(w);
+  const float a2 = a * a, b2 = b * b;
+  s2 += a2 + b2;
+  s4 = __builtin_fmaf(a2, a2, __builtin_fmaf(b2, b2, s4));
+}
+
+// VEC: rows are 16-byte aligned and cols % 8 == 0.
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void kurtosis_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx,
+                                                            float inv_rows, float* __restrict__ out) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  float local = 0.0f;   // sum of this wave's row kurtoses
+  for (int64_t r = (int64_t)blockIdx.x * 4 + w; r < rows; r += (int64_t)gridDim.x * 4) {
+    const uint16_t* row = x + r * ldx;
+    float s2 = 0.0f, s4 = 0.0f;
+    if (VEC) {
+      const int64_t nvec = cols >> 3;
+      int64_t i = lane;
+      for (; i + 192 < nvec; i += 256) {   // four loads in flight
+        uint4 a = ld_nt16(row + 8 * i), b = ld_nt16(row + 8 * (i + 64)), c = ld_nt16(row + 8 * (i + 128)), d = ld_nt16(row + 8 * (i + 192));
+        acc_pair(a.x, s2, s4); acc_pair(a.y, s2, s4); acc_pair(a.z, s2, s4); acc_pair(a.w, s2, s4);
+        acc_pair(b.x, s2, s4); acc_pair(b.y, s2, s4); acc_pair(b.z, s2, s4); acc_pair(b.w, s2, s4);
+        acc_pair(c.x, s2, s4); acc_pair(c.y, s2, s4); acc_pair(c.z, s2, s4); acc_pair(c.w, s2, s4);
+        acc_pair(d.x, s2, s4); acc_pair(d.y, s2, s4); acc_pair(d.z, s2, s4); acc_pair(d.w, s2, s4);
+      }
+      for (; i < nvec; i += 64) {
+        uint4 a = ld_nt16(row + 8 * i);
+        acc_pair(a.x, s2, s4); acc_pair(a.y, s2, s4); acc_pair(a.z, s2, s4); acc_pair(a.w, s2, s4);
+      }
+    } else {
+      for (int64_t i = lane; i < cols; i += 64) {
+        const float a = bf16lo(row[i]), a2 = a * a;
+        s2 += a2;
+        s4 = __builtin_fmaf(a2, a2, s4);
+      }
+    }
+    s2 = wave_sum_f32(s2);
+    s4 = wave_sum_f32(s4);
+    // mu4 / mu2^2 = cols * s4 / s2^2; an all-zero row contributes 0
+    if (s2 > 0.0f) local += (float)cols * (s4 / (s2 * s2));
+  }
+  __shared__ float part[4];
+  if (lane == 0) part[w] = local;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const float t = (part[0] + part[1]) + (part[2] + part[3]);
+    if (t != 0.0f) atomicAdd(out, t * inv_rows);
+  }
+}
+
+}  // namespace
+
+extern "C" fog_status fog_kurtosis(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, float* kurt, void* stream) {
+  if (!kurt) return FOG_ERR_NULL;
+  if (rows < 0 || cols < 0) return FOG_ERR_SHAPE;
+  hipStream_t s = (hipStream_t)stream;
+  zero_f32_kernel<<<1, 1, 0, s>>>(kurt);
+  if (rows == 0 || cols == 0) return fog_launch_status();
+  if (!x_bf16) return FOG_ERR_NULL;
+  if (ldx < cols) return FOG_ERR_SHAPE;
+  if (reinterpret_cast<uintptr_t>(x_bf16) & 1u) return FOG_ERR_ALIGN;
+  const bool vec = (reinterpret_cast<uintptr_t>(x_bf16) & 15u) == 0 && cols % 8 == 0 && ldx % 8 == 0;
+  int64_t blocks = (rows + 3) / 4;
+  if (blocks > 2048) blocks = 2048;
+  const uint16_t* x = reinterpret_cast<const uint16_t*>(x_bf16);
+  const float inv = 1.0f / (float)rows;
+  if (vec) kurtosis_kernel<true><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, inv, kurt);
+  else     kurtosis_kernel<false><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, inv, kurt);
+  return fog_launch_status();
+}

@@ -26,6 +26,7 @@ SIGNATURES = {
     "fog_scale": (_I, [_P, _I, _I, _P, _P, _P]),
     "fog_scale_delayed": (_I, [_P, _I, _P, _I, _I, _P, _P, _P]),
     "fog_quantize": (_I, [_P, _I64, _I64, _I64, _I, _P, _P, _I64, _P, _I64, _P, _P]),
+    "fog_kurtosis": (_I, [_P, _I64, _I64, _I64, _P, _P]),
     "fog_fp8_gemm": (_I, [_I, _I64, _I64, _I64, _P, _I, _I64, _P, _P, _I, _I64, _P, _P, _I64, _P, _SZ, _P]),
     "fog_fp8_gemm_workspace": (_SZ, [_I, _I64, _I64, _I64]),
     "fog_fp8_attn_fwd": (_I, [_I, _I, _I, _I, _F, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
@@ -91,6 +92,11 @@ def quantize(x, fmt, scale_t, q=None, qT=None, amax_out=None, stream=None):
                                _ptr(q), q.stride(0) if q is not None else 0,
                                _ptr(qT), qT.stride(0) if qT is not None else 0,
                                _ptr(amax_out), _stream(stream)), "fog_quantize")
+
+
+def kurtosis(x, out, stream=None):
+    rows, cols = x.shape
+    _check(load().fog_kurtosis(_ptr(x), rows, cols, x.stride(0), _ptr(out), _stream(stream)), "fog_kurtosis")
 
 
 def fp8_gemm(layout, M, N, K, A, fmt_a, sinv_a, B, fmt_b, sinv_b, C, workspace=None, stream=None):
