@@ -118,6 +118,22 @@ def main():
             ach = work / (ms * 1e-3) / 1e9
             kernels[kind] = {"launches_per_step": n // args.steps, "avg_launch_ms": ms / n, "achieved": ach,
                              "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
+    # The kurtosis monitor (a diagnostic, not a step of the training path): timed on its own, after the
+    # timed region, over the activation inputs of every linear layer.
+    if blk.linears:
+        kout = torch.zeros(1, device="cuda")
+        kt = block.EventTimer()
+        for rep in range(4):
+            for l in blk.linears:
+                if rep:
+                    kt.begin("kurtosis", l.X.x.numel() * 2)
+                fog.kurtosis(l.X.x, kout)
+                if rep:
+                    kt.end()
+        torch.cuda.synchronize()
+        n, work, ms = kt.summary()["kurtosis"]
+        kernels["kurtosis_monitor"] = {"launches": n, "avg_launch_ms": ms / n, "achieved": work / (ms * 1e-3) / 1e9,
+                                       "unit": "GB/s", "frac": work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "in_timed_step": False}
     g = kernels.get("gemm") or kernels.get("attn_fwd")
     roofline = {"bound": "mfma", "kernel": "fp8_gemm_kernel" if "gemm" in kernels else "attn_fwd_kernel",
                 "achieved": g["achieved"], "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": g["frac"],

@@ -295,29 +295,36 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
     const int k0_ = (kt_issue) * BK;                                                                                \
     FOG_WAIT_STEP(LAX);                                                                                             \
     FOG_FENCE(); FOG_MFMA(0, fa[0], FB_CUR, 0); FOG_FENCE();                                                        \
-    issue_piece(pa, 0, rsrc_a, k0_, la_); issue_piece(pa, 1, rsrc_a, k0_, la_ + 1024u);                             \
+    issue_piece(pa, 0, rsrc_a, k0_, la_);                                                                           \
     FOG_FENCE(); FOG_MFMA(1, fa[0], FB_CUR, 0); FOG_FENCE();                                                        \
-    issue_piece(pa, 2, rsrc_a, k0_, la_ + 2048u); issue_piece(pa, 3, rsrc_a, k0_, la_ + 3072u);                     \
+    FB_IN[0] = read_frag<B_KM>(sb_, fb_addr, 0);                                                                    \
     FOG_FENCE(); FOG_MFMA(2, fa[0], FB_CUR, 0); FOG_FENCE();                                                        \
-    issue_piece(pb, 0, rsrc_b, k0_, lb_); issue_piece(pb, 1, rsrc_b, k0_, lb_ + 1024u);                             \
+    issue_piece(pa, 1, rsrc_a, k0_, la_ + 1024u);                                                                   \
     FOG_FENCE(); FOG_MFMA(3, fa[0], FB_CUR, 0); FOG_FENCE();                                                        \
-    issue_piece(pb, 2, rsrc_b, k0_, lb_ + 2048u); issue_piece(pb, 3, rsrc_b, k0_, lb_ + 3072u);                     \
-    fa[0] = read_frag<A_KM>(sa_, fa_addr, 0);                                                                       \
+    FB_IN[1] = read_frag<B_KM>(sb_, fb_addr, 1);                                                                    \
     FOG_FENCE(); FOG_MFMA(0, fa[1], FB_CUR, 1); FOG_FENCE();                                                        \
-    FB_IN[0] = read_frag<B_KM>(sb_, fb_addr, 0);                                                    \
+    issue_piece(pa, 2, rsrc_a, k0_, la_ + 2048u);                                                                   \
+    fa[0] = read_frag<A_KM>(sa_, fa_addr, 0);                                                                       \
     FOG_FENCE(); FOG_MFMA(1, fa[1], FB_CUR, 1); FOG_FENCE();                                                        \
-    FB_IN[1] = read_frag<B_KM>(sb_, fb_addr, 1);                                                    \
+    FB_IN[2] = read_frag<B_KM>(sb_, fb_addr, 2);                                                                    \
     FOG_FENCE(); FOG_MFMA(2, fa[1], FB_CUR, 1); FOG_FENCE();                                                        \
-    FB_IN[2] = read_frag<B_KM>(sb_, fb_addr, 2);                                                    \
+    issue_piece(pa, 3, rsrc_a, k0_, la_ + 3072u);                                                                   \
     FOG_FENCE(); FOG_MFMA(3, fa[1], FB_CUR, 1); FOG_FENCE();                                                        \
-    FB_IN[3] = read_frag<B_KM>(sb_, fb_addr, 3);                                                    \
+    FB_IN[3] = read_frag<B_KM>(sb_, fb_addr, 3);                                                                    \
+    FOG_FENCE(); FOG_MFMA(0, fa[2], FB_CUR, 2); FOG_FENCE();                                                        \
+    issue_piece(pb, 0, rsrc_b, k0_, lb_);                                                                           \
     fa[1] = read_frag<A_KM>(sa_, fa_addr, 1);                                                                       \
-    FOG_FENCE(); FOG_MFMA(0, fa[2], FB_CUR, 2); FOG_MFMA(1, fa[2], FB_CUR, 2); FOG_FENCE();                         \
+    FOG_FENCE(); FOG_MFMA(1, fa[2], FB_CUR, 2); FOG_FENCE();                                                        \
     A3_IN = read_frag<A_KM>(sa_, fa_addr, 3);                                                                       \
-    FOG_FENCE(); FOG_MFMA(2, fa[2], FB_CUR, 2); FOG_MFMA(3, fa[2], FB_CUR, 2); FOG_FENCE();                         \
+    FOG_FENCE(); FOG_MFMA(2, fa[2], FB_CUR, 2); FOG_FENCE();                                                        \
+    issue_piece(pb, 1, rsrc_b, k0_, lb_ + 1024u);                                                                   \
+    FOG_FENCE(); FOG_MFMA(3, fa[2], FB_CUR, 2); FOG_FENCE();                                                        \
+    issue_piece(pb, 2, rsrc_b, k0_, lb_ + 2048u);                                                                   \
+    FOG_FENCE(); FOG_MFMA(0, A3_CUR, FB_CUR, 3); FOG_FENCE();                                                       \
     fa[2] = read_frag<A_KM>(sa_, fa_addr, 2);                                                                       \
-    FOG_FENCE();                                                                                                    \
-    FOG_MFMA(0, A3_CUR, FB_CUR, 3); FOG_MFMA(1, A3_CUR, FB_CUR, 3); FOG_MFMA(2, A3_CUR, FB_CUR, 3); FOG_MFMA(3, A3_CUR, FB_CUR, 3); \
+    FOG_FENCE(); FOG_MFMA(1, A3_CUR, FB_CUR, 3); FOG_FENCE();                                                       \
+    issue_piece(pb, 3, rsrc_b, k0_, lb_ + 3072u);                                                                   \
+    FOG_FENCE(); FOG_MFMA(2, A3_CUR, FB_CUR, 3); FOG_MFMA(3, A3_CUR, FB_CUR, 3);                                    \
     FOG_FENCE();                                                                                                    \
   } while (0)
 
