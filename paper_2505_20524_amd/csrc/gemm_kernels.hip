@@ -7,17 +7,21 @@
 // accumulator registers), so every 32-byte operand fragment read from LDS feeds four MFMAs.
 //
 // Memory pipeline: operand tiles go from global memory straight into LDS (buffer_load ... lds, no
-// register staging) through a ring of 4 stages of 32 KB (16 KB per operand); three K-steps are in flight while the fragments of a
-// fourth are consumed from registers, which covers HBM/L2 latency with a single workgroup per CU.  Out-of-range rows, columns
-// and K tails are zero-filled by the buffer bounds check.  Fragments are double buffered in
-// registers: the LDS reads of step k+1 are issued before the 16 MFMAs of step k.
+// register staging).  The unit of loading is a PAIR of K-steps (128 contraction bytes): every load
+// instruction then covers whole 128-byte lines of the operand (8 rows x 128 bytes, or 4 contraction
+// rows x 256 bytes), which halves the number of requests the vector cache sends to L2 compared with
+// 64-byte row pieces; that request stream, not HBM, is what limits this kernel.  LDS holds two pair
+// stages of 64 KB (32 KB per operand).  While the MFMAs of one K-step run, the fragments of the next
+// are read into registers (double buffered), and during the second K-step of a pair the stage of the
+// previous pair, fully read by then, is refilled with the pair after next.  Out-of-range rows,
+// columns and K tails are zero-filled by the buffer bounds check.
 //
 // Operand storage in LDS, chosen so that the direct loads (which write 64 lanes x 16 bytes
 // contiguously) and the fragment reads are both bank-conflict free:
-//   * "K-contiguous" operands (A of NT/NN, B of NT): [256 rows][64 bytes]; the four 16-byte chunks of
-//     a row are XOR-swizzled with (row >> 2) & 3 by choosing which global chunk each lane fetches;
-//     a lane reads its 32 contraction bytes with two 16-byte reads.
-//   * "K-major" operands (B of NN, A and B of TN): [64 k][256 bytes], the sixteen chunks of a row
+//   * "K-contiguous" operands (A of NT/NN, B of NT): [256 rows][128 bytes]; the eight 16-byte chunks
+//     of a row are XOR-swizzled with (row >> 1) & 7 by choosing which global chunk each lane fetches;
+//     a lane reads the 32 contraction bytes of its K-step with two 16-byte reads.
+//   * "K-major" operands (B of NN, A and B of TN): [128 k][256 bytes], the sixteen chunks of a row
 //     swizzled with k & 7; a lane gathers 8 contraction bytes of its own column with the
 //     byte-transposing LDS read (ds_read_b64_tr_b8), four of them per 32-byte fragment.
 // Both give byte j of a lane's fragment the contraction index 32 * (lane / 32) + j of the step,
@@ -32,13 +36,13 @@ namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kThreads = 256;
-constexpr int NSTAGE = 4;
-constexpr int OPERAND_BYTES = 256 * BK;      // 16 KB, both storage forms
-// LDS map: the four stages of the A operand first (64 KB), then the four stages of B (64 KB), so that
-// "stage * 16 KB + tile row offset" of any fragment read fits the 16-bit immediate of the LDS
-// instructions and one address register per operand serves all four stages.
-constexpr int RING_A = 0, RING_B = NSTAGE * OPERAND_BYTES;
-constexpr int RING_BYTES = 2 * NSTAGE * OPERAND_BYTES;  // 131072
+constexpr int PAIR_K = 2 * BK;               // contraction bytes per load unit
+constexpr int OPERAND_BYTES = 256 * PAIR_K;  // 32 KB per operand and pair stage, both storage forms
+// LDS map: the two pair stages of the A operand first (64 KB), then those of B (64 KB), so that
+// "stage * 32 KB + K-step half + tile row offset" of any fragment read fits the 16-bit immediate
+// of the LDS instructions and one address register per operand serves both stages.
+constexpr int RING_A = 0, RING_B = 2 * OPERAND_BYTES;
+constexpr int RING_BYTES = 4 * OPERAND_BYTES;  // 131072
 constexpr int EPI_STRIDE = 128 + 16;          // epilogue staging: 32 rows x 64 bf16 per wave, padded rows
 constexpr int EPI_BYTES = 32 * EPI_STRIDE;    // per wave
 constexpr int LDS_BYTES = RING_BYTES + 4 * EPI_BYTES;  // 149504
@@ -81,79 +85,100 @@ FOG_DEVICE v4i make_rsrc(const void* base, uint32_t bytes) {
   return r;
 }
 
-// Per-thread state of one operand's direct loads: 4 pieces of 1 KB per wave and K-step.
+// Per-thread state of one operand's direct loads.  A wave fetches 8 pieces of 1 KB per pair of
+// K-steps; piece j of wave w lands at byte 8192 w + 1024 j of the operand's pair stage.  The
+// swizzle makes the offsets of even and of odd pieces two arithmetic progressions, so two
+// offsets and a uniform stride describe all eight.
 struct LoadPlan {
-  uint32_t off[4];   // byte offset of the NEXT step to issue, or >= OOB when the row / column chunk is outside the matrix
-  int klim;          // K minus the contraction index this lane's chunk of piece 0 starts at within a step;
-  int kdelta;        // pieces j > 0 start kdelta * j further on: the chunk of piece j of the step that
-                     // starts at k0 is inside the matrix iff k0 + kdelta * j < klim
-  uint32_t step;     // offset increment per K-step
+  uint32_t off[2];   // byte offset of pieces 0 and 1 of the NEXT pair to issue; piece j is at
+                     // off[j & 1] + (j >> 1) * stride2; >= OOB when the piece's column chunk is outside the matrix
+  int klim[2];       // the chunk of piece j of the pair that starts at contraction index k0 is inside
+                     // the matrix iff k0 + kdelta * j < klim[j & 1]  (kdelta: 0 K-contiguous, 4 K-major)
+  int jlim;          // pieces j >= jlim lie below the last row of a K-contiguous operand
+  uint32_t stride2;  // uniform: 16 rows (K-contiguous) or 8 contraction rows (K-major)
+  uint32_t step;     // uniform: offset increment per pair of K-steps
 };
 
-// K-contiguous operand: piece p covers tile rows 16 p .. 16 p + 15; lane -> (row, LDS chunk position).
+// K-contiguous operand: piece j covers tile rows 64 w + 8 j .. + 7; lane -> (row, LDS chunk position).
 FOG_DEVICE LoadPlan plan_kc(int64_t ld, int row0, int rows, int K) {
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int r8 = l >> 3, pos = l & 7;
   LoadPlan p;
-  p.step = BK;
+  p.step = PAIR_K;
+  p.stride2 = (uint32_t)(16 * ld);
+  const int first = row0 + 64 * w + r8;      // global row of piece 0
+  const int rem = rows - first;
+  p.jlim = rem > 0 ? (rem + 7) >> 3 : 0;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int row = 16 * (4 * w + j) + (l >> 2);
-    const int c = (l & 3) ^ ((row >> 2) & 3);  // global chunk that lives at LDS position (l & 3) of this row; same for every j
-    p.klim = K - 16 * c;
-    p.kdelta = 0;
-    p.off[j] = (row0 + row < rows) ? (uint32_t)((int64_t)(row0 + row) * ld + 16 * c) : OOB;
+  for (int par = 0; par < 2; ++par) {
+    // row = 64 w + 8 j + r8: the swizzle key (row >> 1) & 7 is (r8 >> 1) ^ 4 (j & 1)
+    const int c = pos ^ (r8 >> 1) ^ (4 * par);  // global chunk that lives at LDS position pos of this row
+    p.klim[par] = K - 16 * c;
+    p.off[par] = (uint32_t)((int64_t)(first + 8 * par) * ld + 16 * c);
   }
   return p;
 }
-// K-major operand: piece p covers contraction rows 4 p .. 4 p + 3; lane -> (k, LDS chunk position).
+// K-major operand: piece j covers contraction rows 32 w + 4 j .. + 3 of the pair; lane -> (k, LDS chunk position).
 FOG_DEVICE LoadPlan plan_km(int64_t ld, int col0, int cols, int K) {
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
   LoadPlan p;
-  p.step = (uint32_t)(BK * ld);
+  p.step = (uint32_t)(PAIR_K * ld);
+  p.stride2 = (uint32_t)(8 * ld);
+  p.jlim = 8;
+  const int k = 32 * w + (l >> 4);            // contraction row of piece 0 within the pair
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int k = 4 * (4 * w + j) + (l >> 4);
-    const int c = (l & 15) ^ (k & 7);
-    if (j == 0) p.klim = K - k;
-    p.kdelta = 4;
-    p.off[j] = (col0 + 16 * c < cols) ? (uint32_t)((int64_t)k * ld + col0 + 16 * c) : OOB;  // cols % 16 == 0
+  for (int par = 0; par < 2; ++par) {
+    // k + 4 j: the swizzle key (k + 4 j) & 7 is ((l >> 4) & 7) ^ 4 (j & 1)
+    const int c = (l & 15) ^ (l >> 4) ^ (4 * par);
+    p.klim[par] = K - k;
+    p.off[par] = (col0 + 16 * c < cols) ? (uint32_t)((int64_t)(k + 4 * par) * ld + col0 + 16 * c) : OOB;  // cols % 16 == 0
   }
   return p;
 }
-// Issue piece j of the K-step that starts at contraction index k0 and advance the plan.  Lanes whose
-// chunk lies at or past K (K tail, or steps past the end) fetch zeros.  Offsets that start at OOB
-// stay >= OOB (spans are < 2^31 bytes).  Branch-free: one compare and one select per load.
-FOG_DEVICE void issue_piece(LoadPlan& p, int j, v4i rsrc, int k0, uint32_t lds_piece_addr) {
-  load_to_lds(rsrc, k0 + p.kdelta * j < p.klim ? p.off[j] : OOB, lds_piece_addr);
-  p.off[j] += p.step;
+// Issue piece j of the pair that starts at contraction index k0.  Lanes whose chunk lies at or past
+// K (K tail, or pairs past the end) or below the last row fetch zeros.  Offsets that start at OOB
+// stay >= OOB (spans are < 2^31 bytes).  Branch-free.
+template <bool KM>
+FOG_DEVICE void issue_piece(const LoadPlan& p, int j, v4i rsrc, int k0, uint32_t lds_piece_addr) {
+  const bool ok = (KM || j < p.jlim) && (k0 + (KM ? 4 * j : 0) < p.klim[j & 1]);
+  load_to_lds(rsrc, ok ? p.off[j & 1] + (uint32_t)(j >> 1) * p.stride2 : OOB, lds_piece_addr);
+}
+FOG_DEVICE void advance(LoadPlan& p) {
+  p.off[0] += p.step;
+  p.off[1] += p.step;
 }
 
 // ---- LDS -> MFMA operand fragments (32 rows x 64 contraction bytes; 32 bytes per lane) ----
-// Per-lane byte offsets inside an operand tile, computed once; tile i / read r / stage are added as
-// compile-time constants so that they fold into the instructions' immediate offsets.
+// Per-lane byte offsets inside an operand's pair stage, computed once; tile i / read r / K-step
+// half / stage are added as compile-time constants so that they fold into the instructions'
+// immediate offsets.
 struct FragAddr {
   uint32_t a[4];
 };
-// K-contiguous: a[0], a[1] = the two 16-byte chunks of row (l & 31); row tile i adds 2048 i.
+// K-contiguous: a[2 h], a[2 h + 1] = the two 16-byte chunks of row (l & 31) for the K-step half h;
+// row tile i adds 4096 i.
 FOG_DEVICE FragAddr fragaddr_kc(int row_base) {
   const int l = threadIdx.x & 63;
   const int row = row_base + (l & 31);   // row_base is a multiple of 32: the swizzle key is tile-independent
-  const int s = (row >> 2) & 3;
-  const int c = 2 * (l >> 5);
+  const int s = (row >> 1) & 7;
   FragAddr f;
-  f.a[0] = row * BK + ((c ^ s) << 4);
-  f.a[1] = row * BK + (((c + 1) ^ s) << 4);
-  f.a[2] = f.a[3] = 0;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int c = 4 * h + 2 * (l >> 5);
+    f.a[2 * h] = row * PAIR_K + ((c ^ s) << 4);
+    f.a[2 * h + 1] = row * PAIR_K + (((c + 1) ^ s) << 4);
+  }
   return f;
 }
-// K-major: a[j] = address of this lane's 8-byte piece for column tile j, read 0; read r adds 2048 r.
+// K-major: a[j] = address of this lane's 8-byte piece for column tile j, read 0 of the first K-step
+// of the pair; read r adds 2048 r, the second K-step adds 16384.
 // Within a block of 16 lanes the transposing read hands lane i the bytes (i & 7) of the rows addressed
 // by lanes 2 jj + (i >> 3), jj = 0..7.  Lane p therefore points at contraction row kbase + p / 2 and at
 // the 8-byte column group p % 2, which gives lane i column col + i.
 FOG_DEVICE FragAddr fragaddr_km(int col_base) {
   const int l = threadIdx.x & 63;
   const int i = l & 15;
-  const int k = 32 * (l >> 5) + (i >> 1);   // + 8 r: the swizzle key k & 7 does not depend on r
+  const int k = 32 * (l >> 5) + (i >> 1);   // + 8 r (+ 64): the swizzle key k & 7 does not depend on r
   FragAddr f;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -162,19 +187,20 @@ FOG_DEVICE FragAddr fragaddr_km(int col_base) {
   }
   return f;
 }
+// Fragment of row / column tile i for the K-step half h of the pair stage at `stage`.
 template <bool KM>
-FOG_DEVICE v8i read_frag(const uint8_t* tile, const FragAddr& fa, int i) {
+FOG_DEVICE v8i read_frag(const uint8_t* stage, const FragAddr& fa, int i, int h) {
   v8i f;
   if (KM) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      v2i v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(tile + fa.a[i] + 2048 * r));
+      v2i v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(stage + fa.a[i] + 16384 * h + 2048 * r));
       f[2 * r] = v[0];
       f[2 * r + 1] = v[1];
     }
   } else {
-    v4i lo = *reinterpret_cast<const v4i*>(tile + fa.a[0] + 2048 * i);
-    v4i hi = *reinterpret_cast<const v4i*>(tile + fa.a[1] + 2048 * i);
+    v4i lo = *reinterpret_cast<const v4i*>(stage + fa.a[2 * h] + 4096 * i);
+    v4i hi = *reinterpret_cast<const v4i*>(stage + fa.a[2 * h + 1] + 4096 * i);
     f[0] = lo[0]; f[1] = lo[1]; f[2] = lo[2]; f[3] = lo[3];
     f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3];
   }
@@ -230,7 +256,7 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
 
   const v4i rsrc_a = make_rsrc(g.A, g.a_bytes), rsrc_b = make_rsrc(g.B, g.b_bytes);
   // LDS byte address of this wave's first piece in stage 0 (wave-uniform, kept in a scalar register)
-  const uint32_t lds_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(uintptr_t)smem + 4096u * w));
+  const uint32_t lds_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(uintptr_t)smem + 8192u * w));
   const FragAddr fa_addr = A_KM ? fragaddr_km(wm) : fragaddr_kc(wm);
   const FragAddr fb_addr = B_KM ? fragaddr_km(wn) : fragaddr_kc(wn);
   const uint8_t* ring_a = smem + RING_A;
@@ -246,90 +272,93 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   const int nk = (g.K + BK - 1) / BK;
-  const int nk4 = (nk + 3) & ~3;  // steps are handled four at a time (one per LDS stage); steps past K multiply zeros
+  const int nk4 = (nk + 3) & ~3;  // steps are handled four at a time (two pair stages); steps past K multiply zeros
 
-#define FOG_ISSUE(kt, STAGE)                                                                       \
-  do {                                                                                             \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                \
-      issue_piece(pa, j, rsrc_a, (kt) * BK, lds_w + RING_A + (STAGE) * OPERAND_BYTES + 1024u * j); \
-      issue_piece(pb, j, rsrc_b, (kt) * BK, lds_w + RING_B + (STAGE) * OPERAND_BYTES + 1024u * j); \
-    }                                                                                              \
+#define FOG_LOAD_A(j, k0, ST) issue_piece<A_KM>(pa, j, rsrc_a, k0, lds_w + RING_A + (ST) * OPERAND_BYTES + 1024u * (j))
+#define FOG_LOAD_B(j, k0, ST) issue_piece<B_KM>(pb, j, rsrc_b, k0, lds_w + RING_B + (ST) * OPERAND_BYTES + 1024u * (j))
+#define FOG_ISSUE_PAIR(k0, ST)                                \
+  do {                                                        \
+    _Pragma("unroll") for (int j = 0; j < 8; ++j) {           \
+      FOG_LOAD_A(j, k0, ST);                                  \
+      FOG_LOAD_B(j, k0, ST);                                  \
+    }                                                         \
+    advance(pa); advance(pb);                                 \
   } while (0)
-#define FOG_READ(STAGE, FA_, FB_)                                                                        \
-  do {                                                                                                   \
-    const uint8_t* sa_ = ring_a + (STAGE) * OPERAND_BYTES;                                               \
-    const uint8_t* sb_ = ring_b + (STAGE) * OPERAND_BYTES;                                               \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) FA_[i] = read_frag<A_KM>(sa_, fa_addr, i);             \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j) FB_[j] = read_frag<B_KM>(sb_, fb_addr, j);             \
-  } while (0)
+#define FOG_RA(i, ST, H) read_frag<A_KM>(ring_a + (ST) * OPERAND_BYTES, fa_addr, i, H)
+#define FOG_RB(j, ST, H) read_frag<B_KM>(ring_b + (ST) * OPERAND_BYTES, fb_addr, j, H)
 #define FOG_MFMA(j, FAI_, FB_, i) \
   acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(FB_[j], FAI_, acc[i][j], FB, FA, 0, 0, 0, 0)
 #define FOG_FENCE() __builtin_amdgcn_sched_barrier(0)
-  // Wait until at most N of this thread's vector-memory operations are outstanding and its own
-  // fragment reads have returned, then synchronise: the awaited step is visible to every wave and
-  // the stage whose fragments were read during the previous step is free to be overwritten.
-  // The counter is decremented in issue order, so N = 16 (two K-steps of 8 loads) means "the step
-  // after the current one has landed".  Right after an epilogue the 32 output stores of the
-  // finished tile are outstanding too and younger than the loads that matter, so N = 48 for the
-  // first three steps of the next tile: the stores drain while that tile computes.
-  // s_waitcnt immediates: lgkmcnt = 0, expcnt unbounded, vmcnt = 16 (0x4070) or 48 (0xC070).
-#define FOG_WAIT_STEP(LAX)                                  \
-  do {                                                      \
-    if (LAX) __builtin_amdgcn_s_waitcnt(0xC070);            \
-    else     __builtin_amdgcn_s_waitcnt(0x4070);            \
-    __syncthreads();                                        \
-  } while (0)
-  // One K-step.  Past the barrier the stage of the step whose fragments are already in registers is
-  // free, so the loads four steps ahead go there (three K-steps stay in flight); the next step's
-  // fragments are fetched; this step's 16 MFMAs run on the fragments fetched one step earlier.
-  // The matrix core must not idle while the wave issues the 8 loads and 16 LDS reads, so they are
-  // dealt out between the MFMAs (each occupies the pipe for 64 cycles) and the order is pinned.
+  // One K-step = 16 MFMAs on the fragments fetched one step earlier, dealt out with the LDS reads
+  // of the next step's fragments and (second step of a pair) the 16 direct loads of the pair after
+  // next; the matrix core must not idle while the wave issues them, so the order is pinned.
   // Registers: the B fragments are double buffered (FB_CUR / FB_IN); the A fragments of rows 0..2
   // are refreshed in place as soon as their row of MFMAs has been issued, only row 3 has a second
-  // copy (A3_CUR / A3_IN), so that every read is issued at least four MFMAs before the step ends.
-#define FOG_STEP(kt_issue, ST_ISSUE, ST_READ, FB_IN, FB_CUR, A3_IN, A3_CUR, LAX)                                   \
-  do {                                                                                                             \
-    const uint8_t* sa_ = ring_a + (ST_READ) * OPERAND_BYTES;                                                        \
-    const uint8_t* sb_ = ring_b + (ST_READ) * OPERAND_BYTES;                                                        \
-    const uint32_t la_ = lds_w + RING_A + (ST_ISSUE) * OPERAND_BYTES, lb_ = lds_w + RING_B + (ST_ISSUE) * OPERAND_BYTES; \
-    const int k0_ = (kt_issue) * BK;                                                                                \
-    FOG_WAIT_STEP(LAX);                                                                                             \
-    FOG_FENCE(); FOG_MFMA(0, fa[0], FB_CUR, 0); FOG_FENCE();                                                        \
-    issue_piece(pa, 0, rsrc_a, k0_, la_);                                                                           \
-    FOG_FENCE(); FOG_MFMA(1, fa[0], FB_CUR, 0); FOG_FENCE();                                                        \
-    FB_IN[0] = read_frag<B_KM>(sb_, fb_addr, 0);                                                                    \
-    FOG_FENCE(); FOG_MFMA(2, fa[0], FB_CUR, 0); FOG_FENCE();                                                        \
-    issue_piece(pa, 1, rsrc_a, k0_, la_ + 1024u);                                                                   \
-    FOG_FENCE(); FOG_MFMA(3, fa[0], FB_CUR, 0); FOG_FENCE();                                                        \
-    FB_IN[1] = read_frag<B_KM>(sb_, fb_addr, 1);                                                                    \
-    FOG_FENCE(); FOG_MFMA(0, fa[1], FB_CUR, 1); FOG_FENCE();                                                        \
-    issue_piece(pa, 2, rsrc_a, k0_, la_ + 2048u);                                                                   \
-    fa[0] = read_frag<A_KM>(sa_, fa_addr, 0);                                                                       \
-    FOG_FENCE(); FOG_MFMA(1, fa[1], FB_CUR, 1); FOG_FENCE();                                                        \
-    FB_IN[2] = read_frag<B_KM>(sb_, fb_addr, 2);                                                                    \
-    FOG_FENCE(); FOG_MFMA(2, fa[1], FB_CUR, 1); FOG_FENCE();                                                        \
-    issue_piece(pa, 3, rsrc_a, k0_, la_ + 3072u);                                                                   \
-    FOG_FENCE(); FOG_MFMA(3, fa[1], FB_CUR, 1); FOG_FENCE();                                                        \
-    FB_IN[3] = read_frag<B_KM>(sb_, fb_addr, 3);                                                                    \
-    FOG_FENCE(); FOG_MFMA(0, fa[2], FB_CUR, 2); FOG_FENCE();                                                        \
-    issue_piece(pb, 0, rsrc_b, k0_, lb_);                                                                           \
-    fa[1] = read_frag<A_KM>(sa_, fa_addr, 1);                                                                       \
-    FOG_FENCE(); FOG_MFMA(1, fa[2], FB_CUR, 2); FOG_FENCE();                                                        \
-    A3_IN = read_frag<A_KM>(sa_, fa_addr, 3);                                                                       \
-    FOG_FENCE(); FOG_MFMA(2, fa[2], FB_CUR, 2); FOG_FENCE();                                                        \
-    issue_piece(pb, 1, rsrc_b, k0_, lb_ + 1024u);                                                                   \
-    FOG_FENCE(); FOG_MFMA(3, fa[2], FB_CUR, 2); FOG_FENCE();                                                        \
-    issue_piece(pb, 2, rsrc_b, k0_, lb_ + 2048u);                                                                   \
-    FOG_FENCE(); FOG_MFMA(0, A3_CUR, FB_CUR, 3); FOG_FENCE();                                                       \
-    fa[2] = read_frag<A_KM>(sa_, fa_addr, 2);                                                                       \
-    FOG_FENCE(); FOG_MFMA(1, A3_CUR, FB_CUR, 3); FOG_FENCE();                                                       \
-    issue_piece(pb, 3, rsrc_b, k0_, lb_ + 3072u);                                                                   \
-    FOG_FENCE(); FOG_MFMA(2, A3_CUR, FB_CUR, 3); FOG_MFMA(3, A3_CUR, FB_CUR, 3);                                    \
-    FOG_FENCE();                                                                                                    \
+  // copy (A3_CUR / A3_IN), so that every read is issued at least three MFMAs before the step ends.
+  // L(n) is the n-th of 16 load slots (empty in the first step of a pair).
+#define FOG_STEP_BODY(RST, RH, FB_IN, FB_CUR, A3_IN, A3_CUR, L)                                   \
+  do {                                                                                             \
+    FOG_FENCE(); FOG_MFMA(0, fa[0], FB_CUR, 0); FOG_FENCE();                                       \
+    L(0); FB_IN[0] = FOG_RB(0, RST, RH);                                                           \
+    FOG_FENCE(); FOG_MFMA(1, fa[0], FB_CUR, 0); FOG_FENCE();                                       \
+    L(1);                                                                                          \
+    FOG_FENCE(); FOG_MFMA(2, fa[0], FB_CUR, 0); FOG_FENCE();                                       \
+    L(2); FB_IN[1] = FOG_RB(1, RST, RH);                                                           \
+    FOG_FENCE(); FOG_MFMA(3, fa[0], FB_CUR, 0); FOG_FENCE();                                       \
+    L(3);                                                                                          \
+    FOG_FENCE(); FOG_MFMA(0, fa[1], FB_CUR, 1); FOG_FENCE();                                       \
+    L(4); fa[0] = FOG_RA(0, RST, RH);                                                              \
+    FOG_FENCE(); FOG_MFMA(1, fa[1], FB_CUR, 1); FOG_FENCE();                                       \
+    L(5); FB_IN[2] = FOG_RB(2, RST, RH);                                                           \
+    FOG_FENCE(); FOG_MFMA(2, fa[1], FB_CUR, 1); FOG_FENCE();                                       \
+    L(6);                                                                                          \
+    FOG_FENCE(); FOG_MFMA(3, fa[1], FB_CUR, 1); FOG_FENCE();                                       \
+    L(7); FB_IN[3] = FOG_RB(3, RST, RH);                                                           \
+    FOG_FENCE(); FOG_MFMA(0, fa[2], FB_CUR, 2); FOG_FENCE();                                       \
+    L(8); fa[1] = FOG_RA(1, RST, RH);                                                              \
+    FOG_FENCE(); FOG_MFMA(1, fa[2], FB_CUR, 2); FOG_FENCE();                                       \
+    L(9); A3_IN = FOG_RA(3, RST, RH);                                                              \
+    FOG_FENCE(); FOG_MFMA(2, fa[2], FB_CUR, 2); FOG_FENCE();                                       \
+    L(10);                                                                                         \
+    FOG_FENCE(); FOG_MFMA(3, fa[2], FB_CUR, 2); FOG_FENCE();                                       \
+    L(11);                                                                                         \
+    FOG_FENCE(); FOG_MFMA(0, A3_CUR, FB_CUR, 3); FOG_FENCE();                                      \
+    L(12); fa[2] = FOG_RA(2, RST, RH);                                                             \
+    FOG_FENCE(); FOG_MFMA(1, A3_CUR, FB_CUR, 3); FOG_FENCE();                                      \
+    L(13);                                                                                         \
+    FOG_FENCE(); FOG_MFMA(2, A3_CUR, FB_CUR, 3); FOG_FENCE();                                      \
+    L(14);                                                                                         \
+    FOG_FENCE(); FOG_MFMA(3, A3_CUR, FB_CUR, 3); FOG_FENCE();                                      \
+    L(15);                                                                                         \
+    FOG_FENCE();                                                                                   \
   } while (0)
+#define FOG_NO_LOAD(n) do { } while (0)
+  // First K-step of the pair in stage ST: the second half of that stage is read; nothing is loaded
+  // and nothing in LDS changes hands, so the waves do not synchronise (the compiler's own counters
+  // make each wave wait for its fragment reads).
+#define FOG_STEP_FIRST(ST, FB_IN, FB_CUR, A3_IN, A3_CUR) FOG_STEP_BODY(ST, 1, FB_IN, FB_CUR, A3_IN, A3_CUR, FOG_NO_LOAD)
+  // Second K-step of the pair in stage ST.  Wait until this thread's direct loads have landed and its
+  // fragment reads have returned, then synchronise: the pair in the other stage is visible to every
+  // wave and stage ST, read to the end during the previous step, is free.  Its refill (the pair that
+  // starts at contraction index K0_) is issued over the step, one load per MFMA, while the first
+  // half of the other stage is read.  Right after an epilogue the 32 output stores of the finished
+  // tile are outstanding too and younger than the loads that matter (the counter is decremented in
+  // issue order), so 32 operations may stay in flight: the stores drain while the next tile computes.
+  // s_waitcnt immediates: lgkmcnt = 0, expcnt unbounded, vmcnt = 0 (0x0070) or 32 (0x8070).
+#define FOG_STEP_SECOND(ST, K0_, FB_IN, FB_CUR, A3_IN, A3_CUR, LAX)                               \
+  do {                                                                                             \
+    const int k0_ = (K0_);                                                                         \
+    if (LAX) __builtin_amdgcn_s_waitcnt(0x8070);                                                   \
+    else     __builtin_amdgcn_s_waitcnt(0x0070);                                                   \
+    __syncthreads();                                                                               \
+    FOG_STEP_BODY(1 - (ST), 0, FB_IN, FB_CUR, A3_IN, A3_CUR, FOG_L##ST);                           \
+    advance(pa); advance(pb);                                                                      \
+  } while (0)
+#define FOG_L0(n) do { if ((n) < 8) FOG_LOAD_A((n), k0_, 0); else FOG_LOAD_B((n) - 8, k0_, 0); } while (0)
+#define FOG_L1(n) do { if ((n) < 8) FOG_LOAD_A((n), k0_, 1); else FOG_LOAD_B((n) - 8, k0_, 1); } while (0)
 
   // The load stream runs ahead of the MFMAs across tile boundaries: during the last four steps of a
-  // tile the first four steps of the workgroup's next tile are already being fetched, so a new tile
+  // tile the first two pairs of the workgroup's next tile are already being fetched, so a new tile
   // starts with its data in LDS and its first fragments in registers, and the epilogue's stores
   // drain while the next tile computes.
   int m0, n0;
@@ -337,13 +366,15 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
   LoadPlan pa = A_KM ? plan_km(g.lda, m0, g.M, g.K) : plan_kc(g.lda, m0, g.M, g.K);
   LoadPlan pb = B_KM ? plan_km(g.ldb, n0, g.N, g.K) : plan_kc(g.ldb, n0, g.N, g.K);
   v8i fa[4], fa3, xb[4], yb[4];   // A fragments (row 3 twice), B fragments twice
-  FOG_ISSUE(0, 0);
-  FOG_ISSUE(1, 1);
-  FOG_ISSUE(2, 2);
-  FOG_ISSUE(3, 3);
-  __builtin_amdgcn_s_waitcnt(0x4F78);  // vmcnt = 24: step 0 has landed
+  FOG_ISSUE_PAIR(0, 0);
+  FOG_ISSUE_PAIR(PAIR_K, 1);
+  __builtin_amdgcn_s_waitcnt(0x4F70);  // vmcnt = 16: the first pair has landed
   __syncthreads();
-  FOG_READ(0, fa, xb);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    fa[i] = FOG_RA(i, 0, 0);
+    xb[i] = FOG_RB(i, 0, 0);
+  }
 
   uint8_t* epi = smem + RING_BYTES + w * EPI_BYTES;  // this wave's private staging area
   bool stores_pending = false;                        // uniform: an epilogue's stores may still be in flight
@@ -359,19 +390,17 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
           pa = A_KM ? plan_km(g.lda, m0, g.M, g.K) : plan_kc(g.lda, m0, g.M, g.K);
           pb = B_KM ? plan_km(g.ldb, n0, g.N, g.K) : plan_kc(g.ldb, n0, g.N, g.K);
         } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) pa.off[j] = pb.off[j] = OOB;
+          pa.off[0] = pa.off[1] = pb.off[0] = pb.off[1] = OOB;
         }
       }
-      const int ki = kt == nk4 - 4 ? 0 : kt + 4;  // K-step number (within its tile) of the first load issued below
-      FOG_STEP(ki + 0, 0, 1, yb, xb, fa3, fa[3], stores_pending);
-      FOG_STEP(ki + 1, 1, 2, xb, yb, fa[3], fa3, stores_pending);
-      FOG_STEP(ki + 2, 2, 3, yb, xb, fa3, fa[3], stores_pending);
-      FOG_STEP(ki + 3, 3, 0, xb, yb, fa[3], fa3, false);
+      const int ki = kt == nk4 - 4 ? 0 : kt + 4;  // K-step number (within its tile) of the first pair issued below
+      FOG_STEP_FIRST(0, yb, xb, fa3, fa[3]);
+      FOG_STEP_SECOND(0, ki * BK, xb, yb, fa[3], fa3, stores_pending);
+      FOG_STEP_FIRST(1, yb, xb, fa3, fa[3]);
+      FOG_STEP_SECOND(1, ki * BK + PAIR_K, xb, yb, fa[3], fa3, false);
       stores_pending = false;
     }
     // fa, xb now hold step 0 of the next tile.
-
     // Epilogue.  With B as the first MFMA operand, lane l holds for tile (i, j), register r:
     //   row    m = m_cur + wm + 32 i + (l & 31)
     //   column n = n_cur + wn + 32 j + 8 (r / 4) + 4 (l / 32) + (r % 4)
@@ -417,12 +446,19 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
     if (!fast) __builtin_amdgcn_s_waitcnt(0x0F70);
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
-#undef FOG_ISSUE
-#undef FOG_READ
+#undef FOG_LOAD_A
+#undef FOG_LOAD_B
+#undef FOG_ISSUE_PAIR
+#undef FOG_RA
+#undef FOG_RB
 #undef FOG_MFMA
 #undef FOG_FENCE
-#undef FOG_WAIT_STEP
-#undef FOG_STEP
+#undef FOG_STEP_BODY
+#undef FOG_NO_LOAD
+#undef FOG_STEP_FIRST
+#undef FOG_STEP_SECOND
+#undef FOG_L0
+#undef FOG_L1
 }
 
 // C = 0 for K == 0 (no contraction): bf16 zeros.
