@@ -43,9 +43,10 @@ constexpr int OPERAND_BYTES = 256 * PAIR_K;  // 32 KB per operand and pair stage
 // of the LDS instructions and one address register per operand serves both stages.
 constexpr int RING_A = 0, RING_B = 2 * OPERAND_BYTES;
 constexpr int RING_BYTES = 4 * OPERAND_BYTES;  // 131072
-constexpr int EPI_STRIDE = 128 + 16;          // epilogue staging: 32 rows x 64 bf16 per wave, padded rows
-constexpr int EPI_BYTES = 32 * EPI_STRIDE;    // per wave
-constexpr int LDS_BYTES = RING_BYTES + 4 * EPI_BYTES;  // 149504
+constexpr int EPI_STRIDE = 64 + 16;           // epilogue staging: 32 rows x 32 bf16, padded rows
+constexpr int EPI_BUF = 32 * EPI_STRIDE;      // one staged block
+constexpr int EPI_BYTES = 2 * EPI_BUF;        // per wave: two blocks
+constexpr int LDS_BYTES = RING_BYTES + 4 * EPI_BYTES;  // 151552
 constexpr uint32_t OOB = 0x80000000u;        // a buffer offset past any operand (spans are < 2^31 bytes)
 
 struct GemmArgs {
@@ -404,44 +405,66 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
     // Epilogue.  With B as the first MFMA operand, lane l holds for tile (i, j), register r:
     //   row    m = m_cur + wm + 32 i + (l & 31)
     //   column n = n_cur + wn + 32 j + 8 (r / 4) + 4 (l / 32) + (r % 4)
-    // Each 32 x 64 block is scaled, converted to bf16, parked in the wave's LDS area and written out
-    // as 16-byte pieces, eight lanes per 128-byte row segment: 32 fully coalesced stores per lane.
+    // Each 32 x 32 block is scaled, converted to bf16, parked in one of the wave's two LDS staging
+    // buffers (alternating, so that the next block is converted while this one is written out) and
+    // stored as 16-byte pieces, four lanes per 64-byte row segment: 32 coalesced stores per lane.
     const bool fast = g.vec_store != 0 && m_cur + BM <= g.M && n_cur + BN <= g.N;
+    const int prow = l >> 2, piece = l & 3;   // this lane's row (+ 16 t) and 16-byte piece of a staged block
+    if (fast) {
+      uint16_t* cbase = g.C + (int64_t)(m_cur + wm + prow) * g.ldc + (n_cur + wn + 8 * piece);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < 4; ++i) {
 #pragma unroll
-      for (int half = 0; half < 2; ++half) {
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-          const int j = 2 * half + jj;
+        for (int j = 0; j < 4; ++j) {
+          uint8_t* buf = epi + ((i * 4 + j) & 1) * EPI_BUF;
 #pragma unroll
           for (int qd = 0; qd < 4; ++qd) {
             const float v0 = acc[i][j][4 * qd + 0] * alpha, v1 = acc[i][j][4 * qd + 1] * alpha;
             const float v2 = acc[i][j][4 * qd + 2] * alpha, v3 = acc[i][j][4 * qd + 3] * alpha;
-            acc[i][j][4 * qd + 0] = 0.0f; acc[i][j][4 * qd + 1] = 0.0f;
-            acc[i][j][4 * qd + 2] = 0.0f; acc[i][j][4 * qd + 3] = 0.0f;
-            const int ncol = 32 * jj + 8 * qd + 4 * (l >> 5);  // column inside the 64-wide block
-            *reinterpret_cast<uint2*>(epi + (l & 31) * EPI_STRIDE + 2 * ncol) = make_uint2(cvt_pk_bf16(v0, v1), cvt_pk_bf16(v2, v3));
+            *reinterpret_cast<uint2*>(buf + (l & 31) * EPI_STRIDE + 16 * qd + 8 * (l >> 5)) = make_uint2(cvt_pk_bf16(v0, v1), cvt_pk_bf16(v2, v3));
+          }
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            const uint4 v = *reinterpret_cast<const uint4*>(buf + (16 * t + prow) * EPI_STRIDE + 16 * piece);
+            *reinterpret_cast<uint4*>(cbase + (int64_t)(32 * i + 16 * t) * g.ldc + 32 * j) = v;
           }
         }
+      }
+    } else {
+      // edge tiles and unaligned C: the same staging, element-wise guarded stores
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int row = 8 * t + (l >> 3), piece = l & 7;  // 8 lanes cover one 128-byte row segment
-          const uint4 v = *reinterpret_cast<const uint4*>(epi + row * EPI_STRIDE + 16 * piece);
-          const int m = m_cur + wm + 32 * i + row;
-          const int n = n_cur + wn + 64 * half + 8 * piece;
-          uint16_t* dst = g.C + (int64_t)m * g.ldc + n;
-          if (fast) {
-            *reinterpret_cast<uint4*>(dst) = v;
-          } else if (m < g.M) {
-            const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+      for (int i = 0; i < 4; ++i) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-              if (n + e < g.N) dst[e] = (uint16_t)(wv[e >> 1] >> (16 * (e & 1)));
+        for (int j = 0; j < 4; ++j) {
+          uint8_t* buf = epi + ((i * 4 + j) & 1) * EPI_BUF;
+#pragma unroll
+          for (int qd = 0; qd < 4; ++qd) {
+            const float v0 = acc[i][j][4 * qd + 0] * alpha, v1 = acc[i][j][4 * qd + 1] * alpha;
+            const float v2 = acc[i][j][4 * qd + 2] * alpha, v3 = acc[i][j][4 * qd + 3] * alpha;
+            *reinterpret_cast<uint2*>(buf + (l & 31) * EPI_STRIDE + 16 * qd + 8 * (l >> 5)) = make_uint2(cvt_pk_bf16(v0, v1), cvt_pk_bf16(v2, v3));
+          }
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            const uint4 v = *reinterpret_cast<const uint4*>(buf + (16 * t + prow) * EPI_STRIDE + 16 * piece);
+            const int m = m_cur + wm + 32 * i + 16 * t + prow;
+            const int n = n_cur + wn + 32 * j + 8 * piece;
+            if (m < g.M) {
+              uint16_t* dst = g.C + (int64_t)m * g.ldc + n;
+              const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (n + e < g.N) dst[e] = (uint16_t)(wv[e >> 1] >> (16 * (e & 1)));
+            }
           }
         }
       }
     }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
     stores_pending = fast;  // the slow path is only taken by edge tiles; its stores are simply waited for
     if (!fast) __builtin_amdgcn_s_waitcnt(0x0F70);
   }
