@@ -101,11 +101,33 @@ fog_status fog_scale_delayed(float* history, int len, const float* new_amax, fog
  * The fast path needs cols % 16 == 0 (rows % 16 == 0 too when qT is given), 16-byte aligned
  * pointers and leading dimensions that are multiples of 16; other shapes take a slower
  * general kernel with identical results.
- * Errors: NULL x / scale / both outputs, negative sizes or ld < row length (SHAPE).
+ * Errors: NULL scale, NULL x or both outputs NULL for a non-empty input, negative sizes or
+ * ld < row length (SHAPE).
  */
 fog_status fog_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, fog_fp8 fmt,
                         const float* scale, uint8_t* q, int64_t ldq, uint8_t* qT, int64_t ldqT,
                         float* amax_out, void* stream);
+
+/*
+ * Just-in-time scaling in one call (Section 2: abs-max of the tensor being cast, then the cast;
+ * Appendix E for the scale): the same results, bit for bit, as fog_amax -> fog_scale -> fog_quantize,
+ * in two launches instead of four.  The abs-max pass ends in the workgroup that finishes last,
+ * which derives the scale; the cast pass follows on the same stream.  Meant for small tensors,
+ * where launches dominate: every workgroup of the abs-max pass ends with a device-wide fence, so on
+ * tensors of tens of megabytes the three separate calls are the faster route.
+ *   amax, scale : one float each, overwritten.   scale_inv : one float or NULL.
+ *   q, qT, x_bf16, leading dimensions, fmt : as in fog_quantize.   margin : as in fog_scale.
+ *   workspace : fog_quantize_jit_workspace() bytes, 4-byte aligned, owned by the caller.  It must
+ *               hold zeros before the first call; every call leaves it zeroed, so one workspace
+ *               serves any number of calls that do not overlap in time (calls on different
+ *               streams need one each).
+ * Errors: as fog_quantize and fog_scale; WORKSPACE when the workspace is too small.
+ */
+fog_status fog_quantize_jit(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, fog_fp8 fmt, int margin,
+                            uint8_t* q, int64_t ldq, uint8_t* qT, int64_t ldqT,
+                            float* amax, float* scale, float* scale_inv,
+                            void* workspace, size_t workspace_bytes, void* stream);
+size_t fog_quantize_jit_workspace(void);
 
 /*
  * Activation kurtosis, the paper's outlier diagnostic (Section 4): for each token vector x (a row),

@@ -35,10 +35,13 @@ class Cast:
         self.amax = torch.zeros(1, device="cuda")
         self.scale = torch.ones(1, device="cuda")
         self.sinv = torch.ones(1, device="cuda")
+        self.ws = torch.zeros(2, dtype=torch.int32, device="cuda")   # for run_jit: zeroed once, every call leaves it zeroed
         self.bytes_amax = 2 * rows * cols
         self.bytes_cast = (3 + (1 if transpose else 0)) * rows * cols
 
     def run(self, timer=None):
+        """Just-in-time scaling through the three calls: abs-max, scale, cast.  On large tensors this is
+        faster than the one-call form, whose abs-max pass ends every workgroup with a device-wide fence."""
         if timer:
             timer.begin("amax", self.bytes_amax)
         fog.amax(self.x, self.amax)
@@ -50,6 +53,10 @@ class Cast:
         fog.quantize(self.x, self.fmt, self.scale, q=self.q, qT=self.qT)
         if timer:
             timer.end()
+
+    def run_jit(self):
+        """The same flow in one call (two launches instead of four)."""
+        fog.quantize_jit(self.x, self.fmt, self.amax, self.scale, self.sinv, self.ws, q=self.q, qT=self.qT)
 
 
 class LinearStep:
@@ -150,16 +157,21 @@ class Block:
 class EventTimer:
     """Per-kernel-class HIP-event timing on the stream the library launches on (torch's current stream)."""
 
-    def __init__(self):
+    def __init__(self, only=None):
         self.spans = []
         self._open = None
+        self.only = only        # None: every kind; else the set of kinds to record (events cost time themselves)
 
     def begin(self, kind, work):
+        if self.only is not None and kind not in self.only:
+            return
         e0 = torch.cuda.Event(enable_timing=True)
         e0.record()
         self._open = (kind, work, e0)
 
     def end(self):
+        if self._open is None:
+            return
         kind, work, e0 = self._open
         e1 = torch.cuda.Event(enable_timing=True)
         e1.record()

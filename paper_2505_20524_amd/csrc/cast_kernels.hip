@@ -17,23 +17,70 @@ __global__ void zero_u32_kernel(uint32_t* p) { *p = 0u; }
 // ---------------------------------------------------------------- abs-max
 // bf16 magnitudes order like unsigned 16-bit integers, so the running maximum is a packed
 // u16 max over the sign-cleared bit patterns; the result is the float whose upper half is it.
+//
+// JIT: the just-in-time flow in one launch.  `out` is then a zero-initialised accumulator in the
+// caller's workspace, followed by a ticket counter; the workgroup that draws the last ticket has
+// the final maximum, derives the scale from it, publishes abs-max / scale / 1/scale and puts the
+// two workspace words back to zero for the next call.
+FOG_DEVICE void scale_from_amax(float a, int fmt, int margin, float* scale, float* scale_inv);
+struct JitOut {
+  float* amax;
+  float* scale;
+  float* scale_inv;
+  int fmt, margin;
+};
+FOG_DEVICE void publish_block_max(uint32_t r, uint32_t* out, bool jit, const JitOut& j) {
+  // same-address atomics are served one at a time: skip the ones that cannot raise the maximum
+  if (r && (r << 16) > __hip_atomic_load(out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(out, r << 16);
+  if (!jit) return;
+  __threadfence();
+  if (atomicAdd(out + 1, 1u) == gridDim.x - 1) {
+    __threadfence();
+    const float a = __uint_as_float(atomicExch(out, 0u));
+    atomicExch(out + 1, 0u);
+    *j.amax = a;
+    scale_from_amax(a, j.fmt, j.margin, j.scale, j.scale_inv);
+  }
+}
+
+template <bool JIT>
 __global__ __launch_bounds__(kThreads) void amax_kernel(const uint4* __restrict__ x, int64_t nvec,
                                                         const uint16_t* __restrict__ tail, int ntail,
-                                                        uint32_t* __restrict__ out) {
-  const int64_t stride = (int64_t)gridDim.x * kThreads;
-  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+                                                        uint32_t* __restrict__ out, JitOut jit) {
+  // Every workgroup owns one contiguous span and walks it in batches of eight 16-byte loads per
+  // thread; the next batch is requested before the current one is reduced, so loads never stop.
+  constexpr int NL = 8;
+  const int64_t per = (nvec + gridDim.x - 1) / gridDim.x;
+  const int64_t b0 = per * blockIdx.x, b1 = b0 + per < nvec ? b0 + per : nvec;
   uint32_t m[4] = {0, 0, 0, 0};
-  for (; i + 7 * stride < nvec; i += 8 * stride) {   // eight 16-byte loads in flight per thread
-    uint4 v[8];
+  int64_t i = b0 + threadIdx.x;
+  uint4 v[NL];
+  bool have = i + (NL - 1) * kThreads < b1;
+  if (have) {
 #pragma unroll
-    for (int k = 0; k < 8; ++k) v[k] = ld_nt16(x + i + k * stride);
+    for (int k = 0; k < NL; ++k) v[k] = ld_nt16(x + i + k * kThreads);
+  }
+  while (have) {
+    const int64_t n = i + NL * kThreads;
+    const bool more = n + (NL - 1) * kThreads < b1;
+    uint4 nx[NL];
+    if (more) {
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
+      for (int k = 0; k < NL; ++k) nx[k] = ld_nt16(x + n + k * kThreads);
+    }
+#pragma unroll
+    for (int k = 0; k < NL; ++k) {
       m[0] = pkmax_abs_bf16(m[0], v[k].x); m[1] = pkmax_abs_bf16(m[1], v[k].y);
       m[2] = pkmax_abs_bf16(m[2], v[k].z); m[3] = pkmax_abs_bf16(m[3], v[k].w);
     }
+    if (more) {
+#pragma unroll
+      for (int k = 0; k < NL; ++k) v[k] = nx[k];
+    }
+    i = n;
+    have = more;
   }
-  for (; i < nvec; i += stride) {
+  for (; i < b1; i += kThreads) {
     uint4 a = ld_nt16(x + i);
     m[0] = pkmax_abs_bf16(m[0], a.x); m[1] = pkmax_abs_bf16(m[1], a.y);
     m[2] = pkmax_abs_bf16(m[2], a.z); m[3] = pkmax_abs_bf16(m[3], a.w);
@@ -52,7 +99,30 @@ __global__ __launch_bounds__(kThreads) void amax_kernel(const uint4* __restrict_
     uint32_t r = part[0];
 #pragma unroll
     for (int w = 1; w < kThreads / 64; ++w) r = r > part[w] ? r : part[w];
-    if (r) atomicMax(out, r << 16);
+    publish_block_max(r, out, JIT, jit);
+  }
+}
+
+// Abs-max of a matrix whose rows are not contiguous or not 16-byte aligned (slow, same result).
+template <bool JIT>
+__global__ __launch_bounds__(kThreads) void amax_strided_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                                int64_t ldx, uint32_t* __restrict__ out, JitOut jit) {
+  const int64_t total = rows * cols;
+  uint32_t m = 0;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
+    const int64_t r = i / cols, c = i - r * cols;
+    const uint32_t a = x[r * ldx + c] & 0x7FFFu;
+    m = m > a ? m : a;
+  }
+  m = wave_max_u32(m);
+  __shared__ uint32_t part[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t r = part[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) r = r > part[w] ? r : part[w];
+    publish_block_max(r, out, JIT, jit);
   }
 }
 
@@ -298,9 +368,9 @@ extern "C" fog_status fog_amax(const void* x_bf16, int64_t n, float* amax, void*
     int64_t blocks = (nvec + kThreads * 8 - 1) / (kThreads * 8);
     if (blocks > 1024) blocks = 1024;   // 4 workgroups per CU; one atomic per workgroup
     if (blocks < 1) blocks = 1;
-    amax_kernel<<<(int)blocks, kThreads, 0, s>>>(reinterpret_cast<const uint4*>(x_bf16), nvec,
-                                                 reinterpret_cast<const uint16_t*>(x_bf16) + nvec * 8, ntail,
-                                                 reinterpret_cast<uint32_t*>(amax));
+    amax_kernel<false><<<(int)blocks, kThreads, 0, s>>>(reinterpret_cast<const uint4*>(x_bf16), nvec,
+                                                        reinterpret_cast<const uint16_t*>(x_bf16) + nvec * 8, ntail,
+                                                        reinterpret_cast<uint32_t*>(amax), JitOut{});
   }
   return fog_launch_status();
 }
@@ -356,25 +426,72 @@ static void launch_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64
   quantize_general_kernel<FMT><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, amax_out);
 }
 
-extern "C" fog_status fog_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, fog_fp8 fmt,
-                                   const float* scale, uint8_t* q, int64_t ldq, uint8_t* qT, int64_t ldqT,
-                                   float* amax_out, void* stream) {
-  if (!scale || (!q && !qT)) return FOG_ERR_NULL;
+static fog_status quantize_checks(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, fog_fp8 fmt,
+                                  const uint8_t* q, int64_t ldq, const uint8_t* qT, int64_t ldqT) {
   if (rows < 0 || cols < 0) return FOG_ERR_SHAPE;
   if (fmt != FOG_E4M3 && fmt != FOG_E5M2) return FOG_ERR_UNSUPPORTED;
-  hipStream_t s = (hipStream_t)stream;
-  const bool empty = rows == 0 || cols == 0;
-  if (!empty) {
-    if (!x_bf16) return FOG_ERR_NULL;
+  if (rows != 0 && cols != 0) {
+    if (!x_bf16 || (!q && !qT)) return FOG_ERR_NULL;
     if (ldx < cols || (q && ldq < cols) || (qT && ldqT < rows)) return FOG_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(x_bf16) & 1u) != 0) return FOG_ERR_ALIGN;
   }
+  return FOG_OK;
+}
+
+extern "C" fog_status fog_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, fog_fp8 fmt,
+                                   const float* scale, uint8_t* q, int64_t ldq, uint8_t* qT, int64_t ldqT,
+                                   float* amax_out, void* stream) {
+  if (!scale) return FOG_ERR_NULL;
+  const fog_status st = quantize_checks(x_bf16, rows, cols, ldx, fmt, q, ldq, qT, ldqT);
+  if (st != FOG_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
   if (amax_out) zero_u32_kernel<<<1, 1, 0, s>>>(reinterpret_cast<uint32_t*>(amax_out));
-  if (!empty) {
+  if (rows != 0 && cols != 0) {
     const uint16_t* x = reinterpret_cast<const uint16_t*>(x_bf16);
     uint32_t* am = reinterpret_cast<uint32_t*>(amax_out);
     if (fmt == FOG_E4M3) launch_quantize<FOG_E4M3>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, am, s);
     else                 launch_quantize<FOG_E5M2>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, am, s);
   }
+  return fog_launch_status();
+}
+
+extern "C" size_t fog_quantize_jit_workspace(void) { return 2 * sizeof(uint32_t); }
+
+extern "C" fog_status fog_quantize_jit(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, fog_fp8 fmt, int margin,
+                                       uint8_t* q, int64_t ldq, uint8_t* qT, int64_t ldqT,
+                                       float* amax, float* scale, float* scale_inv,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (!amax || !scale || !workspace) return FOG_ERR_NULL;
+  if (workspace_bytes < fog_quantize_jit_workspace()) return FOG_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 3u) != 0) return FOG_ERR_ALIGN;
+  if (margin < -64 || margin > 64) return FOG_ERR_SHAPE;
+  const fog_status st = quantize_checks(x_bf16, rows, cols, ldx, fmt, q, ldq, qT, ldqT);
+  if (st != FOG_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  const uint16_t* x = reinterpret_cast<const uint16_t*>(x_bf16);
+  uint32_t* ws = reinterpret_cast<uint32_t*>(workspace);
+  const JitOut jit{amax, scale, scale_inv, (int)fmt, margin};
+  const int64_t n = rows * cols;
+  if (n == 0) {
+    // nothing to scan: abs-max 0, scale 1 (one workgroup draws the only ticket)
+    amax_strided_kernel<true><<<1, kThreads, 0, s>>>(x, 0, 1, 1, ws, jit);
+    return fog_launch_status();
+  }
+  if ((ldx == cols || rows == 1) && aligned16(x_bf16)) {
+    const int64_t nvec = n / 8;
+    const int ntail = (int)(n - nvec * 8);
+    int64_t blocks = (nvec + kThreads * 8 - 1) / (kThreads * 8);
+    // fewer workgroups than fog_amax: each one ends with a device-wide fence and a ticket, which cost
+    // more than the scan gains from a wider launch
+    if (blocks > 512) blocks = 512;
+    if (blocks < 1) blocks = 1;
+    amax_kernel<true><<<(int)blocks, kThreads, 0, s>>>(reinterpret_cast<const uint4*>(x), nvec, x + nvec * 8, ntail, ws, jit);
+  } else {
+    int64_t blocks = (n + kThreads - 1) / kThreads;
+    if (blocks > 4096) blocks = 4096;
+    amax_strided_kernel<true><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, ws, jit);
+  }
+  if (fmt == FOG_E4M3) launch_quantize<FOG_E4M3>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, nullptr, s);
+  else                 launch_quantize<FOG_E5M2>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, nullptr, s);
   return fog_launch_status();
 }

@@ -26,6 +26,8 @@ SIGNATURES = {
     "fog_scale": (_I, [_P, _I, _I, _P, _P, _P]),
     "fog_scale_delayed": (_I, [_P, _I, _P, _I, _I, _P, _P, _P]),
     "fog_quantize": (_I, [_P, _I64, _I64, _I64, _I, _P, _P, _I64, _P, _I64, _P, _P]),
+    "fog_quantize_jit": (_I, [_P, _I64, _I64, _I64, _I, _I, _P, _I64, _P, _I64, _P, _P, _P, _P, _SZ, _P]),
+    "fog_quantize_jit_workspace": (_SZ, []),
     "fog_kurtosis": (_I, [_P, _I64, _I64, _I64, _P, _P]),
     "fog_fp8_gemm": (_I, [_I, _I64, _I64, _I64, _P, _I, _I64, _P, _P, _I, _I64, _P, _P, _I64, _P, _SZ, _P]),
     "fog_fp8_gemm_workspace": (_SZ, [_I, _I64, _I64, _I64]),
@@ -92,6 +94,20 @@ def quantize(x, fmt, scale_t, q=None, qT=None, amax_out=None, stream=None):
                                _ptr(q), q.stride(0) if q is not None else 0,
                                _ptr(qT), qT.stride(0) if qT is not None else 0,
                                _ptr(amax_out), _stream(stream)), "fog_quantize")
+
+
+def quantize_jit(x, fmt, amax_out, scale_out, scale_inv_out, workspace, q=None, qT=None, margin=0, stream=None):
+    rows, cols = x.shape
+    _check(load().fog_quantize_jit(_ptr(x), rows, cols, x.stride(0), fmt, margin,
+                                   _ptr(q), q.stride(0) if q is not None else 0,
+                                   _ptr(qT), qT.stride(0) if qT is not None else 0,
+                                   _ptr(amax_out), _ptr(scale_out), _ptr(scale_inv_out),
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "fog_quantize_jit")
+
+
+def quantize_jit_workspace():
+    return load().fog_quantize_jit_workspace()
 
 
 def kurtosis(x, out, stream=None):

@@ -151,3 +151,56 @@ def test_argument_errors():
     assert lib.fog_quantize(x.data_ptr(), 4, 16, 16, 0, out.data_ptr(), None, 0, None, 0, None, st) == 1
     assert lib.fog_quantize(x.data_ptr(), 4, 16, 16, 7, out.data_ptr(), q.data_ptr(), 16, None, 0, None, st) == 4
     assert lib.fog_scale(None, 0, 0, out.data_ptr(), None, st) == 1
+
+
+@pytest.mark.parametrize("fmt", [fp8.E4M3, fp8.E5M2])
+@pytest.mark.parametrize("rows,cols,pad,transpose", [
+    (256, 512, 0, True), (128, 1024, 0, False), (272, 336, 0, True), (33, 100, 0, True), (5, 17, 3, False),
+    (64, 128, 16, True), (1, 8, 0, False), (2048, 4096, 0, True), (0, 64, 0, False)])
+def test_quantize_jit_matches_oracle_and_separate_calls(fmt, rows, cols, pad, transpose):
+    """The one-call just-in-time flow: abs-max, scale, 1/scale and codes equal the oracle's bit for bit,
+    and the caller's workspace is left zeroed so that it can be reused (three calls, one workspace)."""
+    rng = np.random.default_rng(rows * 7 + cols + fmt)
+    ws = torch.zeros(2, dtype=torch.int32, device="cuda")
+    for call in range(3):
+        x = (rng.standard_normal((rows, cols + pad)) * 10.0 ** rng.uniform(-3, 3)).astype(np.float32)
+        if rows and call == 1:
+            x[rows // 2, cols // 3] = -7.5e4                   # the maximum sits in the last-but-one call only
+        xb = synth.f32_to_bf16_bits(x)
+        xd = dev(xb)[:, :cols] if pad else dev(xb)
+        am, s, si = (torch.full((1,), -1.0, device="cuda") for _ in range(3))
+        q = torch.full((rows, cols), 0xAA, dtype=torch.uint8, device="cuda")
+        qT = torch.full((cols, rows), 0xAA, dtype=torch.uint8, device="cuda") if transpose else None
+        fog.quantize_jit(xd, fmt, am, s, si, ws, q=q, qT=qT)
+        torch.cuda.synchronize()
+        assert ws.cpu().tolist() == [0, 0]
+        view = xb[:, :cols]
+        a = scaling.amax(view) if rows else np.float32(0.0)
+        rho, rinv = scaling.compute_scale(a, fmt)
+        assert np.float32(am.item()).tobytes() == np.float32(a).tobytes()
+        assert np.float32(s.item()).tobytes() == rho.tobytes() and np.float32(si.item()).tobytes() == rinv.tobytes()
+        if rows:
+            want = scaling.quantize(view, rho, fmt)
+            assert np.array_equal(q.cpu().numpy(), want)
+            if transpose:
+                assert np.array_equal(qT.cpu().numpy(), want.T)
+
+
+def test_quantize_jit_argument_errors():
+    lib = fog.load()
+    st = torch.cuda.current_stream().cuda_stream
+    x = torch.zeros((16, 16), dtype=torch.int16, device="cuda")
+    q = torch.zeros((16, 16), dtype=torch.uint8, device="cuda")
+    f = torch.zeros(3, device="cuda")
+    ws = torch.zeros(2, dtype=torch.int32, device="cuda")
+    a, s, si = f.data_ptr(), f.data_ptr() + 4, f.data_ptr() + 8
+    call = lambda *args: lib.fog_quantize_jit(*args)
+    assert lib.fog_quantize_jit_workspace() == 8
+    assert call(x.data_ptr(), 16, 16, 16, 0, 0, q.data_ptr(), 16, None, 0, a, s, si, ws.data_ptr(), 4, st) == 5
+    assert call(x.data_ptr(), 16, 16, 16, 0, 0, q.data_ptr(), 16, None, 0, a, s, si, None, 8, st) == 1
+    assert call(x.data_ptr(), 16, 16, 16, 0, 0, None, 0, None, 0, a, s, si, ws.data_ptr(), 8, st) == 1
+    assert call(x.data_ptr(), 16, 16, 8, 0, 0, q.data_ptr(), 16, None, 0, a, s, si, ws.data_ptr(), 8, st) == 2
+    assert call(x.data_ptr(), 16, 16, 16, 7, 0, q.data_ptr(), 16, None, 0, a, s, si, ws.data_ptr(), 8, st) == 4
+    assert call(x.data_ptr(), 16, 16, 16, 0, 99, q.data_ptr(), 16, None, 0, a, s, si, ws.data_ptr(), 8, st) == 2
+    assert call(x.data_ptr(), 16, 16, 16, 0, 0, q.data_ptr(), 16, None, 0, a, s, None, ws.data_ptr(), 8, st) == 0
+    torch.cuda.synchronize()
