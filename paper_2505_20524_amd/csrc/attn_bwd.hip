@@ -239,6 +239,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
     }
   };
 
+  FOG_SETTLE(kf[0]); FOG_SETTLE(kf[1]); FOG_SETTLE(vf[0]); FOG_SETTLE(vf[1]);
   issue(0);
   issue(1);
   issue(2);
@@ -247,7 +248,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
   v16f sa[2], da[2], sb[2], db[2];
   if (skip == 0 && nqb > 0) scores(0, sa, da);
 
-  auto block = [&](int i, v16f* st, v16f* dp, v16f* stn, v16f* dpn) {
+  auto block = [&](const bool CLAMP_P, int i, v16f* st, v16f* dp, v16f* stn, v16f* dpn) __attribute__((always_inline)) {
     __builtin_amdgcn_s_waitcnt(0x0075);  // vmcnt = 5: block i + 1 landed; lgkmcnt = 0: own LDS reads done
     __syncthreads();
     issue(i + 3);
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
             pq[b] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[qt][r], c, -lsv[b]));   // rho_p P
             ds[b] = pq[b] * __builtin_fmaf(dp[qt][r], cdpk, -ddv[b]);                 // rho_ds dS
           }
-          if (clamp_p) {
+          if (CLAMP_P) {
             pf[4 * qt + qd] = (int)cvt4_fp8<FOG_E4M3>(pq[0], pq[1], pq[2], pq[3]);
           } else {
             uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(pq[0], pq[1], 0u, false);
@@ -298,9 +299,18 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
       }
     }
   };
-  for (int i = 0; i < nqb; i += 2) {   // two blocks per trip so that the score registers just swap roles
-    block(i, sa, da, sb, db);
-    if (i + 1 < nqb) block(i + 1, sb, db, sa, da);
+  // The saturating form of the P cast is only needed for a scale above the format's maximum; the
+  // choice is made once, outside the loop, so that the loop body stays one straight-line block.
+  if (clamp_p) {
+    for (int i = 0; i < nqb; i += 2) {   // two blocks per trip so that the score registers just swap roles
+      block(true, i, sa, da, sb, db);
+      if (i + 1 < nqb) block(true, i + 1, sb, db, sa, da);
+    }
+  } else {
+    for (int i = 0; i < nqb; i += 2) {
+      block(false, i, sa, da, sb, db);
+      if (i + 1 < nqb) block(false, i + 1, sb, db, sa, da);
+    }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
   if (!wave_on) return;
@@ -373,6 +383,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(BwdArgs a) {
   const RowFrag rf = rowfrag_addr();
   const ColFrag cf = colfrag_addr();
 
+  FOG_SETTLE(qf[0]); FOG_SETTLE(qf[1]); FOG_SETTLE(dof[0]); FOG_SETTLE(dof[1]); FOG_SETTLE(lse); FOG_SETTLE(Dq);
   issue(0);
   issue(1);
   issue(2);

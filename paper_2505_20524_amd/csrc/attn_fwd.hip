@@ -177,6 +177,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
     }
   };
 
+  FOG_SETTLE(qf[0]); FOG_SETTLE(qf[1]);
   issue(0);
   issue(1);
   issue(2);

@@ -91,3 +91,11 @@ FOG_DEVICE void st_nt8(void* p, uint2 v) {
   u32x2 w = {v.x, v.y};
   __builtin_nontemporal_store(w, reinterpret_cast<u32x2*>(p));
 }
+
+// Makes the compiler treat `v` as used here.  Kernels that stream tiles into LDS with direct loads
+// issued from inline assembly wait for those loads with explicit s_waitcnt immediates; the
+// compiler does not see them, so any ordinary global load still "outstanding" in its bookkeeping
+// when the loop starts would make it put s_waitcnt vmcnt(0) inside the loop (where the value is
+// first used), which also waits for the whole prefetch stream.  Using every such value once
+// before the first direct load moves that wait in front of the loop.
+#define FOG_SETTLE(v) asm volatile("" ::"v"(v))
