@@ -169,14 +169,20 @@ size_t fog_fp8_gemm_workspace(fog_layout layout, int64_t M, int64_t N, int64_t K
  * m_i = ceil(max_j x_ij) (an integer, so that the cast of p is independent of the order in
  * which keys are visited); p = 2^(x - m_i); l_i = sum_j p_ij (binary32, p not cast);
  * P~ = sat_rne_E4M3(scale_p * p);  O = sinv_v (P~ V~) / (scale_p l_i);  lse_i = m_i + log2 l_i.
- *   Q, K, V : [B, H, S, D] contiguous E4M3 bytes;  D must be 128, S a multiple of 64.
+ * Grouped-query attention (Appendix B; the paper's models use 4 to 8 query groups): H_kv key/value
+ * heads serve H query heads, query head h reading key/value head h / (H / H_kv); H_kv == H is
+ * ordinary multi-head attention.
+ *   Q       : [B, H, S, D] contiguous E4M3 bytes;  D must be 128, S a multiple of 64 (any length
+ *             whose head, S * D bytes, stays below 2^31).
+ *   K, V    : [B, H_kv, S, D] contiguous E4M3 bytes;  H must be a multiple of H_kv.
  *   sinv_* : reciprocal scales of the casts, one float each.  scale_p: one float (p <= 1, so
  *            the paper's formula gives 448).
  *   O_bf16 : [B, H, S, D] bfloat16;  lse : [B, H, S] floats (log2 domain).
  *   amax_p : NULL or one float receiving max p (for a delayed scale_p).  Overwritten.
- * Errors: NULL, SHAPE, ALIGN (16 bytes), UNSUPPORTED (D != 128, S % 64 != 0).
+ * Errors: NULL, SHAPE (negative sizes, H not a multiple of H_kv), ALIGN (16 bytes), UNSUPPORTED
+ * (D != 128, S % 64 != 0).
  */
-fog_status fog_fp8_attn_fwd(int B, int H, int S, int D, float softmax_scale, int causal,
+fog_status fog_fp8_attn_fwd(int B, int H, int H_kv, int S, int D, float softmax_scale, int causal,
                             const uint8_t* Q, const uint8_t* K, const uint8_t* V,
                             const float* sinv_q, const float* sinv_k, const float* sinv_v, const float* scale_p,
                             void* O_bf16, float* lse, float* amax_p,
@@ -193,19 +199,21 @@ fog_status fog_fp8_attn_fwd(int B, int H, int S, int D, float softmax_scale, int
  *     dQ   = s sinv_k / scale_ds * (dS~ K~),   dK = s sinv_q / scale_ds * (dS~^T Q~)
  *   dO_e5m2 : dO cast to E5M2 with reciprocal scale sinv_do;  dO_bf16, O_bf16: the bf16 tensors.
  *   lse : from the forward.  scale_ds : one float (delayed-style: amax_ds of a previous call).
- *   dQ, dK, dV : [B, H, S, D] bfloat16, overwritten.   amax_ds : NULL or one float, max |dS|.
- *   workspace : fog_fp8_attn_workspace(B, H, S, D, 1) bytes (three floats per row: D_i and two
+ *   dQ : [B, H, S, D], dK, dV : [B, H_kv, S, D] bfloat16, overwritten; under grouped-query attention
+ *        dK and dV of a key/value head are the sums over its H / H_kv query heads, accumulated
+ *        in binary32 and rounded once.   amax_ds : NULL or one float, max |dS|.
+ *   workspace : fog_fp8_attn_workspace(B, H, H_kv, S, D, 1) bytes (three floats per row: D_i and two
  *               per-row constants with the scales folded in), 4-byte aligned.
  * Same shape rules and errors as the forward; WORKSPACE when the workspace is too small.
  */
-fog_status fog_fp8_attn_bwd(int B, int H, int S, int D, float softmax_scale, int causal,
+fog_status fog_fp8_attn_bwd(int B, int H, int H_kv, int S, int D, float softmax_scale, int causal,
                             const uint8_t* Q, const uint8_t* K, const uint8_t* V,
                             const float* sinv_q, const float* sinv_k, const float* sinv_v,
                             const void* O_bf16, const void* dO_bf16, const uint8_t* dO_e5m2, const float* sinv_do,
                             const float* lse, const float* scale_p, const float* scale_ds,
                             void* dQ_bf16, void* dK_bf16, void* dV_bf16, float* amax_ds,
                             void* workspace, size_t workspace_bytes, void* stream);
-size_t fog_fp8_attn_workspace(int B, int H, int S, int D, int is_bwd);
+size_t fog_fp8_attn_workspace(int B, int H, int H_kv, int S, int D, int is_bwd);
 
 #ifdef __cplusplus
 }

@@ -40,6 +40,7 @@ struct BwdArgs {
   uint32_t* amax_ds; float* Dws;
   float softmax_scale;
   int BH, S, nblk;
+  int BHkv, G;   // key/value heads in all, query heads per key/value head (grouped-query attention)
 };
 
 // LDS tiles are [64 rows][128 bytes]; the 16-byte chunks of a row sit at position chunk ^ swz(row).
@@ -169,11 +170,12 @@ constexpr int KV_STAGE = 2 * TILE + 512;
 template <bool CAUSAL>
 __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
   __shared__ __attribute__((aligned(1024))) uint8_t smem[NSTAGE * KV_STAGE];
-  const int bh = blockIdx.x % a.BH;
-  const int kblk = blockIdx.x / a.BH;                  // early key blocks see the most queries: launched first
+  const int bhk = blockIdx.x % a.BHkv;                 // key/value head; its query heads are bhk * G .. + G - 1
+  const int kblk = blockIdx.x / a.BHkv;                // early key blocks see the most queries: launched first
   const int t = threadIdx.x, w = t >> 6, l = t & 63, g = l >> 5;
-  const int S = a.S;
-  const int64_t hoff = (int64_t)bh * S;
+  const int S = a.S, G = a.G;
+  const int64_t hoff = (int64_t)bhk * S;               // rows of this K/V head
+  const int64_t qoff = hoff * G;                       // first row of the group's first query head
   const int key0 = kblk * BLK + 32 * w;
   const int key = key0 + (l & 31);
   const bool wave_on = key0 < S;
@@ -196,29 +198,33 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
     for (int r = 0; r < 16; ++r) { dv[d][r] = 0.0f; dk[d][r] = 0.0f; }
 
   const int qb_first = CAUSAL ? (kblk * BLK) / STEP : 0;
-  const int nqb = S / STEP - qb_first;                 // query blocks this workgroup walks
-  // first block (relative) this wave needs: blocks whose last query is below the wave's first key are skipped
+  const int nqb = S / STEP - qb_first;                 // query blocks of one head this workgroup walks
+  const int total = nqb * G;                           // ... and of the whole group: head after head, one stream
+  // first block (relative, within a head) this wave needs: blocks whose last query is below the wave's first key are skipped
   const int skip = !wave_on ? nqb : (CAUSAL ? max(0, key0 / STEP - qb_first) : 0);
 
-  const uint32_t head_bytes = (uint32_t)S * HD;
-  const v4i rsrc_q = make_rsrc(a.Q + hoff * HD, head_bytes), rsrc_do = make_rsrc(a.dO8 + hoff * HD, head_bytes);
+  const uint32_t group_bytes = (uint32_t)G * S * HD;
+  const v4i rsrc_q = make_rsrc(a.Q + qoff * HD, group_bytes), rsrc_do = make_rsrc(a.dO8 + qoff * HD, group_bytes);
   const int64_t nrows = (int64_t)a.BH * S;
-  const v4i rsrc_lse = make_rsrc(a.Dws + 2 * nrows + hoff, (uint32_t)S * 4), rsrc_d = make_rsrc(a.Dws + nrows + hoff, (uint32_t)S * 4);
+  const v4i rsrc_lse = make_rsrc(a.Dws + 2 * nrows + qoff, (uint32_t)G * S * 4), rsrc_d = make_rsrc(a.Dws + nrows + qoff, (uint32_t)G * S * 4);
   uint32_t off[2];
   tile_load_offsets(off);
   const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)smem);
   const uint32_t lds_w = lds0 + 2048u * (uint32_t)__builtin_amdgcn_readfirstlane(w);
   const bool rows_d = __builtin_amdgcn_readfirstlane(w) & 1;   // odd waves fetch D, even waves lse (two copies each: identical bytes)
-  auto issue = [&](int i) {   // relative block i -> stage i % 4; blocks past the end fetch zeros
-    const uint32_t adv = i < nqb ? (uint32_t)(qb_first + i) * (STEP * HD) : OOB;
-    const uint32_t radv = i < nqb ? (uint32_t)(qb_first + i) * (STEP * 4) : OOB;
-    const uint32_t base = (uint32_t)(i & (NSTAGE - 1)) * KV_STAGE;
+  int iss_i = 0, iss_g = 0;   // query block and head of the next block to issue (issue() is called once per block, in order)
+  auto issue = [&](int it) {  // block it of the stream -> stage it % 4; blocks past the end fetch zeros
+    const uint32_t row0 = (uint32_t)(iss_g * S + (qb_first + iss_i) * STEP);
+    const uint32_t adv = iss_g < G ? row0 * HD : OOB;
+    const uint32_t radv = iss_g < G ? row0 * 4 : OOB;
+    const uint32_t base = (uint32_t)(it & (NSTAGE - 1)) * KV_STAGE;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       load16_to_lds(rsrc_q, off[j] + adv, lds_w + base + 1024u * j);
       load16_to_lds(rsrc_do, off[j] + adv, lds_w + base + TILE + 1024u * j);
     }
     load4_to_lds(rows_d ? rsrc_d : rsrc_lse, (uint32_t)(4 * l) + radv, lds0 + base + 2 * TILE + (rows_d ? 256u : 0u));
+    if (++iss_i == nqb) { iss_i = 0; ++iss_g; }
   };
   const RowFrag rf = rowfrag_addr();
   const ColFrag cf = colfrag_addr();
@@ -246,16 +252,19 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
   __builtin_amdgcn_s_waitcnt(0x0F7A);  // vmcnt = 10: block 0 has landed (5 direct loads per thread and block)
   __syncthreads();
   v16f sa[2], da[2], sb[2], db[2];
-  if (skip == 0 && nqb > 0) scores(0, sa, da);
+  if (skip == 0 && total > 0) scores(0, sa, da);
 
-  auto block = [&](const bool CLAMP_P, int i, v16f* st, v16f* dp, v16f* stn, v16f* dpn) __attribute__((always_inline)) {
+  int cur_i = 0;
+  auto block = [&](const bool CLAMP_P, int it, v16f* st, v16f* dp, v16f* stn, v16f* dpn) __attribute__((always_inline)) {
     __builtin_amdgcn_s_waitcnt(0x0075);  // vmcnt = 5: block i + 1 landed; lgkmcnt = 0: own LDS reads done
     __syncthreads();
-    issue(i + 3);
-    const bool cur = i >= skip, nxt = i + 1 >= skip && i + 1 < nqb;
-    if (nxt) scores(i + 1, stn, dpn);
+    issue(it + 3);
+    const int i = cur_i, i_next = i + 1 == nqb ? 0 : i + 1;   // query block within its head, of this block and of the next
+    cur_i = i_next;
+    const bool cur = i >= skip, nxt = i_next >= skip && it + 1 < total;
+    if (nxt) scores(it + 1, stn, dpn);
     if (cur) {
-      const uint8_t* sq = smem + (i & (NSTAGE - 1)) * KV_STAGE;
+      const uint8_t* sq = smem + (it & (NSTAGE - 1)) * KV_STAGE;
       const uint8_t* sdo = sq + TILE;
       const float* srow = reinterpret_cast<const float*>(sq + 2 * TILE);   // [0..63] lse - log2 rho_p, [64..127] D rho_ds / rho_p
       const int qbase = (qb_first + i) * STEP;
@@ -302,14 +311,14 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
   // The saturating form of the P cast is only needed for a scale above the format's maximum; the
   // choice is made once, outside the loop, so that the loop body stays one straight-line block.
   if (clamp_p) {
-    for (int i = 0; i < nqb; i += 2) {   // two blocks per trip so that the score registers just swap roles
-      block(true, i, sa, da, sb, db);
-      if (i + 1 < nqb) block(true, i + 1, sb, db, sa, da);
+    for (int it = 0; it < total; it += 2) {   // two blocks per trip so that the score registers just swap roles
+      block(true, it, sa, da, sb, db);
+      if (it + 1 < total) block(true, it + 1, sb, db, sa, da);
     }
   } else {
-    for (int i = 0; i < nqb; i += 2) {
-      block(false, i, sa, da, sb, db);
-      if (i + 1 < nqb) block(false, i + 1, sb, db, sa, da);
+    for (int it = 0; it < total; it += 2) {
+      block(false, it, sa, da, sb, db);
+      if (it + 1 < total) block(false, it + 1, sb, db, sa, da);
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
@@ -367,7 +376,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(BwdArgs a) {
   const int nkb_wave = !wave_on ? 0 : (CAUSAL ? min(nkb, (q0 + 31) / STEP + 1) : nkb);
 
   const uint32_t head_bytes = (uint32_t)S * HD;
-  const v4i rsrc_k = make_rsrc(a.K + hoff * HD, head_bytes), rsrc_v = make_rsrc(a.V + hoff * HD, head_bytes);
+  const int64_t kvoff = (int64_t)(bh / a.G) * S;   // the G query heads of a group are consecutive and share one K/V head
+  const v4i rsrc_k = make_rsrc(a.K + kvoff * HD, head_bytes), rsrc_v = make_rsrc(a.V + kvoff * HD, head_bytes);
   uint32_t off[2];
   tile_load_offsets(off);
   const uint32_t lds_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(uintptr_t)smem + 2048u * w));
@@ -464,20 +474,21 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 }  // namespace
 
-extern "C" size_t fog_fp8_attn_workspace(int B, int H, int S, int D, int is_bwd) {
-  (void)D;
+extern "C" size_t fog_fp8_attn_workspace(int B, int H, int H_kv, int S, int D, int is_bwd) {
+  (void)D; (void)H_kv;
   if (!is_bwd || B <= 0 || H <= 0 || S <= 0) return 0;
   return (size_t)3 * B * H * S * sizeof(float);
 }
 
-extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int S, int D, float softmax_scale, int causal,
+extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int H_kv, int S, int D, float softmax_scale, int causal,
                                        const uint8_t* Q, const uint8_t* K, const uint8_t* V,
                                        const float* sinv_q, const float* sinv_k, const float* sinv_v,
                                        const void* O_bf16, const void* dO_bf16, const uint8_t* dO_e5m2, const float* sinv_do,
                                        const float* lse, const float* scale_p, const float* scale_ds,
                                        void* dQ_bf16, void* dK_bf16, void* dV_bf16, float* amax_ds,
                                        void* workspace, size_t workspace_bytes, void* stream) {
-  if (B < 0 || H < 0 || S < 0 || D < 0) return FOG_ERR_SHAPE;
+  if (B < 0 || H < 0 || H_kv < 0 || S < 0 || D < 0) return FOG_ERR_SHAPE;
+  if ((H > 0) != (H_kv > 0) || (H_kv > 0 && H % H_kv != 0)) return FOG_ERR_SHAPE;
   if (!(softmax_scale > 0.0f)) return FOG_ERR_UNSUPPORTED;
   if (D != HD || S % STEP != 0) return FOG_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
@@ -491,9 +502,9 @@ extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int S, int D, float softmax
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O_bf16) || !aligned16(dO_bf16) || !aligned16(dO_e5m2) ||
       !aligned16(dQ_bf16) || !aligned16(dK_bf16) || !aligned16(dV_bf16))
     return FOG_ERR_ALIGN;
-  if (!workspace || workspace_bytes < fog_fp8_attn_workspace(B, H, S, D, 1) || (reinterpret_cast<uintptr_t>(workspace) & 3u))
+  if (!workspace || workspace_bytes < fog_fp8_attn_workspace(B, H, H_kv, S, D, 1) || (reinterpret_cast<uintptr_t>(workspace) & 3u))
     return FOG_ERR_WORKSPACE;
-  if ((int64_t)S * HD >= 0x7FFFFFFF) return FOG_ERR_UNSUPPORTED;
+  if ((int64_t)(H / H_kv) * S * HD >= 0x7FFFFFFF) return FOG_ERR_UNSUPPORTED;   // a group of query heads is one 32-bit addressed buffer
   if ((int64_t)B * H > 0x7FFFFF || (int64_t)B * H * ((S + BLK - 1) / BLK) > 0x7FFFFFF0) return FOG_ERR_UNSUPPORTED;
   BwdArgs a;
   a.Q = Q; a.K = K; a.V = V; a.dO8 = dO_e5m2;
@@ -504,12 +515,13 @@ extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int S, int D, float softmax
   a.amax_ds = reinterpret_cast<uint32_t*>(amax_ds); a.Dws = reinterpret_cast<float*>(workspace);
   a.softmax_scale = softmax_scale;
   a.BH = B * H; a.S = S; a.nblk = (S + BLK - 1) / BLK;
+  a.BHkv = B * H_kv; a.G = H / H_kv;
   if (amax_ds) zero_u32b<<<1, 1, 0, s>>>(a.amax_ds);
   const int64_t rows = (int64_t)a.BH * S;
   attn_bwd_rowdot_kernel<<<(int)((rows + 15) / 16), kThreads, 0, s>>>(a.O, a.dO, a.lse, a.scale_p, a.scale_ds, a.Dws, rows);
-  const int grid = a.BH * a.nblk;
-  if (causal) attn_bwd_dkdv_kernel<true><<<grid, kThreads, 0, s>>>(a);
-  else        attn_bwd_dkdv_kernel<false><<<grid, kThreads, 0, s>>>(a);
+  const int grid = a.BH * a.nblk, grid_kv = a.BHkv * a.nblk;
+  if (causal) attn_bwd_dkdv_kernel<true><<<grid_kv, kThreads, 0, s>>>(a);
+  else        attn_bwd_dkdv_kernel<false><<<grid_kv, kThreads, 0, s>>>(a);
   if (causal) { if (amax_ds) attn_bwd_dq_kernel<true, true><<<grid, kThreads, 0, s>>>(a); else attn_bwd_dq_kernel<true, false><<<grid, kThreads, 0, s>>>(a); }
   else        { if (amax_ds) attn_bwd_dq_kernel<false, true><<<grid, kThreads, 0, s>>>(a); else attn_bwd_dq_kernel<false, false><<<grid, kThreads, 0, s>>>(a); }
   return fog_launch_status();

@@ -46,6 +46,7 @@ struct FwdArgs {
   uint16_t* O; float* lse; uint32_t* amax_p;
   float softmax_scale;
   int BH, S, nqb;
+  int G;   // query heads per key/value head (grouped-query attention); 1 = multi-head
 };
 
 FOG_DEVICE float lane_xor32(float v) { return __shfl_xor(v, 32, 64); }
@@ -110,8 +111,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
 
   // ---- direct loads: 2 pieces of K and 2 of V (1 KB = 8 rows each) per wave and block
   const uint32_t head_bytes = (uint32_t)S * HD;
-  const v4i rsrc_k = make_rsrc(a.K + (int64_t)bh * S * HD, head_bytes);
-  const v4i rsrc_v = make_rsrc(a.V + (int64_t)bh * S * HD, head_bytes);
+  const int kvh = bh / a.G;   // heads are laid out [B][H]: the G query heads of a group are consecutive and share one K/V head
+  const v4i rsrc_k = make_rsrc(a.K + (int64_t)kvh * S * HD, head_bytes);
+  const v4i rsrc_v = make_rsrc(a.V + (int64_t)kvh * S * HD, head_bytes);
   uint32_t off_k[2], off_v[2];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
@@ -295,13 +297,14 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 }  // namespace
 
-extern "C" fog_status fog_fp8_attn_fwd(int B, int H, int S, int D, float softmax_scale, int causal,
+extern "C" fog_status fog_fp8_attn_fwd(int B, int H, int H_kv, int S, int D, float softmax_scale, int causal,
                                        const uint8_t* Q, const uint8_t* K, const uint8_t* V,
                                        const float* sinv_q, const float* sinv_k, const float* sinv_v, const float* scale_p,
                                        void* O_bf16, float* lse, float* amax_p,
                                        void* workspace, size_t workspace_bytes, void* stream) {
   (void)workspace; (void)workspace_bytes;
-  if (B < 0 || H < 0 || S < 0 || D < 0) return FOG_ERR_SHAPE;
+  if (B < 0 || H < 0 || H_kv < 0 || S < 0 || D < 0) return FOG_ERR_SHAPE;
+  if ((H > 0) != (H_kv > 0) || (H_kv > 0 && H % H_kv != 0)) return FOG_ERR_SHAPE;
   if (!(softmax_scale > 0.0f)) return FOG_ERR_UNSUPPORTED;
   if (D != HD || S % BKV != 0) return FOG_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
@@ -317,6 +320,7 @@ extern "C" fog_status fog_fp8_attn_fwd(int B, int H, int S, int D, float softmax
   a.O = reinterpret_cast<uint16_t*>(O_bf16); a.lse = lse; a.amax_p = reinterpret_cast<uint32_t*>(amax_p);
   a.softmax_scale = softmax_scale;
   a.BH = B * H; a.S = S; a.nqb = (S + BQ - 1) / BQ;
+  a.G = H / H_kv;
   const int grid = a.BH * a.nqb;
   if (causal) attn_fwd_kernel<true><<<grid, kThreads, 0, s>>>(a);
   else        attn_fwd_kernel<false><<<grid, kThreads, 0, s>>>(a);

@@ -31,10 +31,10 @@ SIGNATURES = {
     "fog_kurtosis": (_I, [_P, _I64, _I64, _I64, _P, _P]),
     "fog_fp8_gemm": (_I, [_I, _I64, _I64, _I64, _P, _I, _I64, _P, _P, _I, _I64, _P, _P, _I64, _P, _SZ, _P]),
     "fog_fp8_gemm_workspace": (_SZ, [_I, _I64, _I64, _I64]),
-    "fog_fp8_attn_fwd": (_I, [_I, _I, _I, _I, _F, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
-    "fog_fp8_attn_bwd": (_I, [_I, _I, _I, _I, _F, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P,
+    "fog_fp8_attn_fwd": (_I, [_I, _I, _I, _I, _I, _F, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
+    "fog_fp8_attn_bwd": (_I, [_I, _I, _I, _I, _I, _F, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P,
                               _P, _P, _P, _P, _P, _SZ, _P]),
-    "fog_fp8_attn_workspace": (_SZ, [_I, _I, _I, _I, _I]),
+    "fog_fp8_attn_workspace": (_SZ, [_I, _I, _I, _I, _I, _I]),
 }
 
 
@@ -127,22 +127,23 @@ def fp8_gemm_workspace(layout, M, N, K):
 
 
 def fp8_attn_fwd(B, H, S, D, softmax_scale, causal, Q, K, V, sinv_q, sinv_k, sinv_v, scale_p, O, lse,
-                 amax_p=None, workspace=None, stream=None):
+                 amax_p=None, workspace=None, stream=None, H_kv=None):
+    """H_kv: key/value heads (grouped-query attention); None means H (multi-head)."""
     ws = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(load().fog_fp8_attn_fwd(B, H, S, D, softmax_scale, int(causal), _ptr(Q), _ptr(K), _ptr(V),
+    _check(load().fog_fp8_attn_fwd(B, H, H if H_kv is None else H_kv, S, D, softmax_scale, int(causal), _ptr(Q), _ptr(K), _ptr(V),
                                    _ptr(sinv_q), _ptr(sinv_k), _ptr(sinv_v), _ptr(scale_p), _ptr(O), _ptr(lse),
                                    _ptr(amax_p), _ptr(workspace), ws, _stream(stream)), "fog_fp8_attn_fwd")
 
 
 def fp8_attn_bwd(B, H, S, D, softmax_scale, causal, Q, K, V, sinv_q, sinv_k, sinv_v, O, dO, dO8, sinv_do,
-                 lse, scale_p, scale_ds, dQ, dK, dV, amax_ds=None, workspace=None, stream=None):
+                 lse, scale_p, scale_ds, dQ, dK, dV, amax_ds=None, workspace=None, stream=None, H_kv=None):
     ws = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(load().fog_fp8_attn_bwd(B, H, S, D, softmax_scale, int(causal), _ptr(Q), _ptr(K), _ptr(V),
+    _check(load().fog_fp8_attn_bwd(B, H, H if H_kv is None else H_kv, S, D, softmax_scale, int(causal), _ptr(Q), _ptr(K), _ptr(V),
                                    _ptr(sinv_q), _ptr(sinv_k), _ptr(sinv_v), _ptr(O), _ptr(dO), _ptr(dO8),
                                    _ptr(sinv_do), _ptr(lse), _ptr(scale_p), _ptr(scale_ds),
                                    _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(amax_ds), _ptr(workspace), ws,
                                    _stream(stream)), "fog_fp8_attn_bwd")
 
 
-def fp8_attn_workspace(B, H, S, D, is_bwd):
-    return load().fog_fp8_attn_workspace(B, H, S, D, int(is_bwd))
+def fp8_attn_workspace(B, H, S, D, is_bwd, H_kv=None):
+    return load().fog_fp8_attn_workspace(B, H, H if H_kv is None else H_kv, S, D, int(is_bwd))

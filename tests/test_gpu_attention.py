@@ -20,12 +20,19 @@ def cast_all(q, k, v, do):
     return out
 
 
+def kv_of(c, h):
+    """Key/value head of query head h: the tensors of c["k"], c["v"] are [B, H_kv, S, D] (H_kv == H: multi-head)."""
+    H, Hkv = c["q"][0].shape[1], c["k"][0].shape[1]
+    return h // (H // Hkv)
+
+
 def gpu_fwd(c, B, H, S, s, causal, want_amax=True):
     O = torch.full((B, H, S, 128), 0x7FC0, dtype=torch.int16, device="cuda")
     lse = torch.full((B, H, S), float("nan"), device="cuda")
     am = torch.full((1,), -1.0, device="cuda") if want_amax else None
     fog.fp8_attn_fwd(B, H, S, 128, s, causal, dev(c["q"][0]), dev(c["k"][0]), dev(c["v"][0]),
-                     fscalar(c["q"][1]), fscalar(c["k"][1]), fscalar(c["v"][1]), fscalar(448.0), O, lse, amax_p=am)
+                     fscalar(c["q"][1]), fscalar(c["k"][1]), fscalar(c["v"][1]), fscalar(448.0), O, lse, amax_p=am,
+                     H_kv=c["k"][0].shape[1])
     torch.cuda.synchronize()
     return host_u16(O), lse.cpu().numpy(), (am.item() if want_amax else None)
 
@@ -33,7 +40,8 @@ def gpu_fwd(c, B, H, S, s, causal, want_amax=True):
 def oracle_fwd_heads(c, heads, s, causal):
     res = {}
     for (b, h) in heads:
-        res[(b, h)] = attention.attn_fwd_head(c["q"][0][b, h], c["k"][0][b, h], c["v"][0][b, h],
+        hk = kv_of(c, h)
+        res[(b, h)] = attention.attn_fwd_head(c["q"][0][b, h], c["k"][0][b, hk], c["v"][0][b, hk],
                                               c["q"][1], c["k"][1], c["v"][1], s, 448.0, causal)
     return res
 
@@ -43,11 +51,12 @@ def check_fwd(c, B, H, S, s, causal, heads):
     ref = oracle_fwd_heads(c, heads, s, causal)
     pmax = 0.0
     for (b, h), (Or, lr, ap) in ref.items():
-        dx = attention.logit_uncertainty(c["q"][0][b, h], c["k"][0][b, h], c["q"][1], c["k"][1], s, causal)
-        slack = attention.fwd_cast_slack(c["q"][0][b, h], c["k"][0][b, h], c["v"][0][b, h], c["q"][1], c["k"][1], c["v"][1],
+        hk = kv_of(c, h)
+        dx = attention.logit_uncertainty(c["q"][0][b, h], c["k"][0][b, hk], c["q"][1], c["k"][1], s, causal)
+        slack = attention.fwd_cast_slack(c["q"][0][b, h], c["k"][0][b, hk], c["v"][0][b, hk], c["q"][1], c["k"][1], c["v"][1],
                                          s, 448.0, causal, dx=dx)
         check_bf16(O[b, h], Or, what="O[%d,%d]" % (b, h), slack=slack, max_flip_frac=1.0)
-        lunc = attention.lse_uncertainty(c["q"][0][b, h], c["k"][0][b, h], c["q"][1], c["k"][1], s, causal, dx=dx)
+        lunc = attention.lse_uncertainty(c["q"][0][b, h], c["k"][0][b, hk], c["q"][1], c["k"][1], s, causal, dx=dx)
         assert np.all(np.abs(lse[b, h] - lr) <= 2e-4 + lunc), "lse"
         pmax = max(pmax, float(ap))
     assert np.isfinite(lse).all()
@@ -81,39 +90,57 @@ def test_forward_fog_softmax_scale_and_q_zero():
 
 
 def run_bwd(c, B, H, S, s, causal, heads, do_bits):
-    """Feeds the ORACLE's forward results (O rounded to bf16, lse rounded to binary32) to both sides."""
+    """Feeds the ORACLE's forward results (O rounded to bf16, lse rounded to binary32) to both sides.
+    Under grouped-query attention dK and dV of a key/value head are checked when all the query heads of
+    its group are in `heads`: the oracle's per-head contributions are summed in float64 (the kernel sums
+    them in binary32 before its one rounding), and so are the slacks of the cast decisions."""
+    Hkv = c["k"][0].shape[1]
+    G = H // Hkv
     O_bits = np.zeros((B, H, S, 128), np.uint16)
     lse = np.zeros((B, H, S), np.float32)
-    fw = {}
+
+    def head_args(b, h):
+        hk = h // G
+        return (c["q"][0][b, h], c["k"][0][b, hk], c["v"][0][b, hk], c["q"][1], c["k"][1], c["v"][1])
+
     for (b, h) in heads:
-        Or, lr, _ = attention.attn_fwd_head(c["q"][0][b, h], c["k"][0][b, h], c["v"][0][b, h], c["q"][1], c["k"][1], c["v"][1], s, 448.0, causal)
+        Or, lr, _ = attention.attn_fwd_head(*head_args(b, h), s, 448.0, causal)
         O_bits[b, h] = bf16.f64_to_bits_rne(Or)
         lse[b, h] = lr.astype(np.float32)
-        fw[(b, h)] = (O_bits[b, h], lse[b, h])
     # calibrate rho_dS from one oracle pass without the dS cast (delayed-style scale)
     amax_ds = 0.0
     for (b, h) in heads:
-        r = attention.attn_bwd_head(c["q"][0][b, h], c["k"][0][b, h], c["v"][0][b, h], c["q"][1], c["k"][1], c["v"][1],
-                                    O_bits[b, h], do_bits[b, h], c["do"][0][b, h], c["do"][1], lse[b, h], s, 448.0, 1.0, causal, True, False)
+        r = attention.attn_bwd_head(*head_args(b, h), O_bits[b, h], do_bits[b, h], c["do"][0][b, h], c["do"][1], lse[b, h],
+                                    s, 448.0, 1.0, causal, True, False)
         amax_ds = max(amax_ds, float(r[3]))
     rho_ds, _ = scaling.compute_scale(np.float32(amax_ds), fp8.E5M2)
-    dQ, dK, dV = (torch.full((B, H, S, 128), 0x7FC0, dtype=torch.int16, device="cuda") for _ in range(3))
+    dQ = torch.full((B, H, S, 128), 0x7FC0, dtype=torch.int16, device="cuda")
+    dK, dV = (torch.full((B, Hkv, S, 128), 0x7FC0, dtype=torch.int16, device="cuda") for _ in range(2))
     am = torch.full((1,), -1.0, device="cuda")
-    ws = torch.empty(fog.fp8_attn_workspace(B, H, S, 128, True), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(fog.fp8_attn_workspace(B, H, S, 128, True, H_kv=Hkv), dtype=torch.uint8, device="cuda")
     fog.fp8_attn_bwd(B, H, S, 128, s, causal, dev(c["q"][0]), dev(c["k"][0]), dev(c["v"][0]),
                      fscalar(c["q"][1]), fscalar(c["k"][1]), fscalar(c["v"][1]), dev(O_bits), dev(do_bits), dev(c["do"][0]),
-                     fscalar(c["do"][1]), dev(lse), fscalar(448.0), fscalar(rho_ds), dQ, dK, dV, amax_ds=am, workspace=ws)
+                     fscalar(c["do"][1]), dev(lse), fscalar(448.0), fscalar(rho_ds), dQ, dK, dV, amax_ds=am, workspace=ws,
+                     H_kv=Hkv)
     torch.cuda.synchronize()
     dQ, dK, dV = host_u16(dQ), host_u16(dK), host_u16(dV)
+    group = {}
     for (b, h) in heads:
-        r = attention.attn_bwd_head(c["q"][0][b, h], c["k"][0][b, h], c["v"][0][b, h], c["q"][1], c["k"][1], c["v"][1],
-                                    O_bits[b, h], do_bits[b, h], c["do"][0][b, h], c["do"][1], lse[b, h], s, 448.0, rho_ds, causal)
-        sl = attention.bwd_cast_slack(c["q"][0][b, h], c["k"][0][b, h], c["v"][0][b, h], c["q"][1], c["k"][1], c["v"][1],
-                                      O_bits[b, h], do_bits[b, h], c["do"][0][b, h], c["do"][1], lse[b, h], s, 448.0, rho_ds,
-                                      causal)
+        tail = (O_bits[b, h], do_bits[b, h], c["do"][0][b, h], c["do"][1], lse[b, h], s, 448.0, rho_ds, causal)
+        r = attention.attn_bwd_head(*head_args(b, h), *tail)
+        sl = attention.bwd_cast_slack(*head_args(b, h), *tail)
         check_bf16(dQ[b, h], r[0], what="dQ[%d,%d]" % (b, h), max_flip_frac=1.0, slack=sl[0])
-        check_bf16(dK[b, h], r[1], what="dK[%d,%d]" % (b, h), max_flip_frac=1.0, slack=sl[1])
-        check_bf16(dV[b, h], r[2], what="dV[%d,%d]" % (b, h), max_flip_frac=1.0, slack=sl[2])
+        acc = group.setdefault((b, h // G), [0, 0.0, 0.0, 0.0, 0.0])
+        acc[0] += 1
+        acc[1] = acc[1] + r[1]; acc[2] = acc[2] + r[2]; acc[3] = acc[3] + sl[1]; acc[4] = acc[4] + sl[2]
+    checked = 0
+    for (b, hk), (n, dk, dv, sk, sv) in group.items():
+        if n != G:
+            continue            # not every query head of the group was evaluated
+        check_bf16(dK[b, hk], dk, what="dK[%d,%d]" % (b, hk), max_flip_frac=1.0, slack=sk)
+        check_bf16(dV[b, hk], dv, what="dV[%d,%d]" % (b, hk), max_flip_frac=1.0, slack=sv)
+        checked += 1
+    assert checked > 0
     if len(heads) == B * H:
         assert abs(am.item() - amax_ds) <= 1e-4 * amax_ds
     return dQ, dK, dV
@@ -125,6 +152,87 @@ def test_backward_parity(B, H, S, causal):
     q, k, v, do = synth.small_attention(2000 + S, B, H, S)
     c = cast_all(q, k, v, do)
     run_bwd(c, B, H, S, 1 / math.sqrt(128), causal, [(b, h) for b in range(B) for h in range(H)], do)
+
+
+def gqa_case(seed, B, H, Hkv, S):
+    """Grouped-query inputs: Q and dO with H heads, K and V with H_kv heads (same recipe, own seed)."""
+    q, _, _, do = synth.small_attention(seed, B, H, S)
+    _, k, v, _ = synth.small_attention(seed + 1, B, Hkv, S)
+    return cast_all(q, k, v, do), do
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("B,H,Hkv,S", [(1, 2, 1, 128), (2, 4, 2, 320), (1, 8, 2, 192), (1, 4, 1, 448)])
+def test_grouped_query_parity(B, H, Hkv, S, causal):
+    """H_kv < H (Appendix B: grouped-query attention): forward per query head against its group's K/V,
+    backward with dK/dV summed over the group."""
+    c, do = gqa_case(3000 + S + H, B, H, Hkv, S)
+    heads = [(b, h) for b in range(B) for h in range(H)]
+    check_fwd(c, B, H, S, 1 / math.sqrt(128), causal, heads)
+    run_bwd(c, B, H, S, 1 / math.sqrt(128), causal, heads, do)
+
+
+@pytest.mark.parametrize("B,H,Hkv,S", [(2, 4, 2, 8192), (1, 2, 1, 16384)])
+def test_long_context_grouped_query_sampled(B, H, Hkv, S):
+    """Sequences of 8192 and 16384 tokens with grouped queries, causal, whole on the GPU; the oracle
+    evaluates sampled outputs one by one.  Under the causal mask row i of O / lse / dQ depends on the
+    keys 0..i only, and row j of dK / dV on the queries j..S-1 only, so each sample is the oracle's own
+    (unmasked) routine on that slice of the head: no S x S matrix is ever formed.  The backward pass
+    consumes the GPU's own forward results on both sides, as a training step does."""
+    G = H // Hkv
+    c, do = gqa_case(S + H, B, H, Hkv, S)
+    s = 0.125
+    O, lse, _ = gpu_fwd(c, B, H, S, s, True)
+    assert np.isfinite(lse).all()
+    rng = np.random.default_rng(S)
+    rows = sorted({0, 1, 63, 64, 127, 128, S // 2 - 1, S // 2, S - 65, S - 64, S - 2, S - 1, *map(int, rng.integers(0, S, 6))})
+    heads = [(0, 0), (B - 1, H - 1)]
+    sq, sk, sv = c["q"][1], c["k"][1], c["v"][1]
+    for (b, h) in heads:
+        hk = h // G
+        for i in rows:
+            args = (c["q"][0][b, h, i:i + 1], c["k"][0][b, hk, :i + 1], c["v"][0][b, hk, :i + 1], sq, sk, sv)
+            Or, lr, _ = attention.attn_fwd_head(*args, s, 448.0, False)
+            dx = attention.logit_uncertainty(args[0], args[1], sq, sk, s, False)
+            slack = attention.fwd_cast_slack(*args, s, 448.0, False, dx=dx)
+            check_bf16(O[b, h, i:i + 1], Or, what="O[%d,%d,%d]" % (b, h, i), slack=slack, max_flip_frac=1.0)
+            lunc = attention.lse_uncertainty(args[0], args[1], sq, sk, s, False, dx=dx)
+            assert np.all(np.abs(lse[b, h, i:i + 1] - lr) <= 2e-4 + lunc)
+    # backward on the GPU's own O and lse; the scale of dS from a first pass (delayed-style)
+    Od, lsed = dev(O), dev(lse)
+    dQ = torch.full((B, H, S, 128), 0x7FC0, dtype=torch.int16, device="cuda")
+    dK, dV = (torch.full((B, Hkv, S, 128), 0x7FC0, dtype=torch.int16, device="cuda") for _ in range(2))
+    am = torch.full((1,), -1.0, device="cuda")
+    ws = torch.empty(fog.fp8_attn_workspace(B, H, S, 128, True, H_kv=Hkv), dtype=torch.uint8, device="cuda")
+    dev_in = (dev(c["q"][0]), dev(c["k"][0]), dev(c["v"][0]), fscalar(sq), fscalar(sk), fscalar(sv), Od, dev(do), dev(c["do"][0]),
+              fscalar(c["do"][1]), lsed, fscalar(448.0))
+    fog.fp8_attn_bwd(B, H, S, 128, s, True, *dev_in, fscalar(1.0), dQ, dK, dV, amax_ds=am, workspace=ws, H_kv=Hkv)
+    torch.cuda.synchronize()
+    rho_ds, _ = scaling.compute_scale(np.float32(am.item()), fp8.E5M2)
+    fog.fp8_attn_bwd(B, H, S, 128, s, True, *dev_in, fscalar(rho_ds), dQ, dK, dV, amax_ds=am, workspace=ws, H_kv=Hkv)
+    torch.cuda.synchronize()
+    dQ, dK, dV = host_u16(dQ), host_u16(dK), host_u16(dV)
+    sdo = c["do"][1]
+
+    def bwd_slice(b, h, qs, ks):
+        """Oracle backward of query head (b, h) restricted to queries qs and keys ks (all visible)."""
+        hk = h // G
+        args = (c["q"][0][b, h, qs], c["k"][0][b, hk, ks], c["v"][0][b, hk, ks], sq, sk, sv,
+                O[b, h, qs], do[b, h, qs], c["do"][0][b, h, qs], sdo, lse[b, h, qs], s, 448.0, rho_ds, False)
+        return attention.attn_bwd_head(*args), attention.bwd_cast_slack(*args)
+
+    for (b, h) in heads:
+        for i in rows:
+            r, sl = bwd_slice(b, h, slice(i, i + 1), slice(0, i + 1))
+            check_bf16(dQ[b, h, i:i + 1], r[0], what="dQ[%d,%d,%d]" % (b, h, i), max_flip_frac=1.0, slack=sl[0])
+    for (b, hk) in [(0, 0), (B - 1, Hkv - 1)]:
+        for j in rows:
+            dk = dv = slk = slv = 0.0
+            for h in range(hk * G, hk * G + G):            # the group's query heads all feed this key
+                r, sl = bwd_slice(b, h, slice(j, S), slice(j, j + 1))
+                dk, dv, slk, slv = dk + r[1], dv + r[2], slk + sl[1], slv + sl[2]
+            check_bf16(dK[b, hk, j:j + 1], dk, what="dK[%d,%d,%d]" % (b, hk, j), max_flip_frac=1.0, slack=slk)
+            check_bf16(dV[b, hk, j:j + 1], dv, what="dV[%d,%d,%d]" % (b, hk, j), max_flip_frac=1.0, slack=slv)
 
 
 def test_config3_full_size_sampled_heads():
@@ -154,13 +262,15 @@ def test_attention_argument_errors():
     f = fscalar(1.0)
     l = torch.zeros(64, device="cuda")
     p, fp = x.data_ptr(), f.data_ptr()
-    args = lambda D, S, q=p: (1, 1, S, D, 0.1, 1, q, p, p, fp, fp, fp, fp, o.data_ptr(), l.data_ptr(), None, None, 0, st)
+    args = lambda D, S, q=p, H=1, Hkv=1: (1, H, Hkv, S, D, 0.1, 1, q, p, p, fp, fp, fp, fp, o.data_ptr(), l.data_ptr(), None, None, 0, st)
     assert lib.fog_fp8_attn_fwd(*args(64, 64)) == 4
     assert lib.fog_fp8_attn_fwd(*args(128, 48)) == 4
     assert lib.fog_fp8_attn_fwd(*args(128, 64, None)) == 1
     assert lib.fog_fp8_attn_fwd(*args(128, 64, p + 4)) == 3
     assert lib.fog_fp8_attn_fwd(*args(128, 64)) == 0
-    b = (1, 1, 64, 128, 0.1, 1, p, p, p, fp, fp, fp, o.data_ptr(), o.data_ptr(), p, fp, l.data_ptr(), fp, fp,
+    assert lib.fog_fp8_attn_fwd(*args(128, 64, p, 3, 2)) == 2          # H not a multiple of H_kv
+    assert lib.fog_fp8_attn_fwd(*args(128, 64, p, 2, 0)) == 2
+    b = (1, 1, 1, 64, 128, 0.1, 1, p, p, p, fp, fp, fp, o.data_ptr(), o.data_ptr(), p, fp, l.data_ptr(), fp, fp,
          o.data_ptr(), o.data_ptr(), o.data_ptr(), None)
     assert lib.fog_fp8_attn_bwd(*b, None, 0, st) == 5
     ws = torch.zeros(3 * 64, device="cuda")

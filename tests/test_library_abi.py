@@ -37,5 +37,5 @@ def test_binding_covers_the_header_and_pure_host_queries():
     assert sorted(fog.SIGNATURES) == declared_symbols()
     lib = fog.load()
     assert lib.fog_fp8_gemm_workspace(0, 4096, 8192, 2048) == 0
-    assert lib.fog_fp8_attn_workspace(4, 16, 2048, 128, 1) >= 4 * 16 * 2048 * 4
-    assert lib.fog_fp8_attn_workspace(4, 16, 2048, 128, 0) == 0
+    assert lib.fog_fp8_attn_workspace(4, 16, 16, 2048, 128, 1) >= 4 * 16 * 2048 * 4
+    assert lib.fog_fp8_attn_workspace(4, 16, 16, 2048, 128, 0) == 0
