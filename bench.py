@@ -144,6 +144,24 @@ def main():
         n, work, ms = kt.summary()["kurtosis"]
         kernels["kurtosis_monitor"] = {"launches": n, "avg_launch_ms": ms / n, "achieved": work / (ms * 1e-3) / 1e9,
                                        "unit": "GB/s", "frac": work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "in_timed_step": False}
+    # The fused QK-RMSNorm + cast producer (an alternative source of the Q / K bytes, not part of the timed
+    # step, whose casts are the plain per-tensor ones): timed on its own over the step's Q and K tensors.
+    if blk.attn is not None:
+        nt = block.EventTimer()
+        one = torch.full((1,), 39.0, device="cuda")
+        am = torch.zeros(1, device="cuda")
+        for rep in range(4):
+            for name in ("Q", "K"):
+                c = blk.attn.c[name]
+                if rep:
+                    nt.begin("qknorm", 3 * c.x.numel())
+                fog.rmsnorm_quantize(c.x, fog.E4M3, one, c.q, gain=1.0, amax_out=am)
+                if rep:
+                    nt.end()
+        torch.cuda.synchronize()
+        n, work, ms = nt.summary()["qknorm"]
+        kernels["qknorm_cast"] = {"launches": n, "avg_launch_ms": ms / n, "achieved": work / (ms * 1e-3) / 1e9,
+                                  "unit": "GB/s", "frac": work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "in_timed_step": False}
     g = kernels.get("gemm") or kernels.get("attn_fwd")
     roofline = {"bound": "mfma", "kernel": "fp8_gemm_kernel" if "gemm" in kernels else "attn_fwd_kernel",
                 "achieved": g["achieved"], "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": g["frac"],

@@ -130,6 +130,27 @@ fog_status fog_quantize_jit(const void* x_bf16, int64_t rows, int64_t cols, int6
 size_t fog_quantize_jit_workspace(void);
 
 /*
+ * QK RMS normalisation with a frozen gain, fused with the FP8 cast (Section 3: N_gamma(x) =
+ * gamma x / rms(x), rms(x) = ||x||_2 / sqrt(D), applied to every query / key vector; the FOG
+ * variants freeze the gains and Appendix A folds their value into the softmax scale, which
+ * leaves one scalar).  Per row x of the matrix (one head of one token):
+ *     y = gain * x / rms(x)   (binary32; a row of zeros gives zeros: the formula has no epsilon)
+ *     q = sat_rne_fmt( fl32( y * scale ) ),      amax_out = max |y| over the matrix.
+ * The scale is the caller's (delayed scaling: from the history that amax_out feeds; |y| never
+ * exceeds gain * sqrt(cols), so FP8MaxValue / (gain * sqrt(cols)) is a scale that cannot saturate).
+ * y is never stored, so a code is a rounding decision on a binary32 value whose last bits depend
+ * on the summation order: codes agree with a float64 evaluation except where rho * y lies within
+ * about 2^-21 (relative) of a rounding boundary.
+ *   x_bf16 : [rows, cols] bfloat16, leading dimension ldx.   q : [rows, cols] bytes, leading dimension ldq.
+ *   gain   : > 0 and finite.   amax_out : NULL or one float, overwritten.
+ * Fast paths: cols in {64, 128, 256, 512} with x 16-byte and q 8-byte aligned, ldx and ldq multiples
+ * of 8; every other shape takes a one-wave-per-row kernel.
+ * Errors: NULL, SHAPE, ALIGN (odd x), UNSUPPORTED (format, gain).
+ */
+fog_status fog_rmsnorm_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, float gain, fog_fp8 fmt,
+                                const float* scale, uint8_t* q, int64_t ldq, float* amax_out, void* stream);
+
+/*
  * Activation kurtosis, the paper's outlier diagnostic (Section 4): for each token vector x (a row),
  * kurt(x) = mu[x^4] / (mu[x^2])^2 (element-wise powers, x not centred); the result is the mean over
  * the rows.  The denominator is read as the squared un-centred second moment (1 for a constant
