@@ -1,7 +1,7 @@
 // Activation kurtosis (Section 4 of the paper): kurt(x) = mu[x^4] / (mu[x^2])^2 per token vector,
 // averaged over the token vectors of a tensor.  The denominator is read as the squared un-centred
 // second moment (the printed sigma^2[x^2] cannot be the variance of x^2: that would fall as an
-// outlier grows).  HBM-bound: every element is read once with 16-byte loads; one wave per row,
+// outlier grows).  HBM-bound: every element is read once with 16-byte loads (eight in flight); one wave per row,
 // binary32 sums of x^2 and x^4, one float atomic per workgroup.
 #include "common.h"
 #include "launch.h"
@@ -31,12 +31,23 @@ __global__ __launch_bounds__(kThreads) void kurtosis_kernel(const uint16_t* __re
     if (VEC) {
       const int64_t nvec = cols >> 3;
       int64_t i = lane;
-      for (; i + 192 < nvec; i += 256) {   // four loads in flight
-        uint4 a = ld_nt16(row + 8 * i), b = ld_nt16(row + 8 * (i + 64)), c = ld_nt16(row + 8 * (i + 128)), d = ld_nt16(row + 8 * (i + 192));
-        acc_pair(a.x, s2, s4); acc_pair(a.y, s2, s4); acc_pair(a.z, s2, s4); acc_pair(a.w, s2, s4);
-        acc_pair(b.x, s2, s4); acc_pair(b.y, s2, s4); acc_pair(b.z, s2, s4); acc_pair(b.w, s2, s4);
-        acc_pair(c.x, s2, s4); acc_pair(c.y, s2, s4); acc_pair(c.z, s2, s4); acc_pair(c.w, s2, s4);
-        acc_pair(d.x, s2, s4); acc_pair(d.y, s2, s4); acc_pair(d.z, s2, s4); acc_pair(d.w, s2, s4);
+      for (; i + 448 < nvec; i += 512) {   // eight loads in flight
+        uint4 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = ld_nt16(row + 8 * (i + 64 * k));
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          acc_pair(v[k].x, s2, s4); acc_pair(v[k].y, s2, s4); acc_pair(v[k].z, s2, s4); acc_pair(v[k].w, s2, s4);
+        }
+      }
+      for (; i + 192 < nvec; i += 256) {   // four
+        uint4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = ld_nt16(row + 8 * (i + 64 * k));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          acc_pair(v[k].x, s2, s4); acc_pair(v[k].y, s2, s4); acc_pair(v[k].z, s2, s4); acc_pair(v[k].w, s2, s4);
+        }
       }
       for (; i < nvec; i += 64) {
         uint4 a = ld_nt16(row + 8 * i);

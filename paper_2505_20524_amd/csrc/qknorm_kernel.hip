@@ -38,33 +38,41 @@ template <int FMT, int LPR>
 __global__ __launch_bounds__(kThreads) void qknorm_rows_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t ldx, float gain,
                                                                const float* __restrict__ scale, uint8_t* __restrict__ q, int64_t ldq,
                                                                uint32_t* __restrict__ amax_out) {
-  constexpr int RPB = kThreads / LPR;   // rows per workgroup and trip
+  constexpr int RPB = kThreads / LPR;   // rows per workgroup and load
+  constexpr int U = 4;                  // rows per lane group and trip: four loads in flight
   const float rho = *scale;
   const int sub = threadIdx.x % LPR, rloc = threadIdx.x / LPR;
   float m = 0.0f;
-  for (int64_t r0 = (int64_t)blockIdx.x * RPB; r0 < rows; r0 += (int64_t)gridDim.x * RPB) {
-    const int64_t r = r0 + rloc;
-    const bool in = r < rows;
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (in) v = ld_nt16(x + r * ldx + 8 * sub);
-    float f[8] = {bf16lo(v.x), bf16hi(v.x), bf16lo(v.y), bf16hi(v.y), bf16lo(v.z), bf16hi(v.z), bf16lo(v.w), bf16hi(v.w)};
-    float s = 0.0f;
+  for (int64_t r0 = (int64_t)blockIdx.x * (RPB * U); r0 < rows; r0 += (int64_t)gridDim.x * (RPB * U)) {
+    uint4 v[U];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) s = __builtin_fmaf(f[k], f[k], s);
-#pragma unroll
-    for (int o = 1; o < LPR; o <<= 1) s += __shfl_xor(s, o, 64);
-    const float inv = inv_rms(s, (float)(8 * LPR), gain);
-    float y[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      y[k] = f[k] * inv;
-      m = fmaxf(m, fabsf(y[k]));
+    for (int u = 0; u < U; ++u) {
+      const int64_t r = r0 + u * RPB + rloc;
+      v[u] = make_uint4(0u, 0u, 0u, 0u);
+      if (r < rows) v[u] = ld_nt16(x + r * ldx + 8 * sub);
     }
-    if (in) {
-      uint2 o;
-      o.x = cvt4_fp8<FMT>(y[0] * rho, y[1] * rho, y[2] * rho, y[3] * rho);
-      o.y = cvt4_fp8<FMT>(y[4] * rho, y[5] * rho, y[6] * rho, y[7] * rho);
-      st_nt8(q + r * ldq + 8 * sub, o);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t r = r0 + u * RPB + rloc;
+      float f[8] = {bf16lo(v[u].x), bf16hi(v[u].x), bf16lo(v[u].y), bf16hi(v[u].y), bf16lo(v[u].z), bf16hi(v[u].z), bf16lo(v[u].w), bf16hi(v[u].w)};
+      float s = 0.0f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) s = __builtin_fmaf(f[k], f[k], s);
+#pragma unroll
+      for (int o = 1; o < LPR; o <<= 1) s += __shfl_xor(s, o, 64);
+      const float inv = inv_rms(s, (float)(8 * LPR), gain);
+      float y[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        y[k] = f[k] * inv;
+        m = fmaxf(m, fabsf(y[k]));
+      }
+      if (r < rows) {
+        uint2 o;
+        o.x = cvt4_fp8<FMT>(y[0] * rho, y[1] * rho, y[2] * rho, y[3] * rho);
+        o.y = cvt4_fp8<FMT>(y[4] * rho, y[5] * rho, y[6] * rho, y[7] * rho);
+        st_nt8(q + r * ldq + 8 * sub, o);
+      }
     }
   }
   if (amax_out) block_amax(m, amax_out);
@@ -103,7 +111,7 @@ void launch_qknorm(const uint16_t* x, int64_t rows, int64_t cols, int64_t ldx, f
   const bool vec = (reinterpret_cast<uintptr_t>(x) & 15u) == 0 && (reinterpret_cast<uintptr_t>(q) & 7u) == 0 && ldx % 8 == 0 && ldq % 8 == 0;
 #define FOG_QKN(LPR)                                                                                            \
   do {                                                                                                          \
-    int64_t blocks = (rows + kThreads / LPR - 1) / (kThreads / LPR);                                            \
+    int64_t blocks = (rows + 4 * (kThreads / LPR) - 1) / (4 * (kThreads / LPR));                                \
     if (blocks > 4096) blocks = 4096;                                                                           \
     qknorm_rows_kernel<FMT, LPR><<<(int)blocks, kThreads, 0, s>>>(x, rows, ldx, gain, scale, q, ldq, amax_out); \
     return;                                                                                                     \
