@@ -264,13 +264,10 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
   const uint8_t* ring_b = smem + RING_B;
   const float alpha = (*g.sinv_a) * (*g.sinv_b);
 
-  v16f acc[4][4];
+  v16f acc[4][4];   // written by the first K-step of every tile (zero accumulator input), never cleared
+  v16f zero16;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+  for (int r = 0; r < 16; ++r) zero16[r] = 0.0f;
 
   const int nk = (g.K + BK - 1) / BK;
   const int nk4 = (nk + 3) & ~3;  // steps are handled four at a time (two pair stages); steps past K multiply zeros
@@ -289,6 +286,10 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
 #define FOG_RB(j, ST, H) read_frag<B_KM>(ring_b + (ST) * OPERAND_BYTES, fb_addr, j, H)
 #define FOG_MFMA(j, FAI_, FB_, i) \
   acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(FB_[j], FAI_, acc[i][j], FB, FA, 0, 0, 0, 0)
+  // first K-step of a tile: the accumulator input is the constant 0, so the 256 accumulator registers
+  // never have to be cleared between tiles
+#define FOG_MFMA_Z(j, FAI_, FB_, i) \
+  acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(FB_[j], FAI_, zero16, FB, FA, 0, 0, 0, 0)
 #define FOG_FENCE() __builtin_amdgcn_sched_barrier(0)
   // One K-step = 16 MFMAs on the fragments fetched one step earlier, dealt out with the LDS reads
   // of the next step's fragments and (second step of a pair) the 16 direct loads of the pair after
@@ -297,39 +298,39 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
   // are refreshed in place as soon as their row of MFMAs has been issued, only row 3 has a second
   // copy (A3_CUR / A3_IN), so that every read is issued at least three MFMAs before the step ends.
   // L(n) is the n-th of 16 load slots (empty in the first step of a pair).
-#define FOG_STEP_BODY(RST, RH, FB_IN, FB_CUR, A3_IN, A3_CUR, L)                                   \
+#define FOG_STEP_BODY(RST, RH, FB_IN, FB_CUR, A3_IN, A3_CUR, L, MF)                                   \
   do {                                                                                             \
-    FOG_FENCE(); FOG_MFMA(0, fa[0], FB_CUR, 0); FOG_FENCE();                                       \
+    FOG_FENCE(); MF(0, fa[0], FB_CUR, 0); FOG_FENCE();                                       \
     L(0); FB_IN[0] = FOG_RB(0, RST, RH);                                                           \
-    FOG_FENCE(); FOG_MFMA(1, fa[0], FB_CUR, 0); FOG_FENCE();                                       \
+    FOG_FENCE(); MF(1, fa[0], FB_CUR, 0); FOG_FENCE();                                       \
     L(1);                                                                                          \
-    FOG_FENCE(); FOG_MFMA(2, fa[0], FB_CUR, 0); FOG_FENCE();                                       \
+    FOG_FENCE(); MF(2, fa[0], FB_CUR, 0); FOG_FENCE();                                       \
     L(2); FB_IN[1] = FOG_RB(1, RST, RH);                                                           \
-    FOG_FENCE(); FOG_MFMA(3, fa[0], FB_CUR, 0); FOG_FENCE();                                       \
+    FOG_FENCE(); MF(3, fa[0], FB_CUR, 0); FOG_FENCE();                                       \
     L(3);                                                                                          \
-    FOG_FENCE(); FOG_MFMA(0, fa[1], FB_CUR, 1); FOG_FENCE();                                       \
+    FOG_FENCE(); MF(0, fa[1], FB_CUR, 1); FOG_FENCE();                                       \
     L(4); fa[0] = FOG_RA(0, RST, RH);                                                              \
-    FOG_FENCE(); FOG_MFMA(1, fa[1], FB_CUR, 1); FOG_FENCE();                                       \
+    FOG_FENCE(); MF(1, fa[1], FB_CUR, 1); FOG_FENCE();                                       \
     L(5); FB_IN[2] = FOG_RB(2, RST, RH);                                                           \
-    FOG_FENCE(); FOG_MFMA(2, fa[1], FB_CUR, 1); FOG_FENCE();                                       \
+    FOG_FENCE(); MF(2, fa[1], FB_CUR, 1); FOG_FENCE();                                       \
     L(6);                                                                                          \
-    FOG_FENCE(); FOG_MFMA(3, fa[1], FB_CUR, 1); FOG_FENCE();                                       \
+    FOG_FENCE(); MF(3, fa[1], FB_CUR, 1); FOG_FENCE();                                       \
     L(7); FB_IN[3] = FOG_RB(3, RST, RH);                                                           \
-    FOG_FENCE(); FOG_MFMA(0, fa[2], FB_CUR, 2); FOG_FENCE();                                       \
+    FOG_FENCE(); MF(0, fa[2], FB_CUR, 2); FOG_FENCE();                                       \
     L(8); fa[1] = FOG_RA(1, RST, RH);                                                              \
-    FOG_FENCE(); FOG_MFMA(1, fa[2], FB_CUR, 2); FOG_FENCE();                                       \
+    FOG_FENCE(); MF(1, fa[2], FB_CUR, 2); FOG_FENCE();                                       \
     L(9); A3_IN = FOG_RA(3, RST, RH);                                                              \
-    FOG_FENCE(); FOG_MFMA(2, fa[2], FB_CUR, 2); FOG_FENCE();                                       \
+    FOG_FENCE(); MF(2, fa[2], FB_CUR, 2); FOG_FENCE();                                       \
     L(10);                                                                                         \
-    FOG_FENCE(); FOG_MFMA(3, fa[2], FB_CUR, 2); FOG_FENCE();                                       \
+    FOG_FENCE(); MF(3, fa[2], FB_CUR, 2); FOG_FENCE();                                       \
     L(11);                                                                                         \
-    FOG_FENCE(); FOG_MFMA(0, A3_CUR, FB_CUR, 3); FOG_FENCE();                                      \
+    FOG_FENCE(); MF(0, A3_CUR, FB_CUR, 3); FOG_FENCE();                                      \
     L(12); fa[2] = FOG_RA(2, RST, RH);                                                             \
-    FOG_FENCE(); FOG_MFMA(1, A3_CUR, FB_CUR, 3); FOG_FENCE();                                      \
+    FOG_FENCE(); MF(1, A3_CUR, FB_CUR, 3); FOG_FENCE();                                      \
     L(13);                                                                                         \
-    FOG_FENCE(); FOG_MFMA(2, A3_CUR, FB_CUR, 3); FOG_FENCE();                                      \
+    FOG_FENCE(); MF(2, A3_CUR, FB_CUR, 3); FOG_FENCE();                                      \
     L(14);                                                                                         \
-    FOG_FENCE(); FOG_MFMA(3, A3_CUR, FB_CUR, 3); FOG_FENCE();                                      \
+    FOG_FENCE(); MF(3, A3_CUR, FB_CUR, 3); FOG_FENCE();                                      \
     L(15);                                                                                         \
     FOG_FENCE();                                                                                   \
   } while (0)
@@ -337,7 +338,8 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
   // First K-step of the pair in stage ST: the second half of that stage is read; nothing is loaded
   // and nothing in LDS changes hands, so the waves do not synchronise (the compiler's own counters
   // make each wave wait for its fragment reads).
-#define FOG_STEP_FIRST(ST, FB_IN, FB_CUR, A3_IN, A3_CUR) FOG_STEP_BODY(ST, 1, FB_IN, FB_CUR, A3_IN, A3_CUR, FOG_NO_LOAD)
+#define FOG_STEP_FIRST(ST, FB_IN, FB_CUR, A3_IN, A3_CUR) FOG_STEP_BODY(ST, 1, FB_IN, FB_CUR, A3_IN, A3_CUR, FOG_NO_LOAD, FOG_MFMA)
+#define FOG_STEP_FIRST_Z(ST, FB_IN, FB_CUR, A3_IN, A3_CUR) FOG_STEP_BODY(ST, 1, FB_IN, FB_CUR, A3_IN, A3_CUR, FOG_NO_LOAD, FOG_MFMA_Z)
   // Second K-step of the pair in stage ST.  Wait until this thread's direct loads have landed and its
   // fragment reads have returned, then synchronise: the pair in the other stage is visible to every
   // wave and stage ST, read to the end during the previous step, is free.  Its refill (the pair that
@@ -352,7 +354,7 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
     if (LAX) __builtin_amdgcn_s_waitcnt(0x8070);                                                   \
     else     __builtin_amdgcn_s_waitcnt(0x0070);                                                   \
     __syncthreads();                                                                               \
-    FOG_STEP_BODY(1 - (ST), 0, FB_IN, FB_CUR, A3_IN, A3_CUR, FOG_L##ST);                           \
+    FOG_STEP_BODY(1 - (ST), 0, FB_IN, FB_CUR, A3_IN, A3_CUR, FOG_L##ST, FOG_MFMA);                           \
     advance(pa); advance(pb);                                                                      \
   } while (0)
 #define FOG_L0(n) do { if ((n) < 8) FOG_LOAD_A((n), k0_, 0); else FOG_LOAD_B((n) - 8, k0_, 0); } while (0)
@@ -382,25 +384,32 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
   for (int tile = walk.first; tile < walk.end; tile += walk.stride) {
     const int m_cur = m0, n_cur = n0;
     const int next = tile + walk.stride;
-    for (int kt = 0; kt < nk4; kt += 4) {
-      if (kt == nk4 - 4) {
-        // last four steps of this tile: the loads issued now belong to the next tile (all
-        // zero-fill if there is none, which keeps the outstanding-load count the waits assume)
-        if (next < walk.end) {
-          tile_origin(next, g.tiles_m, g.tiles_n, m0, n0);
-          pa = A_KM ? plan_km(g.lda, m0, g.M, g.K) : plan_kc(g.lda, m0, g.M, g.K);
-          pb = B_KM ? plan_km(g.ldb, n0, g.N, g.K) : plan_kc(g.ldb, n0, g.N, g.K);
-        } else {
-          pa.off[0] = pa.off[1] = pb.off[0] = pb.off[1] = OOB;
-        }
-      }
-      const int ki = kt == nk4 - 4 ? 0 : kt + 4;  // K-step number (within its tile) of the first pair issued below
-      FOG_STEP_FIRST(0, yb, xb, fa3, fa[3]);
-      FOG_STEP_SECOND(0, ki * BK, xb, yb, fa[3], fa3, stores_pending);
-      FOG_STEP_FIRST(1, yb, xb, fa3, fa[3]);
-      FOG_STEP_SECOND(1, ki * BK + PAIR_K, xb, yb, fa[3], fa3, false);
-      stores_pending = false;
-    }
+    // Four K-steps (two pairs) per trip; FIRST_ is the form of the trip's first step.
+#define FOG_TRIP(FIRST_)                                                                             \
+  do {                                                                                               \
+    if (kt == nk4 - 4) {                                                                             \
+      /* last four steps of this tile: the loads issued now belong to the next tile (all zero-fill  \
+         if there is none, which keeps the outstanding-load count the waits assume) */              \
+      if (next < walk.end) {                                                                         \
+        tile_origin(next, g.tiles_m, g.tiles_n, m0, n0);                                             \
+        pa = A_KM ? plan_km(g.lda, m0, g.M, g.K) : plan_kc(g.lda, m0, g.M, g.K);                     \
+        pb = B_KM ? plan_km(g.ldb, n0, g.N, g.K) : plan_kc(g.ldb, n0, g.N, g.K);                     \
+      } else {                                                                                       \
+        pa.off[0] = pa.off[1] = pb.off[0] = pb.off[1] = OOB;                                         \
+      }                                                                                              \
+    }                                                                                                \
+    /* K-step number (within its tile) of the first pair issued below */                             \
+    const int ki = kt == nk4 - 4 ? 0 : kt + 4;                                                       \
+    FIRST_(0, yb, xb, fa3, fa[3]);                                                                   \
+    FOG_STEP_SECOND(0, ki * BK, xb, yb, fa[3], fa3, stores_pending);                                 \
+    FOG_STEP_FIRST(1, yb, xb, fa3, fa[3]);                                                           \
+    FOG_STEP_SECOND(1, ki * BK + PAIR_K, xb, yb, fa[3], fa3, false);                                 \
+    stores_pending = false;                                                                          \
+  } while (0)
+    int kt = 0;
+    FOG_TRIP(FOG_STEP_FIRST_Z);          // the tile's first step starts the accumulators from zero
+    for (kt = 4; kt < nk4; kt += 4) FOG_TRIP(FOG_STEP_FIRST);
+#undef FOG_TRIP
     // fa, xb now hold step 0 of the next tile.
     // Epilogue.  With B as the first MFMA operand, lane l holds for tile (i, j), register r:
     //   row    m = m_cur + wm + 32 i + (l & 31)
@@ -459,12 +468,6 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
         }
       }
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
     stores_pending = fast;  // the slow path is only taken by edge tiles; its stores are simply waited for
     if (!fast) __builtin_amdgcn_s_waitcnt(0x0F70);
   }
@@ -475,6 +478,8 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
 #undef FOG_RA
 #undef FOG_RB
 #undef FOG_MFMA
+#undef FOG_MFMA_Z
+#undef FOG_STEP_FIRST_Z
 #undef FOG_FENCE
 #undef FOG_STEP_BODY
 #undef FOG_NO_LOAD
