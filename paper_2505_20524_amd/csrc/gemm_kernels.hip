@@ -522,7 +522,11 @@ fog_status launch(const GemmArgs& g, hipStream_t s) {
   const int total = g.tiles_m * g.tiles_n;
   int grid = (compute_units() / 8) * 8;
   if (grid < 8) grid = 8;
-  const int need = ((total + 7) / 8) * 8;
+  // The launch takes ceil(total / grid) rounds of tiles whatever happens; the smallest grid that still
+  // needs that many rounds leaves no workgroup idle in the last one and, on a power-limited part,
+  // lets the busy CUs clock higher (896 tiles: 224 workgroups x 4 rounds instead of 256 x 3.5).
+  const int rounds = (total + grid - 1) / grid;
+  const int need = (((total + rounds - 1) / rounds + 7) / 8) * 8;
   if (grid > need) grid = need;
   kern<<<grid, kThreads, LDS_BYTES, s>>>(g);
   return fog_launch_status();
