@@ -167,8 +167,14 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_rowdot_kernel(const uint16_
 // ------------------------------------------------------------------ kernel 1: dK, dV
 // Ring stage: Q tile, dO tile, then 64 lse and 64 D values.  Five direct loads per thread and stage.
 constexpr int KV_STAGE = 2 * TILE + 512;
-template <bool CAUSAL>
-__global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
+// MODE 0 produces dK and dV together (one wave per SIMD: 128 accumulator registers for the outputs plus
+// double-buffered score tiles); MODE 1 produces dV only and MODE 2 dK only, each with 64 accumulator
+// registers and no score prefetch, so that two workgroups share a CU and one's exponentials and casts
+// run under the other's matrix instructions.  The pair 1 + 2 recomputes S once more than MODE 0 and is
+// still the faster route (same results: the arithmetic per output is identical).
+template <bool CAUSAL, int MODE>
+__global__ __launch_bounds__(kThreads, MODE == 0 ? 1 : 2) void attn_bwd_dkdv_kernel(BwdArgs a) {
+  constexpr bool WANT_DV = MODE != 2, WANT_DK = MODE != 1, PREFETCH = MODE == 0;
   __shared__ __attribute__((aligned(1024))) uint8_t smem[NSTAGE * KV_STAGE];
   const int bhk = blockIdx.x % a.BHkv;                 // key/value head; its query heads are bhk * G .. + G - 1
   const int kblk = blockIdx.x / a.BHkv;                // early key blocks see the most queries: launched first
@@ -184,7 +190,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     kf[h] = frag_global(a.K + hoff * HD, wave_on ? key : 0, h);
-    vf[h] = frag_global(a.V + hoff * HD, wave_on ? key : 0, h);
+    if (WANT_DK) vf[h] = frag_global(a.V + hoff * HD, wave_on ? key : 0, h);
   }
   const float rho_p = *a.scale_p, rho_ds = *a.scale_ds;
   const float c = a.softmax_scale * 1.44269504088896340736f * (*a.sinv_q) * (*a.sinv_k);
@@ -195,7 +201,10 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
   for (int d = 0; d < 4; ++d)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { dv[d][r] = 0.0f; dk[d][r] = 0.0f; }
+    for (int r = 0; r < 16; ++r) {
+      if (WANT_DV) dv[d][r] = 0.0f;
+      if (WANT_DK) dk[d][r] = 0.0f;
+    }
 
   const int qb_first = CAUSAL ? (kblk * BLK) / STEP : 0;
   const int nqb = S / STEP - qb_first;                 // query blocks of one head this workgroup walks
@@ -236,33 +245,45 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { st[qt][r] = 0.0f; dp[qt][r] = 0.0f; }
+      for (int r = 0; r < 16; ++r) {
+        st[qt][r] = 0.0f;
+        if (WANT_DK) dp[qt][r] = 0.0f;
+      }
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         st[qt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_rowfrag(sq, rf, qt, h), kf[h], st[qt], 0, 0, 0, 0, 0, 0);
-        dp[qt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_rowfrag(sdo, rf, qt, h), vf[h], dp[qt], 1, 0, 0, 0, 0, 0);
+        if (WANT_DK) dp[qt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_rowfrag(sdo, rf, qt, h), vf[h], dp[qt], 1, 0, 0, 0, 0, 0);
       }
     }
   };
 
-  FOG_SETTLE(kf[0]); FOG_SETTLE(kf[1]); FOG_SETTLE(vf[0]); FOG_SETTLE(vf[1]);
+  FOG_SETTLE(kf[0]); FOG_SETTLE(kf[1]);
+  if (WANT_DK) { FOG_SETTLE(vf[0]); FOG_SETTLE(vf[1]); }
   issue(0);
   issue(1);
   issue(2);
   __builtin_amdgcn_s_waitcnt(0x0F7A);  // vmcnt = 10: block 0 has landed (5 direct loads per thread and block)
   __syncthreads();
-  v16f sa[2], da[2], sb[2], db[2];
-  if (skip == 0 && total > 0) scores(0, sa, da);
+  v16f sa[2], da[2], sb[2], db[2];   // without the prefetch only sa / da are used
+  if (PREFETCH && skip == 0 && total > 0) scores(0, sa, da);
 
   int cur_i = 0;
   auto block = [&](const bool CLAMP_P, int it, v16f* st, v16f* dp, v16f* stn, v16f* dpn) __attribute__((always_inline)) {
-    __builtin_amdgcn_s_waitcnt(0x0075);  // vmcnt = 5: block i + 1 landed; lgkmcnt = 0: own LDS reads done
-    __syncthreads();
+    // vmcnt = 5: block it + 1 has landed (its scores are produced during this block); without the
+    // prefetch only block it is needed and two younger blocks may stay in flight (vmcnt = 10).
+    // lgkmcnt = 0: own LDS reads done
+    if (PREFETCH) __builtin_amdgcn_s_waitcnt(0x0075);
+    else if (it > 0) __builtin_amdgcn_s_waitcnt(0x007A);
+    if (PREFETCH || it > 0) __syncthreads();
     issue(it + 3);
     const int i = cur_i, i_next = i + 1 == nqb ? 0 : i + 1;   // query block within its head, of this block and of the next
     cur_i = i_next;
     const bool cur = i >= skip, nxt = i_next >= skip && it + 1 < total;
-    if (nxt) scores(it + 1, stn, dpn);
+    if (PREFETCH) {
+      if (nxt) scores(it + 1, stn, dpn);
+    } else if (cur) {
+      scores(it, st, dp);
+    }
     if (cur) {
       const uint8_t* sq = smem + (it & (NSTAGE - 1)) * KV_STAGE;
       const uint8_t* sdo = sq + TILE;
@@ -282,29 +303,32 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
         for (int qd = 0; qd < 4; ++qd) {
           const int qi = 32 * qt + 8 * qd + 4 * g;
           const float4 ls = *reinterpret_cast<const float4*>(srow + qi);
-          const float4 dd = *reinterpret_cast<const float4*>(srow + 64 + qi);
+          float4 dd = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+          if (WANT_DK) dd = *reinterpret_cast<const float4*>(srow + 64 + qi);
           const float lsv[4] = {ls.x, ls.y, ls.z, ls.w}, ddv[4] = {dd.x, dd.y, dd.z, dd.w};
           float pq[4], ds[4];
 #pragma unroll
           for (int b = 0; b < 4; ++b) {
             const int r = 4 * qd + b;
             pq[b] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[qt][r], c, -lsv[b]));   // rho_p P
-            ds[b] = pq[b] * __builtin_fmaf(dp[qt][r], cdpk, -ddv[b]);                 // rho_ds dS
+            if (WANT_DK) ds[b] = pq[b] * __builtin_fmaf(dp[qt][r], cdpk, -ddv[b]);    // rho_ds dS
           }
-          if (CLAMP_P) {
-            pf[4 * qt + qd] = (int)cvt4_fp8<FOG_E4M3>(pq[0], pq[1], pq[2], pq[3]);
-          } else {
-            uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(pq[0], pq[1], 0u, false);
-            pf[4 * qt + qd] = (int)__builtin_amdgcn_cvt_pk_fp8_f32(pq[2], pq[3], pk, true);
+          if (WANT_DV) {
+            if (CLAMP_P) {
+              pf[4 * qt + qd] = (int)cvt4_fp8<FOG_E4M3>(pq[0], pq[1], pq[2], pq[3]);
+            } else {
+              uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(pq[0], pq[1], 0u, false);
+              pf[4 * qt + qd] = (int)__builtin_amdgcn_cvt_pk_fp8_f32(pq[2], pq[3], pk, true);
+            }
           }
-          dsf[4 * qt + qd] = (int)cvt4_fp8<FOG_E5M2>(ds[0], ds[1], ds[2], ds[3]);
+          if (WANT_DK) dsf[4 * qt + qd] = (int)cvt4_fp8<FOG_E5M2>(ds[0], ds[1], ds[2], ds[3]);
         }
       }
       // dV^T += dO^T P~ ;  dK^T += Q^T dS~   (contraction over the 64 queries of this step)
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
-        dv[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_colfrag(sdo, cf, d), pf, dv[d], 1, 0, 0, 0, 0, 0);
-        dk[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_colfrag(sq, cf, d), dsf, dk[d], 0, 1, 0, 0, 0, 0);
+        if (WANT_DV) dv[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_colfrag(sdo, cf, d), pf, dv[d], 1, 0, 0, 0, 0, 0);
+        if (WANT_DK) dk[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_colfrag(sq, cf, d), dsf, dk[d], 0, 1, 0, 0, 0, 0);
       }
     }
   };
@@ -332,10 +356,12 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
     for (int qd = 0; qd < 4; ++qd) {
       const int col = 32 * d + 8 * qd + 4 * g;
-      *reinterpret_cast<uint2*>(dvrow + col) = make_uint2(pack_bf16x2(dv[d][4 * qd] * sdv, dv[d][4 * qd + 1] * sdv),
-                                                          pack_bf16x2(dv[d][4 * qd + 2] * sdv, dv[d][4 * qd + 3] * sdv));
-      *reinterpret_cast<uint2*>(dkrow + col) = make_uint2(pack_bf16x2(dk[d][4 * qd] * sdk, dk[d][4 * qd + 1] * sdk),
-                                                          pack_bf16x2(dk[d][4 * qd + 2] * sdk, dk[d][4 * qd + 3] * sdk));
+      if (WANT_DV)
+        *reinterpret_cast<uint2*>(dvrow + col) = make_uint2(pack_bf16x2(dv[d][4 * qd] * sdv, dv[d][4 * qd + 1] * sdv),
+                                                            pack_bf16x2(dv[d][4 * qd + 2] * sdv, dv[d][4 * qd + 3] * sdv));
+      if (WANT_DK)
+        *reinterpret_cast<uint2*>(dkrow + col) = make_uint2(pack_bf16x2(dk[d][4 * qd] * sdk, dk[d][4 * qd + 1] * sdk),
+                                                            pack_bf16x2(dk[d][4 * qd + 2] * sdk, dk[d][4 * qd + 3] * sdk));
     }
 }
 
@@ -520,8 +546,24 @@ extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int H_kv, int S, int D, flo
   const int64_t rows = (int64_t)a.BH * S;
   attn_bwd_rowdot_kernel<<<(int)((rows + 15) / 16), kThreads, 0, s>>>(a.O, a.dO, a.lse, a.scale_p, a.scale_ds, a.Dws, rows);
   const int grid = a.BH * a.nblk, grid_kv = a.BHkv * a.nblk;
-  if (causal) attn_bwd_dkdv_kernel<true><<<grid_kv, kThreads, 0, s>>>(a);
-  else        attn_bwd_dkdv_kernel<false><<<grid_kv, kThreads, 0, s>>>(a);
+  // dV and dK as two launches (two workgroups per CU each) when there are enough key blocks to fill the
+  // chip four times over; with few key/value heads the single combined launch balances better.
+  const bool split = grid_kv >= 1024;
+  if (causal) {
+    if (split) {
+      attn_bwd_dkdv_kernel<true, 1><<<grid_kv, kThreads, 0, s>>>(a);
+      attn_bwd_dkdv_kernel<true, 2><<<grid_kv, kThreads, 0, s>>>(a);
+    } else {
+      attn_bwd_dkdv_kernel<true, 0><<<grid_kv, kThreads, 0, s>>>(a);
+    }
+  } else {
+    if (split) {
+      attn_bwd_dkdv_kernel<false, 1><<<grid_kv, kThreads, 0, s>>>(a);
+      attn_bwd_dkdv_kernel<false, 2><<<grid_kv, kThreads, 0, s>>>(a);
+    } else {
+      attn_bwd_dkdv_kernel<false, 0><<<grid_kv, kThreads, 0, s>>>(a);
+    }
+  }
   if (causal) { if (amax_ds) attn_bwd_dq_kernel<true, true><<<grid, kThreads, 0, s>>>(a); else attn_bwd_dq_kernel<true, false><<<grid, kThreads, 0, s>>>(a); }
   else        { if (amax_ds) attn_bwd_dq_kernel<false, true><<<grid, kThreads, 0, s>>>(a); else attn_bwd_dq_kernel<false, false><<<grid, kThreads, 0, s>>>(a); }
   return fog_launch_status();

@@ -235,6 +235,15 @@ def test_long_context_grouped_query_sampled(B, H, Hkv, S):
             check_bf16(dV[b, hk, j:j + 1], dv, what="dV[%d,%d,%d]" % (b, hk, j), max_flip_frac=1.0, slack=slv)
 
 
+def test_backward_two_launch_form_noncausal():
+    """Enough key blocks (B H_kv S / 128 >= 1024) for dK and dV to be produced by two launches instead of
+    one; non-causal, two heads checked in full (config 3 below covers the causal case of that form)."""
+    B, H, S = 8, 16, 1024
+    q, k, v, do = synth.small_attention(4242, B, H, S)
+    c = cast_all(q, k, v, do)
+    run_bwd(c, B, H, S, 1 / math.sqrt(128), False, [(0, 0), (B - 1, H - 1)], do)
+
+
 def test_config3_full_size_sampled_heads():
     """Config 3 whole on the GPU (B 4, H 16, S 2048, D 128, causal); the oracle checks 3 (batch, head)
     pairs in full (first, last, one seeded), forward and backward; every head is checked for sanity."""
