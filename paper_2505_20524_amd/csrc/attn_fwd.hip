@@ -189,7 +189,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
   if (nkb_wave > 0) scores(0, sc);
 
   // One key block: SC holds this block's scores, SN receives the next block's.
-  auto block = [&](int kb, v16f* sc, v16f* sn) {
+  auto block = [&](const bool CLAMP_P, int kb, v16f* sc, v16f* sn) __attribute__((always_inline)) {
     // block kb + 1 landed (blocks kb + 2 may be in flight: vmcnt = 4), own LDS reads done (lgkmcnt = 0)
     __builtin_amdgcn_s_waitcnt(0x0074);
     __syncthreads();
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
           const float e2 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 2], c, shift));
           const float e3 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 3], c, shift));
           l_run += (e0 + e1) + (e2 + e3);
-          if (clamp_p) {
+          if (CLAMP_P) {
             pf[4 * kt + qd] = (int)cvt4_fp8<FOG_E4M3>(e0, e1, e2, e3);
           } else {
             uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(e0, e1, 0u, false);
@@ -262,9 +262,18 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
       }
     }
   };
-  for (int kb = 0; kb < nkb; kb += 2) {   // two blocks per trip so that the score registers just swap roles
-    block(kb, sc, sn);
-    if (kb + 1 < nkb) block(kb + 1, sn, sc);
+  // The saturating form of the cast is only needed for a scale above the format's maximum; the choice
+  // is made once, outside the loop, so that the loop body has no branch per group of four scores.
+  if (clamp_p) {
+    for (int kb = 0; kb < nkb; kb += 2) {   // two blocks per trip so that the score registers just swap roles
+      block(true, kb, sc, sn);
+      if (kb + 1 < nkb) block(true, kb + 1, sn, sc);
+    }
+  } else {
+    for (int kb = 0; kb < nkb; kb += 2) {
+      block(false, kb, sc, sn);
+      if (kb + 1 < nkb) block(false, kb + 1, sn, sc);
+    }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
 
