@@ -2,7 +2,7 @@
 
 A "step" is one pass of the whole path over one synthetic batch of a BASELINE config (default:
 config 5, the 8B-scale block): for every linear layer the just-in-time casts of X, W, dY
-(abs-max -> scale -> cast, fused with the transpose for the weight gradient) and the forward /
+(abs-max -> scale -> cast in one call, fused with the transpose for the weight gradient) and the forward /
 data-gradient / weight-gradient FP8 GEMMs, then the casts of Q, K, V, dO and FP8 causal
 attention forward and backward.  Inputs are resident in HBM before the timed region.
 
@@ -11,7 +11,7 @@ step's wall time, casts included in the time), plus
   roofline      -- the dominant kernel (the FP8 GEMM), timed per launch with HIP events on the
                    launch stream inside the timed region,
   cpu_baseline  -- the CPU oracle timed on a bounded sample of the same workload,
-  kernels       -- the same per-class figures for attention, cast and abs-max, from a second set of
+  kernels       -- the same per-class figures for attention and the just-in-time cast, from a second set of
                    passes outside the timed region (event pairs around small kernels cost as much
                    as the kernels themselves and would distort the headline figure).
 """

@@ -111,16 +111,14 @@ fog_status fog_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t 
 /*
  * Just-in-time scaling in one call (Section 2: abs-max of the tensor being cast, then the cast;
  * Appendix E for the scale): the same results, bit for bit, as fog_amax -> fog_scale -> fog_quantize,
- * in two launches instead of four.  The abs-max pass ends in the workgroup that finishes last,
- * which derives the scale; the cast pass follows on the same stream.  Meant for small tensors,
- * where launches dominate: every workgroup of the abs-max pass ends with a device-wide fence, so on
- * tensors of tens of megabytes the three separate calls are the faster route.
+ * in three launches instead of four and without atomics: every workgroup of the abs-max pass leaves
+ * its maximum in its own word of the workspace, one small workgroup reduces the words and derives
+ * the scale, the cast pass follows on the same stream.
  *   amax, scale : one float each, overwritten.   scale_inv : one float or NULL.
  *   q, qT, x_bf16, leading dimensions, fmt : as in fog_quantize.   margin : as in fog_scale.
- *   workspace : fog_quantize_jit_workspace() bytes, 4-byte aligned, owned by the caller.  It must
- *               hold zeros before the first call; every call leaves it zeroed, so one workspace
- *               serves any number of calls that do not overlap in time (calls on different
- *               streams need one each).
+ *   workspace : fog_quantize_jit_workspace() bytes (4 KB), 4-byte aligned, owned by the caller; its
+ *               contents on entry do not matter.  Calls that may overlap in time (different
+ *               streams) need a workspace each.
  * Errors: as fog_quantize and fog_scale; WORKSPACE when the workspace is too small.
  */
 fog_status fog_quantize_jit(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, fog_fp8 fmt, int margin,

@@ -35,28 +35,22 @@ class Cast:
         self.amax = torch.zeros(1, device="cuda")
         self.scale = torch.ones(1, device="cuda")
         self.sinv = torch.ones(1, device="cuda")
-        self.ws = torch.zeros(2, dtype=torch.int32, device="cuda")   # for run_jit: zeroed once, every call leaves it zeroed
-        self.bytes_amax = 2 * rows * cols
-        self.bytes_cast = (3 + (1 if transpose else 0)) * rows * cols
+        self.ws = torch.empty(fog.quantize_jit_workspace(), dtype=torch.uint8, device="cuda")
+        self.bytes_jit = (5 + (1 if transpose else 0)) * rows * cols   # abs-max pass 2 B, cast pass 2 B in + 1 (+1 transposed) out
 
     def run(self, timer=None):
-        """Just-in-time scaling through the three calls: abs-max, scale, cast.  On large tensors this is
-        faster than the one-call form, whose abs-max pass ends every workgroup with a device-wide fence."""
+        """Just-in-time scaling in one call: abs-max pass (per-workgroup maxima), reduce + scale, cast."""
         if timer:
-            timer.begin("amax", self.bytes_amax)
-        fog.amax(self.x, self.amax)
-        if timer:
-            timer.end()
-        fog.scale(self.amax, self.fmt, self.scale, self.sinv)
-        if timer:
-            timer.begin("cast", self.bytes_cast)
-        fog.quantize(self.x, self.fmt, self.scale, q=self.q, qT=self.qT)
+            timer.begin("cast_jit", self.bytes_jit)
+        fog.quantize_jit(self.x, self.fmt, self.amax, self.scale, self.sinv, self.ws, q=self.q, qT=self.qT)
         if timer:
             timer.end()
 
-    def run_jit(self):
-        """The same flow in one call (two launches instead of four)."""
-        fog.quantize_jit(self.x, self.fmt, self.amax, self.scale, self.sinv, self.ws, q=self.q, qT=self.qT)
+    def run_separate(self):
+        """The same flow through the three calls fog_amax, fog_scale, fog_quantize (four launches)."""
+        fog.amax(self.x, self.amax)
+        fog.scale(self.amax, self.fmt, self.scale, self.sinv)
+        fog.quantize(self.x, self.fmt, self.scale, q=self.q, qT=self.qT)
 
 
 class LinearStep:

@@ -18,35 +18,23 @@ __global__ void zero_u32_kernel(uint32_t* p) { *p = 0u; }
 // bf16 magnitudes order like unsigned 16-bit integers, so the running maximum is a packed
 // u16 max over the sign-cleared bit patterns; the result is the float whose upper half is it.
 //
-// JIT: the just-in-time flow in one launch.  `out` is then a zero-initialised accumulator in the
-// caller's workspace, followed by a ticket counter; the workgroup that draws the last ticket has
-// the final maximum, derives the scale from it, publishes abs-max / scale / 1/scale and puts the
-// two workspace words back to zero for the next call.
+// PARTIALS: the form used by the one-call just-in-time flow.  Every workgroup stores its maximum in
+// its own word of the caller's workspace (no atomics, no zero-initialisation, no fence); a
+// one-workgroup kernel then reduces the words and derives the scale.
 FOG_DEVICE void scale_from_amax(float a, int fmt, int margin, float* scale, float* scale_inv);
-struct JitOut {
-  float* amax;
-  float* scale;
-  float* scale_inv;
-  int fmt, margin;
-};
-FOG_DEVICE void publish_block_max(uint32_t r, uint32_t* out, bool jit, const JitOut& j) {
+FOG_DEVICE void publish_block_max(uint32_t r, uint32_t* out, bool partials) {
+  if (partials) {
+    out[blockIdx.x] = r << 16;
+    return;
+  }
   // same-address atomics are served one at a time: skip the ones that cannot raise the maximum
   if (r && (r << 16) > __hip_atomic_load(out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(out, r << 16);
-  if (!jit) return;
-  __threadfence();
-  if (atomicAdd(out + 1, 1u) == gridDim.x - 1) {
-    __threadfence();
-    const float a = __uint_as_float(atomicExch(out, 0u));
-    atomicExch(out + 1, 0u);
-    *j.amax = a;
-    scale_from_amax(a, j.fmt, j.margin, j.scale, j.scale_inv);
-  }
 }
 
-template <bool JIT>
+template <bool PARTIALS>
 __global__ __launch_bounds__(kThreads) void amax_kernel(const uint4* __restrict__ x, int64_t nvec,
                                                         const uint16_t* __restrict__ tail, int ntail,
-                                                        uint32_t* __restrict__ out, JitOut jit) {
+                                                        uint32_t* __restrict__ out) {
   // Every workgroup owns one contiguous span and walks it in batches of eight 16-byte loads per
   // thread; the next batch is requested before the current one is reduced, so loads never stop.
   constexpr int NL = 8;
@@ -99,14 +87,14 @@ __global__ __launch_bounds__(kThreads) void amax_kernel(const uint4* __restrict_
     uint32_t r = part[0];
 #pragma unroll
     for (int w = 1; w < kThreads / 64; ++w) r = r > part[w] ? r : part[w];
-    publish_block_max(r, out, JIT, jit);
+    publish_block_max(r, out, PARTIALS);
   }
 }
 
 // Abs-max of a matrix whose rows are not contiguous or not 16-byte aligned (slow, same result).
-template <bool JIT>
+template <bool PARTIALS>
 __global__ __launch_bounds__(kThreads) void amax_strided_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
-                                                                int64_t ldx, uint32_t* __restrict__ out, JitOut jit) {
+                                                                int64_t ldx, uint32_t* __restrict__ out) {
   const int64_t total = rows * cols;
   uint32_t m = 0;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
@@ -122,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void amax_strided_kernel(const uint16_t* 
     uint32_t r = part[0];
 #pragma unroll
     for (int w = 1; w < kThreads / 64; ++w) r = r > part[w] ? r : part[w];
-    publish_block_max(r, out, JIT, jit);
+    publish_block_max(r, out, PARTIALS);
   }
 }
 
@@ -142,6 +130,25 @@ FOG_DEVICE void scale_from_amax(float a, int fmt, int margin, float* scale, floa
 
 __global__ void scale_kernel(const float* amax, int fmt, int margin, float* scale, float* scale_inv) {
   scale_from_amax(*amax, fmt, margin, scale, scale_inv);
+}
+
+// One workgroup: maximum of the per-workgroup maxima of the abs-max pass, then the scale.
+__global__ __launch_bounds__(kThreads) void scale_partials_kernel(const uint32_t* __restrict__ part, int n, int fmt, int margin,
+                                                                 float* amax, float* scale, float* scale_inv) {
+  uint32_t m = 0;
+  for (int i = threadIdx.x; i < n; i += kThreads) m = m > part[i] ? m : part[i];   // non-negative floats order like their bits
+  m = wave_max_u32(m);
+  __shared__ uint32_t wmax[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t r = wmax[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) r = r > wmax[w] ? r : wmax[w];
+    const float a = __uint_as_float(r);
+    *amax = a;
+    scale_from_amax(a, fmt, margin, scale, scale_inv);
+  }
 }
 
 // One workgroup: roll the history by one (newest first), then scale from its maximum.
@@ -370,7 +377,7 @@ extern "C" fog_status fog_amax(const void* x_bf16, int64_t n, float* amax, void*
     if (blocks < 1) blocks = 1;
     amax_kernel<false><<<(int)blocks, kThreads, 0, s>>>(reinterpret_cast<const uint4*>(x_bf16), nvec,
                                                         reinterpret_cast<const uint16_t*>(x_bf16) + nvec * 8, ntail,
-                                                        reinterpret_cast<uint32_t*>(amax), JitOut{});
+                                                        reinterpret_cast<uint32_t*>(amax));
   }
   return fog_launch_status();
 }
@@ -455,7 +462,9 @@ extern "C" fog_status fog_quantize(const void* x_bf16, int64_t rows, int64_t col
   return fog_launch_status();
 }
 
-extern "C" size_t fog_quantize_jit_workspace(void) { return 2 * sizeof(uint32_t); }
+constexpr int kJitBlocks = 1024;   // workgroups of the abs-max pass = words of workspace
+
+extern "C" size_t fog_quantize_jit_workspace(void) { return kJitBlocks * sizeof(uint32_t); }
 
 extern "C" fog_status fog_quantize_jit(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, fog_fp8 fmt, int margin,
                                        uint8_t* q, int64_t ldq, uint8_t* qT, int64_t ldqT,
@@ -470,27 +479,24 @@ extern "C" fog_status fog_quantize_jit(const void* x_bf16, int64_t rows, int64_t
   hipStream_t s = (hipStream_t)stream;
   const uint16_t* x = reinterpret_cast<const uint16_t*>(x_bf16);
   uint32_t* ws = reinterpret_cast<uint32_t*>(workspace);
-  const JitOut jit{amax, scale, scale_inv, (int)fmt, margin};
   const int64_t n = rows * cols;
-  if (n == 0) {
-    // nothing to scan: abs-max 0, scale 1 (one workgroup draws the only ticket)
-    amax_strided_kernel<true><<<1, kThreads, 0, s>>>(x, 0, 1, 1, ws, jit);
-    return fog_launch_status();
+  int64_t blocks = 0;   // an empty tensor: no partial maxima, abs-max 0, scale 1
+  if (n > 0) {
+    if ((ldx == cols || rows == 1) && aligned16(x_bf16)) {
+      const int64_t nvec = n / 8;
+      const int ntail = (int)(n - nvec * 8);
+      blocks = (nvec + kThreads * 8 - 1) / (kThreads * 8);
+      if (blocks > kJitBlocks) blocks = kJitBlocks;
+      if (blocks < 1) blocks = 1;
+      amax_kernel<true><<<(int)blocks, kThreads, 0, s>>>(reinterpret_cast<const uint4*>(x), nvec, x + nvec * 8, ntail, ws);
+    } else {
+      blocks = (n + kThreads - 1) / kThreads;
+      if (blocks > kJitBlocks) blocks = kJitBlocks;
+      amax_strided_kernel<true><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, ws);
+    }
   }
-  if ((ldx == cols || rows == 1) && aligned16(x_bf16)) {
-    const int64_t nvec = n / 8;
-    const int ntail = (int)(n - nvec * 8);
-    int64_t blocks = (nvec + kThreads * 8 - 1) / (kThreads * 8);
-    // fewer workgroups than fog_amax: each one ends with a device-wide fence and a ticket, which cost
-    // more than the scan gains from a wider launch
-    if (blocks > 512) blocks = 512;
-    if (blocks < 1) blocks = 1;
-    amax_kernel<true><<<(int)blocks, kThreads, 0, s>>>(reinterpret_cast<const uint4*>(x), nvec, x + nvec * 8, ntail, ws, jit);
-  } else {
-    int64_t blocks = (n + kThreads - 1) / kThreads;
-    if (blocks > 4096) blocks = 4096;
-    amax_strided_kernel<true><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, ws, jit);
-  }
+  scale_partials_kernel<<<1, kThreads, 0, s>>>(ws, (int)blocks, (int)fmt, margin, amax, scale, scale_inv);
+  if (n == 0) return fog_launch_status();
   if (fmt == FOG_E4M3) launch_quantize<FOG_E4M3>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, nullptr, s);
   else                 launch_quantize<FOG_E5M2>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, nullptr, s);
   return fog_launch_status();
