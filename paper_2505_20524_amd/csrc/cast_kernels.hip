@@ -20,7 +20,8 @@ __global__ void zero_u32_kernel(uint32_t* p) { *p = 0u; }
 //
 // PARTIALS: the form used by the one-call just-in-time flow.  Every workgroup stores its maximum in
 // its own word of the caller's workspace (no atomics, no zero-initialisation, no fence); a
-// one-workgroup kernel then reduces the words and derives the scale.
+// one-workgroup kernel then reduces the words and derives the scale.  This form reads with ordinary
+// (cache-retaining) loads, because the cast pass re-reads the tensor right away, back to front.
 FOG_DEVICE void scale_from_amax(float a, int fmt, int margin, float* scale, float* scale_inv);
 FOG_DEVICE void publish_block_max(uint32_t r, uint32_t* out, bool partials) {
   if (partials) {
@@ -46,7 +47,7 @@ __global__ __launch_bounds__(kThreads) void amax_kernel(const uint4* __restrict_
   bool have = i + (NL - 1) * kThreads < b1;
   if (have) {
 #pragma unroll
-    for (int k = 0; k < NL; ++k) v[k] = ld_nt16(x + i + k * kThreads);
+    for (int k = 0; k < NL; ++k) v[k] = PARTIALS ? x[i + k * kThreads] : ld_nt16(x + i + k * kThreads);
   }
   while (have) {
     const int64_t n = i + NL * kThreads;
@@ -54,7 +55,7 @@ __global__ __launch_bounds__(kThreads) void amax_kernel(const uint4* __restrict_
     uint4 nx[NL];
     if (more) {
 #pragma unroll
-      for (int k = 0; k < NL; ++k) nx[k] = ld_nt16(x + n + k * kThreads);
+      for (int k = 0; k < NL; ++k) nx[k] = PARTIALS ? x[n + k * kThreads] : ld_nt16(x + n + k * kThreads);
     }
 #pragma unroll
     for (int k = 0; k < NL; ++k) {
@@ -198,12 +199,16 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t*
   const int64_t total = rows * chunks_per_row;
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   uint32_t m = 0;
+  // Chunks are visited back to front: under just-in-time scaling the abs-max pass ran front to back
+  // just before, so the END of the tensor is what the caches still hold.
   auto src_of = [&](int64_t i) {
+    i = total - 1 - i;
     if (rows == 1) return x + i * 16;
     const int64_t r = i / chunks_per_row, c = i - r * chunks_per_row;
     return x + r * ldx + c * 16;
   };
   auto dst_of = [&](int64_t i) {
+    i = total - 1 - i;
     if (rows == 1) return q + i * 16;
     const int64_t r = i / chunks_per_row, c = i - r * chunks_per_row;
     return q + r * ldq + c * 16;
@@ -272,8 +277,9 @@ __global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const uint
                                                                       uint32_t* __restrict__ amax_out, int tiles_c) {
   __shared__ __attribute__((aligned(16))) uint8_t tile[kTile * kTile];  // [col][row], chunk-swizzled
   const float rho = *scale;
-  const int64_t r0 = (int64_t)(blockIdx.x / tiles_c) * kTile;
-  const int64_t c0 = (int64_t)(blockIdx.x % tiles_c) * kTile;
+  const int bid = gridDim.x - 1 - blockIdx.x;   // tiles back to front (see quantize_rows_kernel)
+  const int64_t r0 = (int64_t)(bid / tiles_c) * kTile;
+  const int64_t c0 = (int64_t)(bid % tiles_c) * kTile;
   uint32_t m = 0;
 #pragma unroll
   for (int it = 0; it < 2; ++it) {
