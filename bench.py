@@ -2,8 +2,8 @@
 
 A "step" is one pass of the whole path over one synthetic batch of a BASELINE config (default:
 config 5, the 8B-scale block): for every linear layer the just-in-time casts of X, W, dY
-(abs-max -> scale -> cast in one call, fused with the transpose for the weight gradient) and the forward /
-data-gradient / weight-gradient FP8 GEMMs, then the casts of Q, K, V, dO and FP8 causal
+(abs-max -> scale -> cast in one call) and the forward (NT) / data-gradient (NN) / weight-gradient (TN) FP8
+GEMMs, then the casts of Q, K, V, dO and FP8 causal
 attention forward and backward.  Inputs are resident in HBM before the timed region.
 
 Prints ONE JSON line: metric = FP8 TFLOP/s of the whole step (GEMM + attention FLOPs over the
@@ -144,6 +144,27 @@ def main():
         n, work, ms = kt.summary()["kurtosis"]
         kernels["kurtosis_monitor"] = {"launches": n, "avg_launch_ms": ms / n, "achieved": work / (ms * 1e-3) / 1e9,
                                        "unit": "GB/s", "frac": work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "in_timed_step": False}
+    # The cast fused with the transpose (the arrangement for a weight gradient computed as NT on transposed
+    # copies).  The timed step does not need it: its weight gradients are TN products on the row-major casts,
+    # the kernel gathering the contraction index with the transposing LDS read.  Timed on its own over the
+    # activations and output gradients of every linear layer (2 B read + 2 B written per element).
+    if blk.linears and not blk.linears[0].transposed_wgrad:
+        tt = block.EventTimer()
+        for l in blk.linears:
+            for c in (l.X, l.dY):
+                rows, cols = c.x.shape
+                qT = torch.empty((cols, rows), dtype=torch.uint8, device="cuda")
+                for rep in range(3):
+                    if rep:
+                        tt.begin("cast_transpose", 4 * rows * cols)
+                    fog.quantize(c.x, c.fmt, c.scale, q=c.q, qT=qT)
+                    if rep:
+                        tt.end()
+                del qT
+        torch.cuda.synchronize()
+        n, work, ms = tt.summary()["cast_transpose"]
+        kernels["cast_transpose"] = {"launches": n, "avg_launch_ms": ms / n, "achieved": work / (ms * 1e-3) / 1e9,
+                                     "unit": "GB/s", "frac": work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "in_timed_step": False}
     # The fused QK-RMSNorm + cast producer (an alternative source of the Q / K bytes, not part of the timed
     # step, whose casts are the plain per-tensor ones): timed on its own over the step's Q and K tensors.
     if blk.attn is not None:

@@ -54,12 +54,21 @@ class Cast:
 
 
 class LinearStep:
-    def __init__(self, lin, tensors):
+    """Casts and the three GEMMs of one linear layer.
+
+    transposed_wgrad=False (default): the weight gradient dW = dY~^T X~ is computed in the TN layout straight
+    from the row-major casts; the kernel gathers the contraction index with the byte-transposing LDS read, so
+    no transposed copy of X~ or dY~ is ever written.  transposed_wgrad=True: the casts also emit transposed
+    copies (fused cast + transpose) and dW is an NT product on them, the arrangement for hardware without a
+    transposing read; same results bit for bit."""
+
+    def __init__(self, lin, tensors, transposed_wgrad=False):
         self.lin = lin
+        self.transposed_wgrad = transposed_wgrad
         M, N, K = lin.M, lin.N, lin.K
-        self.X = Cast(_dev_bits(tensors["X"]), E4M3, transpose=True)
+        self.X = Cast(_dev_bits(tensors["X"]), E4M3, transpose=transposed_wgrad)
         self.W = Cast(_dev_bits(tensors["W"]), E4M3, transpose=False)
-        self.dY = Cast(_dev_bits(tensors["dY"]), E5M2, transpose=True)
+        self.dY = Cast(_dev_bits(tensors["dY"]), E5M2, transpose=transposed_wgrad)
         self.Y = torch.empty((M, N), dtype=torch.int16, device="cuda")
         self.dX = torch.empty((M, K), dtype=torch.int16, device="cuda")
         self.dW = torch.empty((N, K), dtype=torch.int16, device="cuda")
@@ -83,10 +92,13 @@ class LinearStep:
         fog.fp8_gemm(fog.NN, M, K, N, self.dY.q, E5M2, self.dY.sinv, self.W.q, E4M3, self.W.sinv, self.dX)
         if timer:
             timer.end()
-        # weight gradient  dW = dY~^T X~, as NT on the transposed copies the cast kernel emitted
+        # weight gradient  dW = dY~^T X~  (contraction over the M tokens, the row index of both operands)
         if timer:
             timer.begin("gemm", f)
-        fog.fp8_gemm(fog.NT, N, K, M, self.dY.qT, E5M2, self.dY.sinv, self.X.qT, E4M3, self.X.sinv, self.dW)
+        if self.transposed_wgrad:
+            fog.fp8_gemm(fog.NT, N, K, M, self.dY.qT, E5M2, self.dY.sinv, self.X.qT, E4M3, self.X.sinv, self.dW)
+        else:
+            fog.fp8_gemm(fog.TN, N, K, M, self.dY.q, E5M2, self.dY.sinv, self.X.q, E4M3, self.X.sinv, self.dW)
         if timer:
             timer.end()
 
@@ -137,7 +149,10 @@ class Block:
 
     def __init__(self, cfg):
         self.cfg = cfg
-        self.linears = [LinearStep(lin, synth.linear_tensors(cfg, i)) for i, lin in enumerate(cfg.linears)]
+        # config 2 is stated with the fused cast + transpose for the weight gradient; the block configs leave the
+        # arrangement open and use the TN product on the row-major casts
+        self.linears = [LinearStep(lin, synth.linear_tensors(cfg, i), transposed_wgrad=(cfg.cid == 2))
+                        for i, lin in enumerate(cfg.linears)]
         self.attn = AttentionStep(cfg.attn, synth.attention_tensors(cfg)) if cfg.attn is not None else None
         self.flops = sum(l.flops for l in self.linears) + (self.attn.flops if self.attn else 0)
 

@@ -45,7 +45,9 @@ def run_config(cid):
     cfg = synth.CONFIGS[cid]
     for idx, lin in enumerate(cfg.linears):
         t = synth.linear_tensors(cfg, idx)
-        step = block.LinearStep(lin, t)
+        # the first linear in the arrangement with transposed copies (fused cast + transpose, NT weight gradient),
+        # the others as the benchmark runs them (row-major casts, TN weight gradient): both at full size
+        step = block.LinearStep(lin, t, transposed_wgrad=(idx == 0))
         step.run()
         torch.cuda.synchronize()
         rm = sample_rows(lin.M, seed=idx)
