@@ -210,7 +210,7 @@ FOG_DEVICE v8i read_frag(const uint8_t* stage, const FragAddr& fa, int i, int h)
 
 // Tile order.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Every XCD
 // owns one contiguous run of logical tile numbers and its workgroups walk that run together, so that
-// the tiles in flight on an XCD at any time are neighbours (groups of 8 tile rows, column by
+// the tiles in flight on an XCD at any time are neighbours (groups of 4 tile rows, column by
 // column) and share a few A and B panels.
 struct TileWalk {
   int first, end, stride;  // logical tile numbers of this workgroup: first, first + stride, ... < end
@@ -225,7 +225,7 @@ FOG_DEVICE TileWalk tile_walk(int total) {
   return t;
 }
 FOG_DEVICE void tile_origin(int logical, int tiles_m, int tiles_n, int& m0, int& n0) {
-  constexpr int GM = 8;
+  constexpr int GM = 4;   // 4 tile rows x 8 tile columns in flight per XCD: the A panels of a group (4 x 256 rows x K) about fit its 4 MB L2
   const int width = GM * tiles_n;
   const int group = logical / width;
   const int first_m = group * GM;
