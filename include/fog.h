@@ -149,6 +149,25 @@ fog_status fog_rmsnorm_quantize(const void* x_bf16, int64_t rows, int64_t cols, 
                                 const float* scale, uint8_t* q, int64_t ldq, float* amax_out, void* stream);
 
 /*
+ * xIELU activation fused with the FP8 cast (Appendix B, equation xIELU: the activation of the
+ * FOG-max variant, between the two GEMMs of the feed-forward block):
+ *     y = alpha_p x^2 + 0.5 x                       for x > 0
+ *     y = alpha_n (e^x - 1) - alpha_n x + 0.5 x     for x <= 0        (binary32; e^x - 1 by expm1)
+ *     q = sat_rne_fmt( fl32( y * scale ) ),         amax_out = max |y| over the matrix.
+ * The scale is the caller's (delayed scaling, fed by amax_out).  y is never stored, so a code is a
+ * rounding decision on a binary32 value: codes agree with a float64 evaluation except where
+ * scale * y lies within about 2^-20 (relative) of a rounding boundary.
+ *   x_bf16 : [rows, cols] bfloat16, leading dimension ldx.   q : [rows, cols] bytes, leading dimension ldq.
+ *   alpha_p, alpha_n : >= 0 and finite (the layer's two scalars as plain numbers).
+ *   amax_out : NULL or one float, overwritten.
+ * Fast path: cols, ldx, ldq multiples of 16 and 16-byte aligned pointers; other shapes take an
+ * element-wise kernel with the same arithmetic.
+ * Errors: NULL, SHAPE, ALIGN (odd x), UNSUPPORTED (format, negative or non-finite alpha).
+ */
+fog_status fog_xielu_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, float alpha_p, float alpha_n,
+                              fog_fp8 fmt, const float* scale, uint8_t* q, int64_t ldq, float* amax_out, void* stream);
+
+/*
  * Activation kurtosis, the paper's outlier diagnostic (Section 4): for each token vector x (a row),
  * kurt(x) = mu[x^4] / (mu[x^2])^2 (element-wise powers, x not centred); the result is the mean over
  * the rows.  The denominator is read as the squared un-centred second moment (1 for a constant

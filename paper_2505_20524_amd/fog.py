@@ -29,6 +29,7 @@ SIGNATURES = {
     "fog_quantize_jit": (_I, [_P, _I64, _I64, _I64, _I, _I, _P, _I64, _P, _I64, _P, _P, _P, _P, _SZ, _P]),
     "fog_quantize_jit_workspace": (_SZ, []),
     "fog_rmsnorm_quantize": (_I, [_P, _I64, _I64, _I64, _F, _I, _P, _P, _I64, _P, _P]),
+    "fog_xielu_quantize": (_I, [_P, _I64, _I64, _I64, _F, _F, _I, _P, _P, _I64, _P, _P]),
     "fog_kurtosis": (_I, [_P, _I64, _I64, _I64, _P, _P]),
     "fog_fp8_gemm": (_I, [_I, _I64, _I64, _I64, _P, _I, _I64, _P, _P, _I, _I64, _P, _P, _I64, _P, _SZ, _P]),
     "fog_fp8_gemm_workspace": (_SZ, [_I, _I64, _I64, _I64]),
@@ -116,6 +117,13 @@ def rmsnorm_quantize(x, fmt, scale_t, q, gain=1.0, amax_out=None, stream=None):
     _check(load().fog_rmsnorm_quantize(_ptr(x), rows, cols, x.stride(0), gain, fmt, _ptr(scale_t), _ptr(q),
                                        q.stride(0) if q is not None else 0, _ptr(amax_out), _stream(stream)),
            "fog_rmsnorm_quantize")
+
+
+def xielu_quantize(x, alpha_p, alpha_n, fmt, scale_t, q, amax_out=None, stream=None):
+    rows, cols = x.shape
+    _check(load().fog_xielu_quantize(_ptr(x), rows, cols, x.stride(0), alpha_p, alpha_n, fmt, _ptr(scale_t), _ptr(q),
+                                     q.stride(0) if q is not None else 0, _ptr(amax_out), _stream(stream)),
+           "fog_xielu_quantize")
 
 
 def kurtosis(x, out, stream=None):
