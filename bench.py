@@ -100,7 +100,8 @@ def main():
         blk.step()
     torch.cuda.synchronize()
     # Timed region: exactly `steps` passes.  HIP events (recorded on the launch stream, torch's current
-    # stream) bracket every launch of the dominant kernel, the FP8 GEMM, inside this region.  The other
+    # stream) bracket the launches of the dominant kernel, the FP8 GEMM, inside this region: one pair around
+    # the three back-to-back products of each linear layer, whose time divided by three is the launch average.  The other
     # kernel classes are timed the same way in a second, untimed set of passes: an event pair costs
     # several microseconds, and 74 of them per step would lower the headline figure by several per cent.
     dominant = "gemm" if blk.linears else "attn_fwd"

@@ -79,22 +79,15 @@ class LinearStep:
         M, N, K = lin.M, lin.N, lin.K
         for c in (self.X, self.W, self.dY):
             c.run(timer)
-        f = 2 * M * N * K
+        # The three products are launched back to back and bracketed by ONE event pair (an event between two
+        # launches costs a gap of several microseconds on the stream): the pair's time is that of three launches.
+        if timer:
+            timer.begin("gemm", 3 * 2 * M * N * K, launches=3)
         # forward  Y = X~ W~^T
-        if timer:
-            timer.begin("gemm", f)
         fog.fp8_gemm(fog.NT, M, N, K, self.X.q, E4M3, self.X.sinv, self.W.q, E4M3, self.W.sinv, self.Y)
-        if timer:
-            timer.end()
         # data gradient  dX = dY~ W~  (W~ is [N, K]: the contraction index N is its row index)
-        if timer:
-            timer.begin("gemm", f)
         fog.fp8_gemm(fog.NN, M, K, N, self.dY.q, E5M2, self.dY.sinv, self.W.q, E4M3, self.W.sinv, self.dX)
-        if timer:
-            timer.end()
         # weight gradient  dW = dY~^T X~  (contraction over the M tokens, the row index of both operands)
-        if timer:
-            timer.begin("gemm", f)
         if self.transposed_wgrad:
             fog.fp8_gemm(fog.NT, N, K, M, self.dY.qT, E5M2, self.dY.sinv, self.X.qT, E4M3, self.X.sinv, self.dW)
         else:
@@ -171,26 +164,26 @@ class EventTimer:
         self._open = None
         self.only = only        # None: every kind; else the set of kinds to record (events cost time themselves)
 
-    def begin(self, kind, work):
+    def begin(self, kind, work, launches=1):
         if self.only is not None and kind not in self.only:
             return
         e0 = torch.cuda.Event(enable_timing=True)
         e0.record()
-        self._open = (kind, work, e0)
+        self._open = (kind, work, e0, launches)
 
     def end(self):
         if self._open is None:
             return
-        kind, work, e0 = self._open
+        kind, work, e0, launches = self._open
         e1 = torch.cuda.Event(enable_timing=True)
         e1.record()
-        self.spans.append((kind, work, e0, e1))
+        self.spans.append((kind, work, e0, e1, launches))
         self._open = None
 
     def summary(self):
         """kind -> (launches, total work, total milliseconds); call after a synchronize."""
         out = {}
-        for kind, work, e0, e1 in self.spans:
+        for kind, work, e0, e1, launches in self.spans:
             n, w, ms = out.get(kind, (0, 0, 0.0))
-            out[kind] = (n + 1, w + work, ms + e0.elapsed_time(e1))
+            out[kind] = (n + launches, w + work, ms + e0.elapsed_time(e1))
         return out
