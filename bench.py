@@ -72,6 +72,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--vendor-context", action="store_true",
+                    help="also time the vendor library's FP8 GEMM (torch._scaled_mm) on the forward shapes: context only, "
+                         "never on the path and never part of `value`")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
@@ -200,6 +203,36 @@ def main():
         n, work, ms = xt.summary()["xielu"]
         kernels["xielu_cast"] = {"launches": n, "avg_launch_ms": ms / n, "achieved": work / (ms * 1e-3) / 1e9,
                                  "unit": "GB/s", "frac": work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "in_timed_step": False}
+    context = None
+    if args.vendor_context and blk.linears:
+        # Context only: the same forward products (NT, E4M3 x E4M3 -> bf16) through the vendor library, next to
+        # this library's kernel on identical operands, each timed over 10 back-to-back launches.
+        def timed(fn, iters=10):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / iters
+        one = torch.ones(1, device="cuda")
+        context = {"kind": "vendor FP8 GEMM via torch._scaled_mm, forward shapes, TFLOP/s", "shapes": []}
+        for l in blk.linears:
+            M, N, K = l.lin.M, l.lin.N, l.lin.K
+            a8, b8 = l.X.q.view(torch.float8_e4m3fn), l.W.q.view(torch.float8_e4m3fn)
+            entry = {"M": M, "N": N, "K": K}
+            ms = timed(lambda: fog.fp8_gemm(fog.NT, M, N, K, l.X.q, fog.E4M3, one, l.W.q, fog.E4M3, one, l.Y))
+            entry["this_library"] = 2.0 * M * N * K / ms / 1e9
+            try:
+                ms = timed(lambda: torch._scaled_mm(a8, b8.t(), scale_a=one, scale_b=one, out_dtype=torch.bfloat16))
+                entry["vendor"] = 2.0 * M * N * K / ms / 1e9
+            except Exception as e:      # the vendor path is optional context
+                entry["vendor"] = None
+                entry["vendor_error"] = repr(e)[:200]
+            context["shapes"].append(entry)
     g = kernels.get("gemm") or kernels.get("attn_fwd")
     roofline = {"bound": "mfma", "kernel": "fp8_gemm_kernel" if "gemm" in kernels else "attn_fwd_kernel",
                 "achieved": g["achieved"], "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": g["frac"],
@@ -214,6 +247,8 @@ def main():
         "frac_of_fp8_peak": value / PEAK_FP8_TFLOPS,
         "roofline": roofline, "kernels": kernels,
     }
+    if context is not None:
+        out["context"] = context
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
