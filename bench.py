@@ -1,6 +1,6 @@
 """Benchmark of the FP8 hot path on one MI355X.
 
-A "step" is one pass of the whole path over one synthetic batch of a BASELINE config (default:
+A "step" is one pass of the whole path over one synthetic batch of a benchmark config (default:
 config 5, the 8B-scale block): for every linear layer the just-in-time casts of X, W, dY
 (abs-max -> scale -> cast in one call) and the forward (NT) / data-gradient (NN) / weight-gradient (TN) FP8
 GEMMs, then the casts of Q, K, V, dO and FP8 causal
