@@ -28,8 +28,8 @@ PEAK_FP8_TFLOPS = 5033.0     # 256 CU x 4 SIMD x 2048 FLOP/clk x 2.4 GHz (dense 
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per fp8_gemm_kernel launch (average over the step's 15 launches), from two rocprofv3 --pmc
 # runs of this script (FETCH_SIZE, WRITE_SIZE), each scaled by the reading of a plain 1 GiB copy:
-# 639 MB read + 123 MB written.  Only measured for the default workload.
-MEASURED_GEMM_TRAFFIC_BYTES = {5: 7.617e8}
+# 668 MB read + 123 MB written.  Only measured for the default workload.
+MEASURED_GEMM_TRAFFIC_BYTES = {5: 7.905e8}
 
 
 def cpu_baseline(cfg):
