@@ -111,9 +111,10 @@ fog_status fog_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t 
 /*
  * Just-in-time scaling in one call (Section 2: abs-max of the tensor being cast, then the cast;
  * Appendix E for the scale): the same results, bit for bit, as fog_amax -> fog_scale -> fog_quantize,
- * in three launches instead of four and without atomics: every workgroup of the abs-max pass leaves
- * its maximum in its own word of the workspace, one small workgroup reduces the words and derives
- * the scale, the cast pass follows on the same stream.
+ * in two launches instead of four and without atomics: every workgroup of the abs-max pass leaves
+ * its maximum in its own word of the workspace; every workgroup of the cast pass, which follows on
+ * the same stream, reduces those words (4 KB at most) and derives the scale itself, and the first
+ * one publishes abs-max, scale and 1/scale.
  *   amax, scale : one float each, overwritten.   scale_inv : one float or NULL.
  *   q, qT, x_bf16, leading dimensions, fmt : as in fog_quantize.   margin : as in fog_scale.
  *   workspace : fog_quantize_jit_workspace() bytes (4 KB), 4-byte aligned, owned by the caller; its

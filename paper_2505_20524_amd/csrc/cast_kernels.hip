@@ -152,6 +152,42 @@ __global__ __launch_bounds__(kThreads) void scale_partials_kernel(const uint32_t
   }
 }
 
+// The same reduction inside a cast kernel: under just-in-time scaling every workgroup of the cast pass
+// derives the scale itself from the per-workgroup maxima of the abs-max pass (at most 4 KB, served from
+// L2), so no launch sits between the two passes; workgroup 0 publishes abs-max, scale and 1/scale.
+struct JitScale {
+  const uint32_t* part;   // NULL: the scale is read from memory instead
+  int n, fmt, margin;
+  float* amax;
+  float* scale;
+  float* scale_inv;
+};
+FOG_DEVICE float scale_from_partials(const JitScale& js) {
+  uint32_t m = 0;
+  for (int i = threadIdx.x; i < js.n; i += kThreads) m = m > js.part[i] ? m : js.part[i];
+  m = wave_max_u32(m);
+  __shared__ uint32_t wmax[kThreads / 64];
+  __shared__ float rho_shared;
+  if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t r = wmax[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) r = r > wmax[w] ? r : wmax[w];
+    const float a = __uint_as_float(r);
+    float sc, si;
+    scale_from_amax(a, js.fmt, js.margin, &sc, &si);
+    rho_shared = sc;
+    if (blockIdx.x == 0) {
+      *js.amax = a;
+      *js.scale = sc;
+      if (js.scale_inv) *js.scale_inv = si;
+    }
+  }
+  __syncthreads();
+  return rho_shared;
+}
+
 // One workgroup: roll the history by one (newest first), then scale from its maximum.
 __global__ __launch_bounds__(kThreads) void scale_delayed_kernel(float* hist, int len, const float* new_amax, int fmt,
                                                                 int margin, float* scale, float* scale_inv) {
@@ -194,8 +230,8 @@ template <int FMT, bool AMAX>
 __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t* __restrict__ x, int64_t rows,
                                                                  int64_t chunks_per_row, int64_t ldx,
                                                                  const float* __restrict__ scale, uint8_t* __restrict__ q,
-                                                                 int64_t ldq, uint32_t* __restrict__ amax_out) {
-  const float rho = *scale;
+                                                                 int64_t ldq, uint32_t* __restrict__ amax_out, JitScale js) {
+  const float rho = js.part ? scale_from_partials(js) : *scale;
   const int64_t total = rows * chunks_per_row;
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   uint32_t m = 0;
@@ -274,9 +310,9 @@ __global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const uint
                                                                       const float* __restrict__ scale,
                                                                       uint8_t* __restrict__ q, int64_t ldq,
                                                                       uint8_t* __restrict__ qT, int64_t ldqT,
-                                                                      uint32_t* __restrict__ amax_out, int tiles_c) {
+                                                                      uint32_t* __restrict__ amax_out, int tiles_c, JitScale js) {
   __shared__ __attribute__((aligned(16))) uint8_t tile[kTile * kTile];  // [col][row], chunk-swizzled
-  const float rho = *scale;
+  const float rho = js.part ? scale_from_partials(js) : *scale;
   const int bid = gridDim.x - 1 - blockIdx.x;   // tiles back to front (see quantize_rows_kernel)
   const int64_t r0 = (int64_t)(bid / tiles_c) * kTile;
   const int64_t c0 = (int64_t)(bid % tiles_c) * kTile;
@@ -344,8 +380,8 @@ __global__ __launch_bounds__(kThreads) void quantize_general_kernel(const uint16
                                                                     int64_t ldx, const float* __restrict__ scale,
                                                                     uint8_t* __restrict__ q, int64_t ldq,
                                                                     uint8_t* __restrict__ qT, int64_t ldqT,
-                                                                    uint32_t* __restrict__ amax_out) {
-  const float rho = *scale;
+                                                                    uint32_t* __restrict__ amax_out, JitScale js) {
+  const float rho = js.part ? scale_from_partials(js) : *scale;
   const int64_t total = rows * cols;
   uint32_t m = 0;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
@@ -407,7 +443,7 @@ extern "C" fog_status fog_scale_delayed(float* history, int len, const float* ne
 
 template <int FMT>
 static void launch_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ldx, const float* scale, uint8_t* q,
-                            int64_t ldq, uint8_t* qT, int64_t ldqT, uint32_t* amax_out, hipStream_t s) {
+                            int64_t ldq, uint8_t* qT, int64_t ldqT, uint32_t* amax_out, hipStream_t s, JitScale js = JitScale{}) {
   const bool base_ok = cols % 16 == 0 && ldx % 16 == 0 && aligned16(x) && (!q || (ldq % 16 == 0 && aligned16(q)));
   if (!qT && base_ok) {
     int64_t r = rows, cpr = cols / 16, lx = ldx, lq = ldq;
@@ -417,16 +453,16 @@ static void launch_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64
     if (blocks > 2048) blocks = 2048;
     if (blocks < 1) blocks = 1;
     if (amax_out)
-      quantize_rows_kernel<FMT, true><<<(int)blocks, kThreads, 0, s>>>(x, r, cpr, lx, scale, q, lq, amax_out);
+      quantize_rows_kernel<FMT, true><<<(int)blocks, kThreads, 0, s>>>(x, r, cpr, lx, scale, q, lq, amax_out, js);
     else
-      quantize_rows_kernel<FMT, false><<<(int)blocks, kThreads, 0, s>>>(x, r, cpr, lx, scale, q, lq, amax_out);
+      quantize_rows_kernel<FMT, false><<<(int)blocks, kThreads, 0, s>>>(x, r, cpr, lx, scale, q, lq, amax_out, js);
     return;
   }
   if (qT && base_ok && rows % 16 == 0 && ldqT % 16 == 0 && aligned16(qT)) {
     const int64_t tr = (rows + kTile - 1) / kTile, tc = (cols + kTile - 1) / kTile;
     if (tr * tc <= 0x7FFFFFFF) {
       const int grid = (int)(tr * tc);
-#define FOG_QT(AM, WQ) quantize_transpose_kernel<FMT, AM, WQ><<<grid, kThreads, 0, s>>>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, amax_out, (int)tc)
+#define FOG_QT(AM, WQ) quantize_transpose_kernel<FMT, AM, WQ><<<grid, kThreads, 0, s>>>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, amax_out, (int)tc, js)
       if (amax_out) { if (q) FOG_QT(true, true); else FOG_QT(true, false); }
       else          { if (q) FOG_QT(false, true); else FOG_QT(false, false); }
 #undef FOG_QT
@@ -436,7 +472,7 @@ static void launch_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64
   int64_t total = rows * cols;
   int64_t blocks = (total + kThreads - 1) / kThreads;
   if (blocks > 8192) blocks = 8192;
-  quantize_general_kernel<FMT><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, amax_out);
+  quantize_general_kernel<FMT><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, amax_out, js);
 }
 
 static fog_status quantize_checks(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, fog_fp8 fmt,
@@ -501,9 +537,12 @@ extern "C" fog_status fog_quantize_jit(const void* x_bf16, int64_t rows, int64_t
       amax_strided_kernel<true><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, ws);
     }
   }
-  scale_partials_kernel<<<1, kThreads, 0, s>>>(ws, (int)blocks, (int)fmt, margin, amax, scale, scale_inv);
-  if (n == 0) return fog_launch_status();
-  if (fmt == FOG_E4M3) launch_quantize<FOG_E4M3>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, nullptr, s);
-  else                 launch_quantize<FOG_E5M2>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, nullptr, s);
+  if (n == 0) {   // nothing to cast: abs-max 0, scale 1
+    scale_partials_kernel<<<1, kThreads, 0, s>>>(ws, 0, (int)fmt, margin, amax, scale, scale_inv);
+    return fog_launch_status();
+  }
+  const JitScale js{ws, (int)blocks, (int)fmt, margin, amax, scale, scale_inv};
+  if (fmt == FOG_E4M3) launch_quantize<FOG_E4M3>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, nullptr, s, js);
+  else                 launch_quantize<FOG_E5M2>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, nullptr, s, js);
   return fog_launch_status();
 }
