@@ -214,8 +214,10 @@ size_t fog_fp8_gemm_workspace(fog_layout layout, int64_t M, int64_t N, int64_t K
  *   Q       : [B, H, S, D] contiguous E4M3 bytes;  D must be 128, S a multiple of 64 (any length
  *             whose head, S * D bytes, stays below 2^31).
  *   K, V    : [B, H_kv, S, D] contiguous E4M3 bytes;  H must be a multiple of H_kv.
- *   sinv_* : reciprocal scales of the casts, one float each.  scale_p: one float (p <= 1, so
- *            the paper's formula gives 448).
+ *   sinv_* : reciprocal scales of the casts, one float each.  scale_p: one float; p <= 1, so the
+ *            paper's formula gives 448, and a larger value is used as 448 (it could only saturate,
+ *            and against the running row reference of an online softmax which entries saturate
+ *            would depend on the order in which key blocks are visited).
  *   O_bf16 : [B, H, S, D] bfloat16;  lse : [B, H, S] floats (log2 domain).
  *   amax_p : NULL or one float receiving max p (for a delayed scale_p).  Overwritten.
  * Errors: NULL, SHAPE (negative sizes, H not a multiple of H_kv), ALIGN (16 bytes), UNSUPPORTED

@@ -99,9 +99,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
     }
   }
 
-  const float rho_p = *a.scale_p;
+  // p <= 1, so 448 is the largest scale that cannot overflow E4M3.  A larger one is used as 448: it could
+  // only saturate, and because p is taken against the RUNNING row reference, which of the entries saturate
+  // would depend on the order in which the key blocks are visited.
+  const float rho_p = fminf(*a.scale_p, 448.0f);
   const float lg_rho_p = __log2f(rho_p);
-  const bool clamp_p = !(rho_p <= 448.0f);   // t <= rho_p (1 + eps): the cast can only overflow for a scale above the format's maximum
   const float c = a.softmax_scale * 1.44269504088896340736f * (*a.sinv_q) * (*a.sinv_k);
 
   // key blocks needed by the workgroup / by this wave
@@ -189,7 +191,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
   if (nkb_wave > 0) scores(0, sc);
 
   // One key block: SC holds this block's scores, SN receives the next block's.
-  auto block = [&](const bool CLAMP_P, int kb, v16f* sc, v16f* sn) __attribute__((always_inline)) {
+  auto block = [&](int kb, v16f* sc, v16f* sn) {
     // block kb + 1 landed (blocks kb + 2 may be in flight: vmcnt = 4), own LDS reads done (lgkmcnt = 0)
     __builtin_amdgcn_s_waitcnt(0x0074);
     __syncthreads();
@@ -225,8 +227,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
           for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
         m_run = m_new;
       }
-      // t = rho_p 2^(x - m) <= rho_p (1 + eps): summed in binary32 and cast to E4M3 (saturating; the
-      // clamp is skipped when rho_p <= 448 makes overflow impossible); 32 codes per lane = one B operand.
+      // t = rho_p 2^(x - m) <= 448 (1 + eps): summed in binary32 and cast to E4M3 (no clamp needed: values
+      // up to 464 round to 448); 32 codes per lane = one B operand.
       const float shift = lg_rho_p - m_run;
       v8i pf;
 #pragma unroll
@@ -238,12 +240,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
           const float e2 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 2], c, shift));
           const float e3 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 3], c, shift));
           l_run += (e0 + e1) + (e2 + e3);
-          if (CLAMP_P) {
-            pf[4 * kt + qd] = (int)cvt4_fp8<FOG_E4M3>(e0, e1, e2, e3);
-          } else {
-            uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(e0, e1, 0u, false);
-            pf[4 * kt + qd] = (int)__builtin_amdgcn_cvt_pk_fp8_f32(e2, e3, pk, true);
-          }
+          uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(e0, e1, 0u, false);
+          pf[4 * kt + qd] = (int)__builtin_amdgcn_cvt_pk_fp8_f32(e2, e3, pk, true);
         }
       }
       // O^T += V^T P^T.  Byte 4 qd' + b of dword (4 kt + qd') of pf is key key0 + 32 kt + 8 qd' + 4 g + b;
@@ -262,18 +260,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
       }
     }
   };
-  // The saturating form of the cast is only needed for a scale above the format's maximum; the choice
-  // is made once, outside the loop, so that the loop body has no branch per group of four scores.
-  if (clamp_p) {
-    for (int kb = 0; kb < nkb; kb += 2) {   // two blocks per trip so that the score registers just swap roles
-      block(true, kb, sc, sn);
-      if (kb + 1 < nkb) block(true, kb + 1, sn, sc);
-    }
-  } else {
-    for (int kb = 0; kb < nkb; kb += 2) {
-      block(false, kb, sc, sn);
-      if (kb + 1 < nkb) block(false, kb + 1, sn, sc);
-    }
+  for (int kb = 0; kb < nkb; kb += 2) {   // two blocks per trip so that the score registers just swap roles
+    block(kb, sc, sn);
+    if (kb + 1 < nkb) block(kb + 1, sn, sc);
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
 

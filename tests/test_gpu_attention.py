@@ -26,35 +26,36 @@ def kv_of(c, h):
     return h // (H // Hkv)
 
 
-def gpu_fwd(c, B, H, S, s, causal, want_amax=True):
+def gpu_fwd(c, B, H, S, s, causal, want_amax=True, rho_p=448.0):
     O = torch.full((B, H, S, 128), 0x7FC0, dtype=torch.int16, device="cuda")
     lse = torch.full((B, H, S), float("nan"), device="cuda")
     am = torch.full((1,), -1.0, device="cuda") if want_amax else None
     fog.fp8_attn_fwd(B, H, S, 128, s, causal, dev(c["q"][0]), dev(c["k"][0]), dev(c["v"][0]),
-                     fscalar(c["q"][1]), fscalar(c["k"][1]), fscalar(c["v"][1]), fscalar(448.0), O, lse, amax_p=am,
+                     fscalar(c["q"][1]), fscalar(c["k"][1]), fscalar(c["v"][1]), fscalar(rho_p), O, lse, amax_p=am,
                      H_kv=c["k"][0].shape[1])
     torch.cuda.synchronize()
     return host_u16(O), lse.cpu().numpy(), (am.item() if want_amax else None)
 
 
-def oracle_fwd_heads(c, heads, s, causal):
+def oracle_fwd_heads(c, heads, s, causal, rho_p=448.0):
     res = {}
     for (b, h) in heads:
         hk = kv_of(c, h)
         res[(b, h)] = attention.attn_fwd_head(c["q"][0][b, h], c["k"][0][b, hk], c["v"][0][b, hk],
-                                              c["q"][1], c["k"][1], c["v"][1], s, 448.0, causal)
+                                              c["q"][1], c["k"][1], c["v"][1], s, rho_p, causal)
     return res
 
 
-def check_fwd(c, B, H, S, s, causal, heads):
-    O, lse, am = gpu_fwd(c, B, H, S, s, causal)
-    ref = oracle_fwd_heads(c, heads, s, causal)
+def check_fwd(c, B, H, S, s, causal, heads, rho_p=448.0):
+    O, lse, am = gpu_fwd(c, B, H, S, s, causal, rho_p=rho_p)
+    rho_p = min(rho_p, 448.0)            # the forward uses a probability scale above the format's maximum as 448
+    ref = oracle_fwd_heads(c, heads, s, causal, rho_p)
     pmax = 0.0
     for (b, h), (Or, lr, ap) in ref.items():
         hk = kv_of(c, h)
         dx = attention.logit_uncertainty(c["q"][0][b, h], c["k"][0][b, hk], c["q"][1], c["k"][1], s, causal)
         slack = attention.fwd_cast_slack(c["q"][0][b, h], c["k"][0][b, hk], c["v"][0][b, hk], c["q"][1], c["k"][1], c["v"][1],
-                                         s, 448.0, causal, dx=dx)
+                                         s, rho_p, causal, dx=dx)
         check_bf16(O[b, h], Or, what="O[%d,%d]" % (b, h), slack=slack, max_flip_frac=1.0)
         lunc = attention.lse_uncertainty(c["q"][0][b, h], c["k"][0][b, hk], c["q"][1], c["k"][1], s, causal, dx=dx)
         assert np.all(np.abs(lse[b, h] - lr) <= 2e-4 + lunc), "lse"
@@ -74,6 +75,19 @@ def test_forward_parity(B, H, S, causal):
     check_fwd(c, B, H, S, 1 / math.sqrt(128), causal, [(b, h) for b in range(B) for h in range(H)])
 
 
+@pytest.mark.parametrize("rho_p", [100.0, 1000.0, 3000.0])
+def test_probability_scale_other_than_the_format_maximum(rho_p):
+    """scale_p below 448 wastes range.  Above 448 the forward uses 448 (p is taken against the running row reference
+    there, so saturation would depend on the visiting order); the backward casts the normalised P, for which
+    saturation is well defined (P > 448 / scale_p maps to 448), and takes its saturating-cast loops."""
+    B, H, S = 1, 2, 256
+    q, k, v, do = synth.small_attention(500 + int(rho_p), B, H, S)
+    c = cast_all(q, k, v, do)
+    heads = [(0, 0), (0, 1)]
+    check_fwd(c, B, H, S, 0.125, True, heads, rho_p=rho_p)
+    run_bwd(c, B, H, S, 0.125, True, heads, do, rho_p=rho_p)
+
+
 def test_forward_fog_softmax_scale_and_q_zero():
     B, H, S = 1, 2, 256
     q, k, v, do = synth.small_attention(77, B, H, S)
@@ -89,7 +103,7 @@ def test_forward_fog_softmax_scale_and_q_zero():
         assert np.abs(lse[0, h] - np.log2(np.arange(1, S + 1))).max() < 1e-5
 
 
-def run_bwd(c, B, H, S, s, causal, heads, do_bits):
+def run_bwd(c, B, H, S, s, causal, heads, do_bits, rho_p=448.0):
     """Feeds the ORACLE's forward results (O rounded to bf16, lse rounded to binary32) to both sides.
     Under grouped-query attention dK and dV of a key/value head are checked when all the query heads of
     its group are in `heads`: the oracle's per-head contributions are summed in float64 (the kernel sums
@@ -104,14 +118,14 @@ def run_bwd(c, B, H, S, s, causal, heads, do_bits):
         return (c["q"][0][b, h], c["k"][0][b, hk], c["v"][0][b, hk], c["q"][1], c["k"][1], c["v"][1])
 
     for (b, h) in heads:
-        Or, lr, _ = attention.attn_fwd_head(*head_args(b, h), s, 448.0, causal)
+        Or, lr, _ = attention.attn_fwd_head(*head_args(b, h), s, rho_p, causal)
         O_bits[b, h] = bf16.f64_to_bits_rne(Or)
         lse[b, h] = lr.astype(np.float32)
     # calibrate rho_dS from one oracle pass without the dS cast (delayed-style scale)
     amax_ds = 0.0
     for (b, h) in heads:
         r = attention.attn_bwd_head(*head_args(b, h), O_bits[b, h], do_bits[b, h], c["do"][0][b, h], c["do"][1], lse[b, h],
-                                    s, 448.0, 1.0, causal, True, False)
+                                    s, rho_p, 1.0, causal, True, False)
         amax_ds = max(amax_ds, float(r[3]))
     rho_ds, _ = scaling.compute_scale(np.float32(amax_ds), fp8.E5M2)
     dQ = torch.full((B, H, S, 128), 0x7FC0, dtype=torch.int16, device="cuda")
@@ -120,13 +134,13 @@ def run_bwd(c, B, H, S, s, causal, heads, do_bits):
     ws = torch.empty(fog.fp8_attn_workspace(B, H, S, 128, True, H_kv=Hkv), dtype=torch.uint8, device="cuda")
     fog.fp8_attn_bwd(B, H, S, 128, s, causal, dev(c["q"][0]), dev(c["k"][0]), dev(c["v"][0]),
                      fscalar(c["q"][1]), fscalar(c["k"][1]), fscalar(c["v"][1]), dev(O_bits), dev(do_bits), dev(c["do"][0]),
-                     fscalar(c["do"][1]), dev(lse), fscalar(448.0), fscalar(rho_ds), dQ, dK, dV, amax_ds=am, workspace=ws,
+                     fscalar(c["do"][1]), dev(lse), fscalar(rho_p), fscalar(rho_ds), dQ, dK, dV, amax_ds=am, workspace=ws,
                      H_kv=Hkv)
     torch.cuda.synchronize()
     dQ, dK, dV = host_u16(dQ), host_u16(dK), host_u16(dV)
     group = {}
     for (b, h) in heads:
-        tail = (O_bits[b, h], do_bits[b, h], c["do"][0][b, h], c["do"][1], lse[b, h], s, 448.0, rho_ds, causal)
+        tail = (O_bits[b, h], do_bits[b, h], c["do"][0][b, h], c["do"][1], lse[b, h], s, rho_p, rho_ds, causal)
         r = attention.attn_bwd_head(*head_args(b, h), *tail)
         sl = attention.bwd_cast_slack(*head_args(b, h), *tail)
         check_bf16(dQ[b, h], r[0], what="dQ[%d,%d]" % (b, h), max_flip_frac=1.0, slack=sl[0])
