@@ -277,6 +277,29 @@ def test_config3_full_size_sampled_heads():
     run_bwd(c, a.B, a.H, a.S, s, True, heads, t["dO"])
 
 
+def test_optional_abs_max_outputs_may_be_null():
+    """amax_p and amax_ds are optional: without them the kernels take the instantiations that skip the
+    running maxima, and the results are bit-identical to the calls that report them."""
+    B, H, S = 1, 2, 192
+    q, k, v, do = synth.small_attention(909, B, H, S)
+    c = cast_all(q, k, v, do)
+    s = 0.125
+    O1, lse1, _ = gpu_fwd(c, B, H, S, s, True, want_amax=True)
+    O2, lse2, _ = gpu_fwd(c, B, H, S, s, True, want_amax=False)
+    assert np.array_equal(O1, O2) and np.array_equal(lse1, lse2)
+    res = []
+    for with_amax in (True, False):
+        dQ, dK, dV = (torch.full((B, H, S, 128), 0x7FC0, dtype=torch.int16, device="cuda") for _ in range(3))
+        am = torch.zeros(1, device="cuda") if with_amax else None
+        ws = torch.empty(fog.fp8_attn_workspace(B, H, S, 128, True), dtype=torch.uint8, device="cuda")
+        fog.fp8_attn_bwd(B, H, S, 128, s, True, dev(c["q"][0]), dev(c["k"][0]), dev(c["v"][0]), fscalar(c["q"][1]), fscalar(c["k"][1]),
+                         fscalar(c["v"][1]), dev(O1), dev(do), dev(c["do"][0]), fscalar(c["do"][1]), dev(lse1), fscalar(448.0),
+                         fscalar(2.0 ** 20), dQ, dK, dV, amax_ds=am, workspace=ws)
+        torch.cuda.synchronize()
+        res.append([host_u16(x) for x in (dQ, dK, dV)])
+    assert all(np.array_equal(a, b) for a, b in zip(*res))
+
+
 def test_attention_argument_errors():
     lib = fog.load()
     st = torch.cuda.current_stream().cuda_stream

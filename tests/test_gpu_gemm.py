@@ -47,6 +47,26 @@ def test_gemm_parity(layout, M, N, K):
     assert stats["max_steps"] <= 1
 
 
+@pytest.mark.parametrize("layout", [gemm.NT, gemm.NN, gemm.TN])
+def test_gemm_padded_leading_dimensions(layout):
+    """Operands and result as views of wider buffers (lda, ldb, ldc larger than the rows): nothing outside the
+    views is read into the result or written."""
+    M, N, K = 304, 528, 400
+    A8, sa, B8, sb = quantized_layer(77, M, N, K)
+    a, b = lay(layout, A8, B8)
+    ref = gemm.fp8_gemm(layout, a, fp8.E4M3, sa, b, fp8.E4M3, sb)
+    pa, pb, pc = 16, 48, 8
+    abuf = torch.full((a.shape[0], a.shape[1] + pa), 0x7E, dtype=torch.uint8, device="cuda")     # padding = largest code: a leak would show
+    bbuf = torch.full((b.shape[0], b.shape[1] + pb), 0x7E, dtype=torch.uint8, device="cuda")
+    abuf[:, :a.shape[1]] = dev(a)
+    bbuf[:, :b.shape[1]] = dev(b)
+    cbuf = torch.full((M, N + pc), 0x7FC0, dtype=torch.int16, device="cuda")
+    fog.fp8_gemm(layout, M, N, K, abuf[:, :a.shape[1]], fp8.E4M3, fscalar(sa), bbuf[:, :b.shape[1]], fp8.E4M3, fscalar(sb), cbuf[:, :N])
+    torch.cuda.synchronize()
+    assert (cbuf[:, N:] == 0x7FC0).all()
+    check_bf16(host_u16(cbuf[:, :N].contiguous()), ref, what="padded ld, layout %d" % layout)
+
+
 def test_gemm_ragged_rows_nt():
     """NT takes any M and N (rows of the operands); K only has to be a multiple of 16."""
     for (M, N, K) in [(1, 1, 16), (257, 259, 160), (300, 37, 128), (5, 700, 400)]:
