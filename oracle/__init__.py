@@ -10,4 +10,4 @@ Every function cites the passage of the paper (section / equation / appendix)
 that defines what it computes.  Pins for each function live in the CPU test
 suite; none is "parity unpinned".
 """
-from . import bf16, fp8, scaling, gemm, attention, kurtosis, qknorm, xielu  # noqa: F401
+from . import bf16, fp8, scaling, gemm, attention, kurtosis, qknorm, xielu, gelu, postnorm  # noqa: F401
