@@ -169,6 +169,59 @@ fog_status fog_xielu_quantize(const void* x_bf16, int64_t rows, int64_t cols, in
                               fog_fp8 fmt, const float* scale, uint8_t* q, int64_t ldq, float* amax_out, void* stream);
 
 /*
+ * GeLU fused with the FP8 cast (Section 3, architecture table: the activation of two of the FOG
+ * variants, between the two GEMMs of the feed-forward block).  The paper names GeLU without a
+ * formula; it is taken as the exact form
+ *     y = x Phi(x) = 0.5 x erfc(-x / sqrt 2)        (binary32)
+ *     q = sat_rne_fmt( fl32( y * scale ) ),         amax_out = max |y| over the matrix.
+ * Arguments, fast path and errors as for fog_xielu_quantize (no activation parameters).  Codes agree
+ * with a float64 evaluation except where scale * y lies within about 2^-19 + x^2 2^-23 (relative,
+ * the second term for x < 0 only) of a rounding boundary.
+ */
+fog_status fog_gelu_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, fog_fp8 fmt, const float* scale,
+                             uint8_t* q, int64_t ldq, float* amax_out, void* stream);
+
+/*
+ * tanh_alpha fused with the FP8 cast (Section 3: tanh(alpha x) applied element-wise to queries and
+ * keys, the entropy regulariser of the FOG-flash variant, in place of the QK RMSNorm):
+ *     y = tanh(alpha * x)                           (binary32)
+ *     q = sat_rne_fmt( fl32( y * scale ) ),         amax_out = max |y| over the matrix.
+ * |y| <= 1, so a caller may use the constant scale FP8MAX and skip the abs-max altogether.
+ *   alpha : finite (the layer's trainable scalar as a plain number).
+ * Other arguments, fast path and errors as for fog_xielu_quantize; codes agree with a float64
+ * evaluation except where scale * y lies within about 2^-19 (relative) of a rounding boundary.
+ */
+fog_status fog_tanh_quantize(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, float alpha, fog_fp8 fmt,
+                             const float* scale, uint8_t* q, int64_t ldq, float* amax_out, void* stream);
+
+/*
+ * Post-RMSNorm with its residual connection, fused with the FP8 cast of the result (Section 3: every
+ * sub-layer output y passes N_gamma(y) = gamma (.) y / rms(y), rms(y) = ||y||_2 / sqrt(cols), with a
+ * trainable gains vector, before it is added to the residual stream x; the block has no
+ * pre-normalisation, so the sum is the next GEMM's input and is cast as in Appendix E):
+ *     xnew = bf16( x + gamma (.) y / rms(y) )       (binary32 evaluation, one rounding to bfloat16;
+ *                                                    a zero vector y adds nothing: no epsilon)
+ *     q    = sat_rne_fmt( fl32( xnew * scale ) )    (the cast of the STORED bfloat16 value: bit-exact
+ *                                                    given xnew)
+ *     amax_out = max |xnew| over the matrix         (bit-exact given xnew)
+ *   x_bf16, y_bf16 : [rows, cols] bfloat16, leading dimensions ldx, ldy.
+ *   gamma  : [cols] floats.        scale : one float (delayed scaling, fed by amax_out).
+ *   xnew_bf16 : [rows, cols] bfloat16, leading dimension ldo; may be the same buffer as x_bf16 with the
+ *            same leading dimension (residual stream updated in place), must not overlap anything else.
+ *   q      : NULL (only the residual update and the abs-max) or [rows, cols] bytes, leading dimension ldq.
+ *   amax_out : NULL or one float, overwritten.
+ * xnew agrees with a float64 evaluation except where the exact sum lies within about
+ * 2^-20 |N(y)| + 2^-23 |xnew| of a bfloat16 rounding boundary.
+ * Fast path (one wave per row, every element read once): cols a multiple of 512 up to 8192, x, y, xnew
+ * and gamma 16-byte aligned, q 8-byte aligned, leading dimensions multiples of 8; other shapes take a
+ * one-wave-per-row kernel that reads y twice.
+ * Errors: NULL, SHAPE, ALIGN (odd bf16 addresses, gamma not 4-byte aligned), UNSUPPORTED (format).
+ */
+fog_status fog_postnorm_residual_quantize(const void* x_bf16, int64_t ldx, const void* y_bf16, int64_t ldy, int64_t rows,
+                                          int64_t cols, const float* gamma, fog_fp8 fmt, const float* scale, void* xnew_bf16,
+                                          int64_t ldo, uint8_t* q, int64_t ldq, float* amax_out, void* stream);
+
+/*
  * Activation kurtosis, the paper's outlier diagnostic (Section 4): for each token vector x (a row),
  * kurt(x) = mu[x^4] / (mu[x^2])^2 (element-wise powers, x not centred); the result is the mean over
  * the rows.  The denominator is read as the squared un-centred second moment (1 for a constant
@@ -176,10 +229,13 @@ fog_status fog_xielu_quantize(const void* x_bf16, int64_t rows, int64_t cols, in
  *   x_bf16 : [rows, cols] bfloat16, leading dimension ldx; one pass, binary32 sums.
  *   kurt   : one float, overwritten.  Rows are summed with float atomics: the last bits may vary
  *            from run to run.
+ *   amax_out : NULL or one float, overwritten with max |x| over the matrix, bit-exact (Appendix E:
+ *            the entry this tensor adds to the scaling history), so that the monitor and the
+ *            delayed-scaling abs-max share one read of the activations.
  * The fast path needs a 16-byte aligned x and cols, ldx multiples of 8; other shapes take a scalar path.
  * Errors: NULL, negative sizes or ldx < cols (SHAPE), odd address (ALIGN).
  */
-fog_status fog_kurtosis(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, float* kurt, void* stream);
+fog_status fog_kurtosis(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, float* kurt, float* amax_out, void* stream);
 
 /*
  * Scaled FP8 product (Appendix E): C = scale_inv_A * scale_inv_B * (decode(A) x decode(B)) in

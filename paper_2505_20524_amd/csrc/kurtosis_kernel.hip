@@ -2,7 +2,9 @@
 // averaged over the token vectors of a tensor.  The denominator is read as the squared un-centred
 // second moment (the printed sigma^2[x^2] cannot be the variance of x^2: that would fall as an
 // outlier grows).  HBM-bound: every element is read once with 16-byte loads (eight in flight); one wave per row,
-// binary32 sums of x^2 and x^4, one float atomic per workgroup.
+// binary32 sums of x^2 and x^4, one float atomic per workgroup.  The same read can also deliver the
+// tensor's abs-max (Appendix E: what the scaling history of the next cast needs), so that monitoring
+// and delayed scaling share one pass over the activations.
 #include "common.h"
 #include "launch.h"
 
@@ -10,9 +12,14 @@ namespace {
 
 constexpr int kThreads = 256;
 
-__global__ void zero_f32_kernel(float* p) { *p = 0.0f; }
+__global__ void zero_f32_kernel(float* p, uint32_t* amax) {
+  *p = 0.0f;
+  if (amax) *amax = 0u;
+}
 
-FOG_DEVICE void acc_pair(uint32_t w, float& s2, float& s4) {
+template <bool AMAX>
+FOG_DEVICE void acc_pair(uint32_t w, float& s2, float& s4, uint32_t& mx) {
+  if (AMAX) mx = pkmax_abs_bf16(mx, w);
   const float a = bf16lo(w), b = bf16hi(w);
   const float a2 = a * a, b2 = b * b;
   s2 += a2 + b2;
@@ -20,11 +27,12 @@ FOG_DEVICE void acc_pair(uint32_t w, float& s2, float& s4) {
 }
 
 // VEC: rows are 16-byte aligned and cols % 8 == 0.
-template <bool VEC>
+template <bool VEC, bool AMAX>
 __global__ __launch_bounds__(kThreads) void kurtosis_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx,
-                                                            float inv_rows, float* __restrict__ out) {
+                                                            float inv_rows, float* __restrict__ out, uint32_t* __restrict__ amax_out) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   float local = 0.0f;   // sum of this wave's row kurtoses
+  uint32_t mx = 0u;     // running max of |x| as two packed 15-bit bf16 magnitudes
   for (int64_t r = (int64_t)blockIdx.x * 4 + w; r < rows; r += (int64_t)gridDim.x * 4) {
     const uint16_t* row = x + r * ldx;
     float s2 = 0.0f, s4 = 0.0f;
@@ -37,7 +45,7 @@ __global__ __launch_bounds__(kThreads) void kurtosis_kernel(const uint16_t* __re
         for (int k = 0; k < 8; ++k) v[k] = ld_nt16(row + 8 * (i + 64 * k));
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-          acc_pair(v[k].x, s2, s4); acc_pair(v[k].y, s2, s4); acc_pair(v[k].z, s2, s4); acc_pair(v[k].w, s2, s4);
+          acc_pair<AMAX>(v[k].x, s2, s4, mx); acc_pair<AMAX>(v[k].y, s2, s4, mx); acc_pair<AMAX>(v[k].z, s2, s4, mx); acc_pair<AMAX>(v[k].w, s2, s4, mx);
         }
       }
       for (; i + 192 < nvec; i += 256) {   // four
@@ -46,16 +54,17 @@ __global__ __launch_bounds__(kThreads) void kurtosis_kernel(const uint16_t* __re
         for (int k = 0; k < 4; ++k) v[k] = ld_nt16(row + 8 * (i + 64 * k));
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-          acc_pair(v[k].x, s2, s4); acc_pair(v[k].y, s2, s4); acc_pair(v[k].z, s2, s4); acc_pair(v[k].w, s2, s4);
+          acc_pair<AMAX>(v[k].x, s2, s4, mx); acc_pair<AMAX>(v[k].y, s2, s4, mx); acc_pair<AMAX>(v[k].z, s2, s4, mx); acc_pair<AMAX>(v[k].w, s2, s4, mx);
         }
       }
       for (; i < nvec; i += 64) {
         uint4 a = ld_nt16(row + 8 * i);
-        acc_pair(a.x, s2, s4); acc_pair(a.y, s2, s4); acc_pair(a.z, s2, s4); acc_pair(a.w, s2, s4);
+        acc_pair<AMAX>(a.x, s2, s4, mx); acc_pair<AMAX>(a.y, s2, s4, mx); acc_pair<AMAX>(a.z, s2, s4, mx); acc_pair<AMAX>(a.w, s2, s4, mx);
       }
     } else {
       for (int64_t i = lane; i < cols; i += 64) {
         const float a = bf16lo(row[i]), a2 = a * a;
+        if (AMAX) mx = pkmax_abs_bf16(mx, row[i]);
         s2 += a2;
         s4 = __builtin_fmaf(a2, a2, s4);
       }
@@ -66,21 +75,35 @@ __global__ __launch_bounds__(kThreads) void kurtosis_kernel(const uint16_t* __re
     if (s2 > 0.0f) local += (float)cols * (s4 / (s2 * s2));
   }
   __shared__ float part[4];
-  if (lane == 0) part[w] = local;
+  __shared__ uint32_t pmax[4];
+  if (AMAX) mx = wave_max_u32((mx & 0xFFFFu) > (mx >> 16) ? (mx & 0xFFFFu) : (mx >> 16));
+  if (lane == 0) {
+    part[w] = local;
+    if (AMAX) pmax[w] = mx;
+  }
   __syncthreads();
   if (threadIdx.x == 0) {
     const float t = (part[0] + part[1]) + (part[2] + part[3]);
     if (t != 0.0f) atomicAdd(out, t * inv_rows);
+    if (AMAX) {
+      uint32_t r = pmax[0];
+#pragma unroll
+      for (int k = 1; k < 4; ++k) r = r > pmax[k] ? r : pmax[k];
+      r <<= 16;   // the float with that bf16 pattern; non-negative floats order like their bits
+      if (r > __hip_atomic_load(amax_out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(amax_out, r);
+    }
   }
 }
 
 }  // namespace
 
-extern "C" fog_status fog_kurtosis(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, float* kurt, void* stream) {
+extern "C" fog_status fog_kurtosis(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, float* kurt, float* amax_out,
+                                   void* stream) {
   if (!kurt) return FOG_ERR_NULL;
   if (rows < 0 || cols < 0) return FOG_ERR_SHAPE;
   hipStream_t s = (hipStream_t)stream;
-  zero_f32_kernel<<<1, 1, 0, s>>>(kurt);
+  uint32_t* am = reinterpret_cast<uint32_t*>(amax_out);
+  zero_f32_kernel<<<1, 1, 0, s>>>(kurt, am);
   if (rows == 0 || cols == 0) return fog_launch_status();
   if (!x_bf16) return FOG_ERR_NULL;
   if (ldx < cols) return FOG_ERR_SHAPE;
@@ -90,7 +113,9 @@ extern "C" fog_status fog_kurtosis(const void* x_bf16, int64_t rows, int64_t col
   if (blocks > 2048) blocks = 2048;
   const uint16_t* x = reinterpret_cast<const uint16_t*>(x_bf16);
   const float inv = 1.0f / (float)rows;
-  if (vec) kurtosis_kernel<true><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, inv, kurt);
-  else     kurtosis_kernel<false><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, inv, kurt);
+#define FOG_KURT(V, A) kurtosis_kernel<V, A><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, inv, kurt, am)
+  if (vec) { if (am) FOG_KURT(true, true); else FOG_KURT(true, false); }
+  else     { if (am) FOG_KURT(false, true); else FOG_KURT(false, false); }
+#undef FOG_KURT
   return fog_launch_status();
 }

@@ -30,7 +30,10 @@ SIGNATURES = {
     "fog_quantize_jit_workspace": (_SZ, []),
     "fog_rmsnorm_quantize": (_I, [_P, _I64, _I64, _I64, _F, _I, _P, _P, _I64, _P, _P]),
     "fog_xielu_quantize": (_I, [_P, _I64, _I64, _I64, _F, _F, _I, _P, _P, _I64, _P, _P]),
-    "fog_kurtosis": (_I, [_P, _I64, _I64, _I64, _P, _P]),
+    "fog_gelu_quantize": (_I, [_P, _I64, _I64, _I64, _I, _P, _P, _I64, _P, _P]),
+    "fog_tanh_quantize": (_I, [_P, _I64, _I64, _I64, _F, _I, _P, _P, _I64, _P, _P]),
+    "fog_postnorm_residual_quantize": (_I, [_P, _I64, _P, _I64, _I64, _I64, _P, _I, _P, _P, _I64, _P, _I64, _P, _P]),
+    "fog_kurtosis": (_I, [_P, _I64, _I64, _I64, _P, _P, _P]),
     "fog_fp8_gemm": (_I, [_I, _I64, _I64, _I64, _P, _I, _I64, _P, _P, _I, _I64, _P, _P, _I64, _P, _SZ, _P]),
     "fog_fp8_gemm_workspace": (_SZ, [_I, _I64, _I64, _I64]),
     "fog_fp8_attn_fwd": (_I, [_I, _I, _I, _I, _I, _F, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
@@ -126,9 +129,29 @@ def xielu_quantize(x, alpha_p, alpha_n, fmt, scale_t, q, amax_out=None, stream=N
            "fog_xielu_quantize")
 
 
-def kurtosis(x, out, stream=None):
+def gelu_quantize(x, fmt, scale_t, q, amax_out=None, stream=None):
     rows, cols = x.shape
-    _check(load().fog_kurtosis(_ptr(x), rows, cols, x.stride(0), _ptr(out), _stream(stream)), "fog_kurtosis")
+    _check(load().fog_gelu_quantize(_ptr(x), rows, cols, x.stride(0), fmt, _ptr(scale_t), _ptr(q),
+                                    q.stride(0) if q is not None else 0, _ptr(amax_out), _stream(stream)), "fog_gelu_quantize")
+
+
+def tanh_quantize(x, alpha, fmt, scale_t, q, amax_out=None, stream=None):
+    rows, cols = x.shape
+    _check(load().fog_tanh_quantize(_ptr(x), rows, cols, x.stride(0), alpha, fmt, _ptr(scale_t), _ptr(q),
+                                    q.stride(0) if q is not None else 0, _ptr(amax_out), _stream(stream)), "fog_tanh_quantize")
+
+
+def postnorm_residual_quantize(x, y, gamma, fmt, scale_t, xnew, q=None, amax_out=None, stream=None):
+    rows, cols = y.shape
+    _check(load().fog_postnorm_residual_quantize(_ptr(x), x.stride(0), _ptr(y), y.stride(0), rows, cols, _ptr(gamma), fmt,
+                                                 _ptr(scale_t), _ptr(xnew), xnew.stride(0), _ptr(q),
+                                                 q.stride(0) if q is not None else 0, _ptr(amax_out), _stream(stream)),
+           "fog_postnorm_residual_quantize")
+
+
+def kurtosis(x, out, amax_out=None, stream=None):
+    rows, cols = x.shape
+    _check(load().fog_kurtosis(_ptr(x), rows, cols, x.stride(0), _ptr(out), _ptr(amax_out), _stream(stream)), "fog_kurtosis")
 
 
 def fp8_gemm(layout, M, N, K, A, fmt_a, sinv_a, B, fmt_b, sinv_b, C, workspace=None, stream=None):

@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import kurtosis
+from oracle import kurtosis, scaling
 from paper_2505_20524_amd import fog, synth
 from parity import dev
 
@@ -14,11 +14,18 @@ RTOL = 2e-5
 
 
 def gpu_kurt(xb, view_cols=None):
+    """Runs the call twice, without and with the abs-max output; the abs-max must be bit-exact (Appendix E)."""
     x = dev(xb)
     if view_cols is not None:
         x = x[:, :view_cols]
     out = torch.full((1,), -1.0, device="cuda")
     fog.kurtosis(x, out)
+    out2 = torch.full((1,), -1.0, device="cuda")
+    am = torch.full((1,), -1.0, device="cuda")
+    fog.kurtosis(x, out2, amax_out=am)
+    view = xb if view_cols is None else xb[:, :view_cols]
+    assert am.item() == scaling.amax(view)
+    assert abs(out2.item() - out.item()) <= 1e-5 * abs(out.item())      # float atomics: order may differ between runs
     return out.item()
 
 
@@ -41,7 +48,7 @@ def test_kurtosis_closed_forms_and_config_tensors():
     z = np.zeros((4, D), np.float32); z[0, :] = 1.0
     assert gpu_kurt(synth.f32_to_bf16_bits(z)) == pytest.approx(0.25, rel=1e-6)     # zero rows contribute 0
     out = torch.full((1,), -1.0, device="cuda")
-    assert fog.load().fog_kurtosis(None, 0, 64, 64, out.data_ptr(), torch.cuda.current_stream().cuda_stream) == 0
+    assert fog.load().fog_kurtosis(None, 0, 64, 64, out.data_ptr(), None, torch.cuda.current_stream().cuda_stream) == 0
     torch.cuda.synchronize()
     assert out.item() == 0.0
     # the activations of config 1 (4 outlier channels x50) and config 5 (2 channels x1000, "massive activations")
@@ -57,8 +64,8 @@ def test_kurtosis_argument_errors():
     st = torch.cuda.current_stream().cuda_stream
     x = torch.zeros(64, dtype=torch.int16, device="cuda")
     out = torch.zeros(1, device="cuda")
-    assert lib.fog_kurtosis(x.data_ptr(), 4, 16, 16, None, st) == 1
-    assert lib.fog_kurtosis(x.data_ptr(), -1, 16, 16, out.data_ptr(), st) == 2
-    assert lib.fog_kurtosis(x.data_ptr(), 4, 16, 8, out.data_ptr(), st) == 2
-    assert lib.fog_kurtosis(x.data_ptr() + 1, 4, 8, 8, out.data_ptr(), st) == 3
-    assert lib.fog_kurtosis(None, 4, 16, 16, out.data_ptr(), st) == 1
+    assert lib.fog_kurtosis(x.data_ptr(), 4, 16, 16, None, None, st) == 1
+    assert lib.fog_kurtosis(x.data_ptr(), -1, 16, 16, out.data_ptr(), None, st) == 2
+    assert lib.fog_kurtosis(x.data_ptr(), 4, 16, 8, out.data_ptr(), None, st) == 2
+    assert lib.fog_kurtosis(x.data_ptr() + 1, 4, 8, 8, out.data_ptr(), None, st) == 3
+    assert lib.fog_kurtosis(None, 4, 16, 16, out.data_ptr(), None, st) == 1

@@ -1,0 +1,101 @@
+"""GPU parity: post-RMSNorm + residual connection fused with the FP8 cast, against the float64 oracle.
+
+The new residual stream is evaluated in binary32 and rounded once to bf16: each stored element must lie
+between the bf16 roundings of the oracle's window ends (they coincide for all but a few elements in 10^3).
+The FP8 codes and the abs-max are exact functions of the bf16 tensor that was stored, so they are checked
+bit for bit with the per-tensor cast oracle applied to the GPU's own bf16 output.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import bf16, fp8, postnorm, scaling
+from paper_2505_20524_amd import fog, synth
+from parity import dev, fscalar
+
+pytestmark = pytest.mark.gpu
+
+
+def check(xb, yb, gamma, cols, fmt, rho, pad=0, in_place=False, with_q=True):
+    rows = xb.shape[0]
+    x, y = dev(xb), dev(yb)
+    if pad:
+        x, y = x[:, :cols], y[:, :cols]
+    g = torch.from_numpy(gamma).cuda()
+    ofull = torch.full((rows, cols + pad), 0x5555, dtype=torch.int16, device="cuda")
+    out = x if in_place else (ofull[:, :cols] if pad else ofull)
+    qfull = torch.full((rows, cols + pad), 0xAA, dtype=torch.uint8, device="cuda")
+    q = (qfull[:, :cols] if pad else qfull) if with_q else None
+    am = torch.full((1,), -1.0, device="cuda")
+    fog.postnorm_residual_quantize(x, y, g, fmt, fscalar(rho), out, q=q, amax_out=am)
+    torch.cuda.synchronize()
+    if pad and not in_place:
+        assert (ofull[:, cols:] == 0x5555).all()
+    if pad and with_q:
+        assert (qfull[:, cols:] == 0xAA).all()
+    got = out.contiguous().cpu().numpy().view(np.uint16)
+    lo, hi = postnorm.residual_window(xb[:, :cols], yb[:, :cols], gamma)
+    v, vl, vh = (bf16.bits_to_f64(b) for b in (got, lo, hi))
+    assert np.all(vl <= v) and np.all(v <= vh)
+    assert np.array_equal(got[lo == hi], lo[lo == hi])
+    assert (lo != hi).mean() <= 5e-3
+    assert am.item() == scaling.amax(got)
+    if with_q:
+        assert np.array_equal(q.contiguous().cpu().numpy(), scaling.quantize(got, rho, fmt))
+    return got
+
+
+def make(rows, cols, pad, seed):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((rows, cols + pad)).astype(np.float32)
+    y = (rng.standard_normal((rows, cols + pad)) * 3.0).astype(np.float32)
+    y[:, 1 % cols] *= 20.0                                   # an outlier channel in the sub-layer output
+    if rows > 2:
+        y[2, :] = 0.0                                        # a zero vector adds nothing
+    gamma = ((rng.random(cols) + 0.5) / np.sqrt(32.0)).astype(np.float32)      # around 1 / sqrt(num_layers)
+    return synth.f32_to_bf16_bits(x), synth.f32_to_bf16_bits(y), gamma
+
+
+@pytest.mark.parametrize("fmt", [fp8.E4M3, fp8.E5M2])
+@pytest.mark.parametrize("rows,cols,pad", [(1, 512, 0), (37, 1024, 0), (16, 1536, 8), (130, 4096, 0), (9, 5120, 0), (6, 8192, 0),
+                                           (5, 17, 3), (33, 100, 0), (3, 8704, 0), (12, 520, 0), (1024, 4096, 0)])
+def test_postnorm_parity(rows, cols, pad, fmt):
+    xb, yb, gamma = make(rows, cols, pad, rows + cols + fmt)
+    ref = postnorm.residual_bf16(xb[:, :cols], yb[:, :cols], gamma)
+    rho = scaling.compute_scale(scaling.amax(ref), fmt)[0]
+    got = check(xb, yb, gamma, cols, fmt, rho, pad=pad)
+    if rows > 2:
+        assert np.array_equal(got[2], xb[2, :cols])
+
+
+def test_in_place_without_codes_and_errors():
+    xb, yb, gamma = make(64, 2048, 0, 7)
+    check(xb, yb, gamma, 2048, fp8.E4M3, np.float32(16.0), in_place=True)
+    check(xb, yb, gamma, 2048, fp8.E4M3, np.float32(16.0), with_q=False)
+    xb, yb, gamma = make(20, 72, 0, 8)
+    check(xb, yb, gamma, 72, fp8.E5M2, np.float32(1000.0), in_place=True)        # general path in place; saturating scale
+    lib = fog.load()
+    st = torch.cuda.current_stream().cuda_stream
+    a = torch.zeros((4, 512), dtype=torch.int16, device="cuda")
+    o = torch.zeros((4, 512), dtype=torch.int16, device="cuda")
+    g = torch.ones(512, device="cuda")
+    q = torch.zeros((4, 512), dtype=torch.uint8, device="cuda")
+    f = fscalar(1.0)
+    call = lib.fog_postnorm_residual_quantize
+    ok = (a.data_ptr(), 512, a.data_ptr(), 512, 4, 512, g.data_ptr(), 0, f.data_ptr(), o.data_ptr(), 512, q.data_ptr(), 512, None, st)
+
+    def with_(i, v):
+        t = list(ok)
+        t[i] = v
+        return call(*t)
+    assert call(*ok) == 0
+    assert with_(0, None) == 1 and with_(2, None) == 1 and with_(6, None) == 1 and with_(8, None) == 1 and with_(9, None) == 1
+    assert with_(4, -1) == 2 and with_(1, 256) == 2 and with_(3, 256) == 2 and with_(10, 256) == 2 and with_(12, 256) == 2
+    assert with_(0, a.data_ptr() + 1) == 3 and with_(6, g.data_ptr() + 2) == 3
+    assert with_(7, 2) == 4
+    am = fscalar(5.0)
+    t = list(ok)
+    t[4], t[13] = 0, am.data_ptr()
+    assert call(*t) == 0
+    torch.cuda.synchronize()
+    assert am.item() == 0.0
