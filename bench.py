@@ -17,6 +17,7 @@ step's wall time, casts included in the time), plus
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -132,77 +133,70 @@ def main():
             ach = work / (ms * 1e-3) / 1e9
             kernels[kind] = {"launches_per_step": n // args.steps, "avg_launch_ms": ms / n, "achieved": ach,
                              "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "in_timed_region": False}
-    # The kurtosis monitor (a diagnostic, not a step of the training path): timed on its own, after the
-    # timed region, over the activation inputs of every linear layer.
-    if blk.linears:
-        kout = torch.zeros(1, device="cuda")
-        kt = block.EventTimer()
-        for rep in range(4):
-            for l in blk.linears:
+    # Figures of kernels that are not steps of the timed path, each timed on its own after the timed region
+    # (first repetition untimed): jobs = [(algorithmic bytes, call), ...].
+    def side_figure(key, jobs, reps=4):
+        t = block.EventTimer()
+        for rep in range(reps):
+            for work, fn in jobs:
                 if rep:
-                    kt.begin("kurtosis", l.X.x.numel() * 2)
-                fog.kurtosis(l.X.x, kout)
+                    t.begin(key, work)
+                fn()
                 if rep:
-                    kt.end()
+                    t.end()
         torch.cuda.synchronize()
-        n, work, ms = kt.summary()["kurtosis"]
-        kernels["kurtosis_monitor"] = {"launches": n, "avg_launch_ms": ms / n, "achieved": work / (ms * 1e-3) / 1e9,
-                                       "unit": "GB/s", "frac": work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "in_timed_step": False}
+        n, work, ms = t.summary()[key]
+        kernels[key] = {"launches": n, "avg_launch_ms": ms / n, "achieved": work / (ms * 1e-3) / 1e9,
+                        "unit": "GB/s", "frac": work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "in_timed_step": False}
+
+    am = torch.zeros(1, device="cuda")
+    if blk.linears:
+        # The kurtosis monitor (a diagnostic) over the activation inputs of every linear layer, alone and with
+        # the abs-max of delayed scaling taken from the same read (2 B per element either way).
+        kout = torch.zeros(1, device="cuda")
+        side_figure("kurtosis_monitor", [(l.X.x.numel() * 2, lambda l=l: fog.kurtosis(l.X.x, kout)) for l in blk.linears])
+        side_figure("kurtosis_with_amax", [(l.X.x.numel() * 2, lambda l=l: fog.kurtosis(l.X.x, kout, amax_out=am)) for l in blk.linears])
     # The cast fused with the transpose (the arrangement for a weight gradient computed as NT on transposed
     # copies).  The timed step does not need it: its weight gradients are TN products on the row-major casts,
-    # the kernel gathering the contraction index with the transposing LDS read.  Timed on its own over the
-    # activations and output gradients of every linear layer (2 B read + 2 B written per element).
+    # the kernel gathering the contraction index with the transposing LDS read.  Over the activations and
+    # output gradients of every linear layer (2 B read + 2 B written per element).
     if blk.linears and not blk.linears[0].transposed_wgrad:
-        tt = block.EventTimer()
+        big = max(l.X.x.numel() for l in blk.linears)
+        big = max(big, max(l.dY.x.numel() for l in blk.linears))
+        qT_store = torch.empty(big, dtype=torch.uint8, device="cuda")
+        jobs = []
         for l in blk.linears:
             for c in (l.X, l.dY):
                 rows, cols = c.x.shape
-                qT = torch.empty((cols, rows), dtype=torch.uint8, device="cuda")
-                for rep in range(3):
-                    if rep:
-                        tt.begin("cast_transpose", 4 * rows * cols)
-                    fog.quantize(c.x, c.fmt, c.scale, q=c.q, qT=qT)
-                    if rep:
-                        tt.end()
-                del qT
-        torch.cuda.synchronize()
-        n, work, ms = tt.summary()["cast_transpose"]
-        kernels["cast_transpose"] = {"launches": n, "avg_launch_ms": ms / n, "achieved": work / (ms * 1e-3) / 1e9,
-                                     "unit": "GB/s", "frac": work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "in_timed_step": False}
-    # The fused QK-RMSNorm + cast producer (an alternative source of the Q / K bytes, not part of the timed
-    # step, whose casts are the plain per-tensor ones): timed on its own over the step's Q and K tensors.
+                qT = qT_store[: rows * cols].view(cols, rows)
+                jobs.append((4 * rows * cols, lambda c=c, qT=qT: fog.quantize(c.x, c.fmt, c.scale, q=c.q, qT=qT)))
+        side_figure("cast_transpose", jobs, reps=3)
+        del qT_store, jobs
+    # Fused producers of the casts (alternative sources of the FP8 bytes, not part of the timed step, whose casts
+    # are the plain per-tensor ones).  QK-RMSNorm and tanh_alpha over the step's Q and K tensors; xIELU and GeLU
+    # over the activation input of the last linear layer (the down projection); 2 B read + 1 B written per element.
     if blk.attn is not None:
-        nt = block.EventTimer()
-        one = torch.full((1,), 39.0, device="cuda")
-        am = torch.zeros(1, device="cuda")
-        for rep in range(4):
-            for name in ("Q", "K"):
-                c = blk.attn.c[name]
-                if rep:
-                    nt.begin("qknorm", 3 * c.x.numel())
-                fog.rmsnorm_quantize(c.x, fog.E4M3, one, c.q, gain=1.0, amax_out=am)
-                if rep:
-                    nt.end()
-        torch.cuda.synchronize()
-        n, work, ms = nt.summary()["qknorm"]
-        kernels["qknorm_cast"] = {"launches": n, "avg_launch_ms": ms / n, "achieved": work / (ms * 1e-3) / 1e9,
-                                  "unit": "GB/s", "frac": work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "in_timed_step": False}
-    # The fused xIELU + cast producer (the input of the second feed-forward GEMM in the FOG-max variant; not part
-    # of the timed step): timed on its own over the activation input of the last linear layer (the down projection).
+        rho_qk = torch.full((1,), 39.0, device="cuda")
+        rho_max = torch.full((1,), 448.0, device="cuda")
+        qk = [blk.attn.c[name] for name in ("Q", "K")]
+        side_figure("qknorm_cast", [(3 * c.x.numel(), lambda c=c: fog.rmsnorm_quantize(c.x, fog.E4M3, rho_qk, c.q, gain=1.0, amax_out=am))
+                                    for c in qk])
+        side_figure("tanh_cast", [(3 * c.x.numel(), lambda c=c: fog.tanh_quantize(c.x, 0.5, fog.E4M3, rho_max, c.q, amax_out=am))
+                                  for c in qk])
     if blk.linears:
         c = blk.linears[-1].X
-        xt = block.EventTimer()
-        am = torch.zeros(1, device="cuda")
-        for rep in range(4):
-            if rep:
-                xt.begin("xielu", 3 * c.x.numel())
-            fog.xielu_quantize(c.x, 0.8, 0.8, fog.E4M3, c.scale, c.q, amax_out=am)
-            if rep:
-                xt.end()
-        torch.cuda.synchronize()
-        n, work, ms = xt.summary()["xielu"]
-        kernels["xielu_cast"] = {"launches": n, "avg_launch_ms": ms / n, "achieved": work / (ms * 1e-3) / 1e9,
-                                 "unit": "GB/s", "frac": work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "in_timed_step": False}
+        side_figure("xielu_cast", [(3 * c.x.numel(), lambda: fog.xielu_quantize(c.x, 0.8, 0.8, fog.E4M3, c.scale, c.q, amax_out=am))])
+        side_figure("gelu_cast", [(3 * c.x.numel(), lambda: fog.gelu_quantize(c.x, fog.E4M3, c.scale, c.q, amax_out=am))])
+        # Post-RMSNorm + residual + cast over the output of the last linear layer (the sub-layer output y) and the
+        # first layer's activation input as the residual stream x, updated into a buffer of its own:
+        # 2 + 2 B read, 2 + 1 B written per element.
+        y, xres = blk.linears[-1].Y, blk.linears[0].X
+        if y.shape == xres.x.shape:
+            gamma = torch.full((y.shape[1],), 1.0 / math.sqrt(32.0), device="cuda")
+            xnew = torch.empty_like(y)
+            side_figure("postnorm_residual_cast", [(7 * y.numel(), lambda: fog.postnorm_residual_quantize(
+                xres.x, y, gamma, fog.E4M3, xres.scale, xnew, q=xres.q, amax_out=am))])
+            del xnew
     context = None
     if args.vendor_context and blk.linears:
         # Context only: the same forward products (NT, E4M3 x E4M3 -> bf16) through the vendor library, next to
