@@ -1,7 +1,7 @@
 // Activation kurtosis (Section 4 of the paper): kurt(x) = mu[x^4] / (mu[x^2])^2 per token vector,
 // averaged over the token vectors of a tensor.  The denominator is read as the squared un-centred
 // second moment (the printed sigma^2[x^2] cannot be the variance of x^2: that would fall as an
-// outlier grows).  HBM-bound: every element is read once with 16-byte loads (eight in flight); one wave per row,
+// outlier grows).  HBM-bound: every element is read once with 16-byte loads (eight to sixteen in flight); one wave per row,
 // binary32 sums of x^2 and x^4, one float atomic per workgroup.  The same read can also deliver the
 // tensor's abs-max (Appendix E: what the scaling history of the next cast needs), so that monitoring
 // and delayed scaling share one pass over the activations.
@@ -33,46 +33,68 @@ __global__ __launch_bounds__(kThreads) void kurtosis_kernel(const uint16_t* __re
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   float local = 0.0f;   // sum of this wave's row kurtoses
   uint32_t mx = 0u;     // running max of |x| as two packed 15-bit bf16 magnitudes
-  for (int64_t r = (int64_t)blockIdx.x * 4 + w; r < rows; r += (int64_t)gridDim.x * 4) {
-    const uint16_t* row = x + r * ldx;
+  const int64_t rstep = (int64_t)gridDim.x * 4;
+  const float fcols = (float)cols;
+  // mu4 / mu2^2 = cols * s4 / s2^2; an all-zero row contributes 0
+  auto close_row = [&](float s2, float s4) {
+    s2 = wave_sum_f32(s2);
+    s4 = wave_sum_f32(s4);
+    if (s2 > 0.0f) local += fcols * (s4 / (s2 * s2));
+  };
+  if (VEC) {
+    // A row is cut into batches of up to eight 16-byte loads per lane; the wave walks its (row, batch)
+    // sequence with the next batch requested before the current one is summed, across row ends too.
+    const int64_t nvec = cols >> 3;
+    const int64_t nb = (nvec + 511) >> 9;
+    auto fetch = [&](int64_t r, int64_t b, uint4 (&v)[8]) {
+      const uint16_t* row = x + r * ldx;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int64_t i = (b << 9) + 64 * k + lane;
+        v[k] = make_uint4(0u, 0u, 0u, 0u);   // zeros add nothing to the sums or the maximum
+        if (i < nvec) v[k] = ld_nt16(row + 8 * i);
+      }
+    };
     float s2 = 0.0f, s4 = 0.0f;
-    if (VEC) {
-      const int64_t nvec = cols >> 3;
-      int64_t i = lane;
-      for (; i + 448 < nvec; i += 512) {   // eight loads in flight
-        uint4 v[8];
+    auto consume = [&](const uint4 (&v)[8], bool last) {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = ld_nt16(row + 8 * (i + 64 * k));
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          acc_pair<AMAX>(v[k].x, s2, s4, mx); acc_pair<AMAX>(v[k].y, s2, s4, mx); acc_pair<AMAX>(v[k].z, s2, s4, mx); acc_pair<AMAX>(v[k].w, s2, s4, mx);
-        }
+      for (int k = 0; k < 8; ++k) {
+        acc_pair<AMAX>(v[k].x, s2, s4, mx); acc_pair<AMAX>(v[k].y, s2, s4, mx); acc_pair<AMAX>(v[k].z, s2, s4, mx); acc_pair<AMAX>(v[k].w, s2, s4, mx);
       }
-      for (; i + 192 < nvec; i += 256) {   // four
-        uint4 v[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = ld_nt16(row + 8 * (i + 64 * k));
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          acc_pair<AMAX>(v[k].x, s2, s4, mx); acc_pair<AMAX>(v[k].y, s2, s4, mx); acc_pair<AMAX>(v[k].z, s2, s4, mx); acc_pair<AMAX>(v[k].w, s2, s4, mx);
-        }
+      if (last) {
+        close_row(s2, s4);
+        s2 = s4 = 0.0f;
       }
-      for (; i < nvec; i += 64) {
-        uint4 a = ld_nt16(row + 8 * i);
-        acc_pair<AMAX>(a.x, s2, s4, mx); acc_pair<AMAX>(a.y, s2, s4, mx); acc_pair<AMAX>(a.z, s2, s4, mx); acc_pair<AMAX>(a.w, s2, s4, mx);
-      }
-    } else {
+    };
+    int64_t r = (int64_t)blockIdx.x * 4 + w, b = 0;
+    uint4 va[8], vb[8];
+    if (r < rows) fetch(r, b, va);
+    while (r < rows) {
+      // (r1, b1): what follows (r, b)
+      int64_t r1 = r, b1 = b + 1;
+      if (b1 == nb) { r1 = r + rstep; b1 = 0; }
+      if (r1 < rows) fetch(r1, b1, vb);
+      consume(va, b + 1 == nb);
+      if (r1 >= rows) break;
+      int64_t r2 = r1, b2 = b1 + 1;
+      if (b2 == nb) { r2 = r1 + rstep; b2 = 0; }
+      if (r2 < rows) fetch(r2, b2, va);
+      consume(vb, b1 + 1 == nb);
+      r = r2;
+      b = b2;
+    }
+  } else {
+    for (int64_t r = (int64_t)blockIdx.x * 4 + w; r < rows; r += rstep) {
+      const uint16_t* row = x + r * ldx;
+      float s2 = 0.0f, s4 = 0.0f;
       for (int64_t i = lane; i < cols; i += 64) {
         const float a = bf16lo(row[i]), a2 = a * a;
         if (AMAX) mx = pkmax_abs_bf16(mx, row[i]);
         s2 += a2;
         s4 = __builtin_fmaf(a2, a2, s4);
       }
+      close_row(s2, s4);
     }
-    s2 = wave_sum_f32(s2);
-    s4 = wave_sum_f32(s4);
-    // mu4 / mu2^2 = cols * s4 / s2^2; an all-zero row contributes 0
-    if (s2 > 0.0f) local += (float)cols * (s4 / (s2 * s2));
   }
   __shared__ float part[4];
   __shared__ uint32_t pmax[4];
@@ -110,7 +132,7 @@ extern "C" fog_status fog_kurtosis(const void* x_bf16, int64_t rows, int64_t col
   if (reinterpret_cast<uintptr_t>(x_bf16) & 1u) return FOG_ERR_ALIGN;
   const bool vec = (reinterpret_cast<uintptr_t>(x_bf16) & 15u) == 0 && cols % 8 == 0 && ldx % 8 == 0;
   int64_t blocks = (rows + 3) / 4;
-  if (blocks > 2048) blocks = 2048;
+  if (blocks > 1024) blocks = 1024;   // four workgroups per CU are resident
   const uint16_t* x = reinterpret_cast<const uint16_t*>(x_bf16);
   const float inv = 1.0f / (float)rows;
 #define FOG_KURT(V, A) kurtosis_kernel<V, A><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, inv, kurt, am)
