@@ -43,14 +43,15 @@ __global__ __launch_bounds__(kThreads) void qknorm_rows_kernel(const uint16_t* _
   const float rho = *scale;
   const int sub = threadIdx.x % LPR, rloc = threadIdx.x / LPR;
   float m = 0.0f;
-  for (int64_t r0 = (int64_t)blockIdx.x * (RPB * U); r0 < rows; r0 += (int64_t)gridDim.x * (RPB * U)) {
-    uint4 v[U];
+  auto fetch = [&](int64_t r0, uint4 (&v)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t r = r0 + u * RPB + rloc;
       v[u] = make_uint4(0u, 0u, 0u, 0u);
       if (r < rows) v[u] = ld_nt16(x + r * ldx + 8 * sub);
     }
+  };
+  auto process = [&](int64_t r0, const uint4 (&v)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t r = r0 + u * RPB + rloc;
@@ -74,6 +75,21 @@ __global__ __launch_bounds__(kThreads) void qknorm_rows_kernel(const uint16_t* _
         st_nt8(q + r * ldq + 8 * sub, o);
       }
     }
+  };
+  // the next trip's loads are requested before the current trip is normalised
+  const int64_t step = (int64_t)gridDim.x * (RPB * U);
+  int64_t r0 = (int64_t)blockIdx.x * (RPB * U);
+  uint4 va[U], vb[U];
+  if (r0 < rows) fetch(r0, va);
+  while (r0 < rows) {
+    const int64_t r1 = r0 + step;
+    if (r1 < rows) fetch(r1, vb);
+    process(r0, va);
+    if (r1 >= rows) break;
+    const int64_t r2 = r1 + step;
+    if (r2 < rows) fetch(r2, va);
+    process(r1, vb);
+    r0 = r2;
   }
   if (amax_out) block_amax(m, amax_out);
 }
@@ -112,7 +128,7 @@ void launch_qknorm(const uint16_t* x, int64_t rows, int64_t cols, int64_t ldx, f
 #define FOG_QKN(LPR)                                                                                            \
   do {                                                                                                          \
     int64_t blocks = (rows + 4 * (kThreads / LPR) - 1) / (4 * (kThreads / LPR));                                \
-    if (blocks > 4096) blocks = 4096;                                                                           \
+    if (blocks > 2048) blocks = 2048;                                                                           \
     qknorm_rows_kernel<FMT, LPR><<<(int)blocks, kThreads, 0, s>>>(x, rows, ldx, gain, scale, q, ldq, amax_out); \
     return;                                                                                                     \
   } while (0)
