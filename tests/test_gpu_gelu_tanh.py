@@ -15,7 +15,8 @@ from parity import dev, fscalar
 
 pytestmark = pytest.mark.gpu
 
-SHAPES = [(1, 16, 0), (64, 256, 0), (333, 1024, 0), (100, 272, 16), (7, 17, 3), (50, 100, 0), (1024, 8192, 0)]
+SHAPES = [(1, 16, 0), (64, 256, 0), (333, 1024, 0), (100, 272, 16), (7, 17, 3), (50, 100, 0), (1024, 8192, 0),
+          (4100, 7168, 0), (8200, 2064, 16)]       # the last two: several trips per workgroup at the largest grid
 
 
 def run(kind, xb, cols, fmt, rho, alpha, pad_q):

@@ -58,7 +58,8 @@ def make(rows, cols, pad, seed):
 
 @pytest.mark.parametrize("fmt", [fp8.E4M3, fp8.E5M2])
 @pytest.mark.parametrize("rows,cols,pad", [(1, 512, 0), (37, 1024, 0), (16, 1536, 8), (130, 4096, 0), (9, 5120, 0), (6, 8192, 0),
-                                           (5, 17, 3), (33, 100, 0), (3, 8704, 0), (12, 520, 0), (1024, 4096, 0)])
+                                           (5, 17, 3), (33, 100, 0), (3, 8704, 0), (12, 520, 0), (1024, 4096, 0),
+                                           (33000, 512, 0), (40000, 24, 0)])       # more rows than one pass of the largest grid
 def test_postnorm_parity(rows, cols, pad, fmt):
     xb, yb, gamma = make(rows, cols, pad, rows + cols + fmt)
     ref = postnorm.residual_bf16(xb[:, :cols], yb[:, :cols], gamma)

@@ -73,6 +73,17 @@ def test_qknorm_special_rows_and_saturation():
     assert fp8.decode(q, fp8.E4M3)[2, 40] == -448.0 and np.isfinite(fp8.decode(q, fp8.E4M3)).all()
 
 
+def test_qknorm_several_trips_per_workgroup():
+    """More rows than one trip of the largest grid covers (2048 workgroups x 64 rows at D = 128): the pipelined
+    loop runs two to four trips with a ragged last one; config 5's Q has 262144 rows."""
+    rng = np.random.default_rng(11)
+    rows = 3 * 131072 + 77
+    xb = synth.f32_to_bf16_bits(rng.standard_normal((rows, 128)).astype(np.float32))
+    check(xb, 128, fp8.E4M3, np.float32(448.0 / 5.0), 1.0)
+    xb = synth.f32_to_bf16_bits(rng.standard_normal((2048 * 32 * 2 + 5, 64)).astype(np.float32))
+    check(xb, 64, fp8.E5M2, np.float32(57344.0 / 5.0), 1.25)
+
+
 def test_qknorm_config_shape_and_errors():
     """The Q tensor of config 3 whole ([B H S, 128] = 131072 rows), then the argument checks."""
     cfg = synth.CONFIGS[3]

@@ -41,7 +41,7 @@ def check(xb, cols, fmt, rho, ap, an, pad_q=0):
 
 @pytest.mark.parametrize("fmt", [fp8.E4M3, fp8.E5M2])
 @pytest.mark.parametrize("rows,cols,pad", [(1, 16, 0), (64, 256, 0), (333, 1024, 0), (100, 272, 16), (7, 17, 3), (50, 100, 0),
-                                           (1024, 8192, 0)])
+                                           (1024, 8192, 0), (4100, 7168, 0), (8200, 2064, 16)])
 def test_xielu_parity(rows, cols, pad, fmt):
     rng = np.random.default_rng(rows + cols + fmt)
     x = (rng.standard_normal((rows, cols + pad)) * 2.0).astype(np.float32)
