@@ -36,6 +36,7 @@ class Cast:
         self.scale = torch.ones(1, device="cuda")
         self.sinv = torch.ones(1, device="cuda")
         self.ws = torch.empty(fog.quantize_jit_workspace(), dtype=torch.uint8, device="cuda")
+        self.history = None     # abs-max history of delayed scaling, allocated on first use
         self.bytes_jit = (5 + (1 if transpose else 0)) * rows * cols   # abs-max pass 2 B, cast pass 2 B in + 1 (+1 transposed) out
 
     def run(self, timer=None):
@@ -43,6 +44,21 @@ class Cast:
         if timer:
             timer.begin("cast_jit", self.bytes_jit)
         fog.quantize_jit(self.x, self.fmt, self.amax, self.scale, self.sinv, self.ws, q=self.q, qT=self.qT)
+        if timer:
+            timer.end()
+
+    def run_delayed(self, timer=None):
+        """Delayed scaling (Appendix E): the abs-max the previous pass reported enters the history (length 1024),
+        the scale comes from the history's maximum, and ONE pass over the tensor casts with it and reports this
+        pass's abs-max: 2 B read + 1 B written per element instead of 5.  Before the first abs-max exists the
+        scale is 1."""
+        if self.history is None:
+            self.history = torch.zeros(1024, device="cuda")
+            self.amax.zero_()
+        fog.scale_delayed(self.history, self.amax, self.fmt, self.scale, self.sinv)
+        if timer:
+            timer.begin("cast_delayed", self.bytes_jit - 2 * self.x.numel())
+        fog.quantize(self.x, self.fmt, self.scale, q=self.q, qT=self.qT, amax_out=self.amax)
         if timer:
             timer.end()
 
@@ -74,11 +90,11 @@ class LinearStep:
         self.dW = torch.empty((N, K), dtype=torch.int16, device="cuda")
         self.flops = 3 * 2 * M * N * K
 
-    def run(self, timer=None):
+    def run(self, timer=None, delayed=False):
         lin = self.lin
         M, N, K = lin.M, lin.N, lin.K
         for c in (self.X, self.W, self.dY):
-            c.run(timer)
+            c.run_delayed(timer) if delayed else c.run(timer)
         # The three products are launched back to back and bracketed by ONE event pair (an event between two
         # launches costs a gap of several microseconds on the stream): the pair's time is that of three launches.
         if timer:
@@ -115,17 +131,17 @@ class AttentionStep:
         self.flops = self.flops_fwd + self.flops_bwd
         self.calibrated = False
 
-    def run(self, timer=None):
+    def run(self, timer=None, delayed=False):
         a, c = self.attn, self.c
         for name in ("Q", "K", "V"):
-            c[name].run(timer)
+            c[name].run_delayed(timer) if delayed else c[name].run(timer)
         if timer:
             timer.begin("attn_fwd", self.flops_fwd)
         fog.fp8_attn_fwd(a.B, a.H, a.S, a.D, self.s, True, c["Q"].q, c["K"].q, c["V"].q, c["Q"].sinv, c["K"].sinv,
                          c["V"].sinv, self.scale_p, self.O, self.lse)
         if timer:
             timer.end()
-        c["dO"].run(timer)
+        c["dO"].run_delayed(timer) if delayed else c["dO"].run(timer)
         if timer:
             timer.begin("attn_bwd", self.flops_bwd)
         # delayed-style scale for dS: the abs-max this call reports sets the scale of the next call
@@ -149,11 +165,12 @@ class Block:
         self.attn = AttentionStep(cfg.attn, synth.attention_tensors(cfg)) if cfg.attn is not None else None
         self.flops = sum(l.flops for l in self.linears) + (self.attn.flops if self.attn else 0)
 
-    def step(self, timer=None):
+    def step(self, timer=None, delayed=False):
+        """One pass of the path; delayed=True scales every cast from its abs-max history instead of just in time."""
         for l in self.linears:
-            l.run(timer)
+            l.run(timer, delayed)
         if self.attn:
-            self.attn.run(timer)
+            self.attn.run(timer, delayed)
 
 
 class EventTimer:

@@ -203,3 +203,35 @@ def test_quantize_jit_argument_errors():
     assert call(x.data_ptr(), 16, 16, 16, 0, 99, q.data_ptr(), 16, None, 0, a, s, si, ws.data_ptr(), 4096, st) == 2
     assert call(x.data_ptr(), 16, 16, 16, 0, 0, q.data_ptr(), 16, None, 0, a, s, None, ws.data_ptr(), 4096, st) == 0
     torch.cuda.synchronize()
+
+
+def test_delayed_scaling_flow_of_the_block_driver():
+    """Cast.run_delayed over five passes with changing data: the scale of pass t comes from the history of the
+    abs-maxes of passes < t (1 before any exists), the codes are the cast with that scale, the reported abs-max is
+    this pass's; all bit for bit against the oracle's history functions (Appendix E)."""
+    from paper_2505_20524_amd import block
+    rng = np.random.default_rng(77)
+    rows, cols = 96, 160
+    for fmt, transpose in ((fp8.E4M3, True), (fp8.E5M2, False)):
+        xb0 = synth.f32_to_bf16_bits(rng.standard_normal((rows, cols)).astype(np.float32))
+        c = block.Cast(dev(xb0), fmt, transpose)
+        hist = np.zeros(1024, np.float32)
+        prev_amax = np.float32(0.0)
+        for t, gain in enumerate((1.0, 30.0, 0.01, 5.0, 5.0)):
+            xb = synth.f32_to_bf16_bits(rng.standard_normal((rows, cols)).astype(np.float32) * gain)
+            c.x.copy_(dev(xb))
+            c.run_delayed()
+            torch.cuda.synchronize()
+            hist = scaling.history_update(hist, prev_amax)
+            rho, rinv = scaling.history_scale(hist, fmt)
+            assert np.float32(c.scale.item()).tobytes() == rho.tobytes(), t
+            assert np.float32(c.sinv.item()).tobytes() == rinv.tobytes(), t
+            want = scaling.quantize(xb, rho, fmt)
+            assert np.array_equal(c.q.cpu().numpy(), want), t
+            if transpose:
+                assert np.array_equal(c.qT.cpu().numpy(), want.T), t
+            prev_amax = scaling.amax(xb)
+            assert np.float32(c.amax.item()) == prev_amax
+            assert np.array_equal(c.history.cpu().numpy(), hist)
+        # after the small third pass the scale still comes from the large second one: the history remembers
+        assert hist.max() == hist[2]
