@@ -144,7 +144,9 @@ FOG_DEVICE float lane_xor32(float v) { return __shfl_xor(v, 32, 64); }
 __global__ __launch_bounds__(kThreads) void attn_bwd_rowdot_kernel(const uint16_t* __restrict__ O, const uint16_t* __restrict__ dO,
                                                                    const float* __restrict__ lse, const float* __restrict__ scale_p,
                                                                    const float* __restrict__ scale_ds, float* __restrict__ ws,
-                                                                   int64_t rows) {
+                                                                   int64_t rows, uint32_t* __restrict__ amax_ds) {
+  // the abs-max of dS starts from 0; the kernels that raise it are launched after this one on the same stream
+  if (amax_ds && blockIdx.x == 0 && threadIdx.x == 0) *amax_ds = 0u;
   const int64_t row = (int64_t)blockIdx.x * (kThreads / 16) + (threadIdx.x >> 4);
   const int part = threadIdx.x & 15;
   float s = 0.0f;
@@ -542,9 +544,9 @@ extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int H_kv, int S, int D, flo
   a.softmax_scale = softmax_scale;
   a.BH = B * H; a.S = S; a.nblk = (S + BLK - 1) / BLK;
   a.BHkv = B * H_kv; a.G = H / H_kv;
-  if (amax_ds) zero_u32b<<<1, 1, 0, s>>>(a.amax_ds);
   const int64_t rows = (int64_t)a.BH * S;
-  attn_bwd_rowdot_kernel<<<(int)((rows + 15) / 16), kThreads, 0, s>>>(a.O, a.dO, a.lse, a.scale_p, a.scale_ds, a.Dws, rows);
+  attn_bwd_rowdot_kernel<<<(int)((rows + 15) / 16), kThreads, 0, s>>>(a.O, a.dO, a.lse, a.scale_p, a.scale_ds, a.Dws, rows,
+                                                                      amax_ds ? a.amax_ds : nullptr);
   const int grid = a.BH * a.nblk, grid_kv = a.BHkv * a.nblk;
   // dV and dK as two launches (two workgroups per CU each) when there are enough key blocks to fill the
   // chip four times over; with few key/value heads the single combined launch balances better.
