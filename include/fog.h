@@ -129,6 +129,35 @@ fog_status fog_quantize_jit(const void* x_bf16, int64_t rows, int64_t cols, int6
 size_t fog_quantize_jit_workspace(void);
 
 /*
+ * Delayed scaling in ONE launch per cast (Appendix E: the scale of a cast comes from the maximum of
+ * the last history_len abs-maxes of the same tensor; Section 2: one pass over the data, against two
+ * for just-in-time scaling).  Call number `step` (0, 1, 2, ... for one tensor, no gaps):
+ *     a_prev  = abs-max of the tensor cast by call step - 1   (0 for step 0)
+ *     history[step mod history_len] = a_prev                   (the oldest entry is replaced)
+ *     scale   = FP8MAX / (2^margin * max(history)),  scale_inv = 1 / scale     (rules of fog_scale)
+ *     q, qT   = casts of x with that scale                     (as fog_quantize)
+ * and the abs-max of x is left in `state` for call step + 1.  Same results, bit for bit, as
+ * fog_scale_delayed followed by fog_quantize(..., amax_out), without their two small launches; the
+ * history is a ring here (entry step mod history_len is the one replaced) where fog_scale_delayed
+ * shifts it, which leaves its maximum, the only thing used, the same.
+ *   history : history_len floats, caller-initialised (zeros: scale 1 until an abs-max exists).
+ *   state   : fog_quantize_delayed_state() bytes (12 KB), 4-byte aligned, owned by the caller, ALL ZERO
+ *             before step 0 and untouched by the caller afterwards; one per tensor.
+ *   amax_prev : NULL or one float, receives a_prev.   scale : one float.   scale_inv : one float or NULL.
+ *   x_bf16, q, qT, leading dimensions, fmt : as in fog_quantize.   margin : as in fog_scale.
+ * An empty tensor advances the history with abs-max 0.  fog_delayed_amax reads the abs-max that call
+ * `step` left in the state (for a checkpoint of the scaling state, or after the last step).
+ * Errors: as fog_quantize and fog_scale; WORKSPACE when the state is too small; SHAPE for step < 0 or
+ * history_len < 1.
+ */
+fog_status fog_quantize_delayed(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, fog_fp8 fmt, int margin,
+                                float* history, int history_len, int64_t step, void* state, size_t state_bytes,
+                                uint8_t* q, int64_t ldq, uint8_t* qT, int64_t ldqT,
+                                float* amax_prev, float* scale, float* scale_inv, void* stream);
+size_t fog_quantize_delayed_state(void);
+fog_status fog_delayed_amax(const void* state, int64_t step, float* amax, void* stream);
+
+/*
  * QK RMS normalisation with a frozen gain, fused with the FP8 cast (Section 3: N_gamma(x) =
  * gamma x / rms(x), rms(x) = ||x||_2 / sqrt(D), applied to every query / key vector; the FOG
  * variants freeze the gains and Appendix A folds their value into the softmax scale, which

@@ -48,19 +48,29 @@ class Cast:
             timer.end()
 
     def run_delayed(self, timer=None):
-        """Delayed scaling (Appendix E): the abs-max the previous pass reported enters the history (length 1024),
-        the scale comes from the history's maximum, and ONE pass over the tensor casts with it and reports this
-        pass's abs-max: 2 B read + 1 B written per element instead of 5.  Before the first abs-max exists the
-        scale is 1."""
+        """Delayed scaling (Appendix E) in one launch: the abs-max the previous pass left behind enters the history
+        (length 1024), the scale comes from the history's maximum, and ONE pass over the tensor casts with it and
+        leaves this pass's abs-max for the next: 2 B read + 1 B written per element instead of 5.  Before the
+        first abs-max exists the scale is 1."""
+        if self.history is None:
+            self.history = torch.zeros(1024, device="cuda")
+            self.state = torch.zeros(fog.quantize_delayed_state(), dtype=torch.uint8, device="cuda")
+            self.step = 0
+        if timer:
+            timer.begin("cast_delayed", self.bytes_jit - 2 * self.x.numel())
+        fog.quantize_delayed(self.x, self.fmt, self.history, self.step, self.state, self.scale, self.sinv, q=self.q, qT=self.qT,
+                             amax_prev=self.amax)
+        if timer:
+            timer.end()
+        self.step += 1
+
+    def run_delayed_two_calls(self):
+        """The same flow through fog_scale_delayed and fog_quantize(..., amax_out): three launches, a shifting history."""
         if self.history is None:
             self.history = torch.zeros(1024, device="cuda")
             self.amax.zero_()
         fog.scale_delayed(self.history, self.amax, self.fmt, self.scale, self.sinv)
-        if timer:
-            timer.begin("cast_delayed", self.bytes_jit - 2 * self.x.numel())
         fog.quantize(self.x, self.fmt, self.scale, q=self.q, qT=self.qT, amax_out=self.amax)
-        if timer:
-            timer.end()
 
     def run_separate(self):
         """The same flow through the three calls fog_amax, fog_scale, fog_quantize (four launches)."""

@@ -155,37 +155,83 @@ __global__ __launch_bounds__(kThreads) void scale_partials_kernel(const uint32_t
 // The same reduction inside a cast kernel: under just-in-time scaling every workgroup of the cast pass
 // derives the scale itself from the per-workgroup maxima of the abs-max pass (at most 4 KB, served from
 // L2), so no launch sits between the two passes; workgroup 0 publishes abs-max, scale and 1/scale.
+// Under delayed scaling in one launch (fog_quantize_delayed) the maxima are those the PREVIOUS cast of
+// this tensor left behind: their maximum enters the abs-max history (a ring: entry `slot` is replaced,
+// every workgroup takes the maximum over the other entries and the new value, workgroup 0 stores it),
+// the scale comes from the history's maximum, and this pass's own maxima go to `cur`, 1024 words that
+// the previous pass cleared; workgroup 0 clears `next` for the pass after this one.  Three buffers in
+// rotation: no word is read and written by different workgroups of one launch.
 struct JitScale {
   const uint32_t* part;   // NULL: the scale is read from memory instead
   int n, fmt, margin;
   float* amax;
   float* scale;
   float* scale_inv;
+  float* hist;            // delayed scaling only (else NULL): the history, hlen entries, entry `slot` is replaced
+  int hlen, slot;
+  uint32_t* cur;          // delayed scaling only: where this pass's workgroup maxima are raised (atomic max)
+  uint32_t* next;         // delayed scaling only: cleared by workgroup 0
 };
+constexpr int kDelayedSlots = 1024;
 FOG_DEVICE float scale_from_partials(const JitScale& js) {
   uint32_t m = 0;
   for (int i = threadIdx.x; i < js.n; i += kThreads) m = m > js.part[i] ? m : js.part[i];
+  uint32_t h = 0;   // maximum of the history entries that stay
+  if (js.hist) {
+    for (int i = threadIdx.x; i < js.hlen; i += kThreads) {
+      const uint32_t v = i == js.slot ? 0u : __float_as_uint(js.hist[i]);   // abs-maxes: non-negative floats order like their bits
+      h = h > v ? h : v;
+    }
+    if (blockIdx.x == 0)
+      for (int i = threadIdx.x; i < kDelayedSlots; i += kThreads) js.next[i] = 0u;
+  }
   m = wave_max_u32(m);
-  __shared__ uint32_t wmax[kThreads / 64];
+  h = wave_max_u32(h);
+  __shared__ uint32_t wmax[kThreads / 64], hmax[kThreads / 64];
   __shared__ float rho_shared;
-  if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
+  if ((threadIdx.x & 63) == 0) {
+    wmax[threadIdx.x >> 6] = m;
+    hmax[threadIdx.x >> 6] = h;
+  }
   __syncthreads();
   if (threadIdx.x == 0) {
-    uint32_t r = wmax[0];
+    uint32_t r = wmax[0], rh = hmax[0];
 #pragma unroll
-    for (int w = 1; w < kThreads / 64; ++w) r = r > wmax[w] ? r : wmax[w];
-    const float a = __uint_as_float(r);
+    for (int w = 1; w < kThreads / 64; ++w) {
+      r = r > wmax[w] ? r : wmax[w];
+      rh = rh > hmax[w] ? rh : hmax[w];
+    }
+    const float a = __uint_as_float(r);                       // abs-max of the tensor the maxima belong to
+    const float basis = __uint_as_float(r > rh ? r : rh);     // what the scale is derived from
     float sc, si;
-    scale_from_amax(a, js.fmt, js.margin, &sc, &si);
+    scale_from_amax(basis, js.fmt, js.margin, &sc, &si);
     rho_shared = sc;
     if (blockIdx.x == 0) {
-      *js.amax = a;
+      if (js.amax) *js.amax = a;
+      if (js.hist) js.hist[js.slot] = a;
       *js.scale = sc;
       if (js.scale_inv) *js.scale_inv = si;
     }
   }
   __syncthreads();
   return rho_shared;
+}
+
+// One workgroup of the above without a cast (empty tensors), and the maximum of one buffer of maxima.
+__global__ __launch_bounds__(kThreads) void delayed_scale_only_kernel(JitScale js) { scale_from_partials(js); }
+__global__ __launch_bounds__(kThreads) void partials_max_kernel(const uint32_t* __restrict__ part, int n, float* __restrict__ amax) {
+  uint32_t m = 0;
+  for (int i = threadIdx.x; i < n; i += kThreads) m = m > part[i] ? m : part[i];
+  m = wave_max_u32(m);
+  __shared__ uint32_t wmax[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t r = wmax[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) r = r > wmax[w] ? r : wmax[w];
+    *amax = __uint_as_float(r);
+  }
 }
 
 // One workgroup: roll the history by one (newest first), then scale from its maximum.
@@ -279,7 +325,7 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t*
       uint32_t r = part[0];
 #pragma unroll
       for (int w = 1; w < kThreads / 64; ++w) r = r > part[w] ? r : part[w];
-      if (r) atomicMax(amax_out, r << 16);
+      if (r) atomicMax(js.cur ? js.cur + (blockIdx.x & (kDelayedSlots - 1)) : amax_out, r << 16);
     }
   }
 }
@@ -369,7 +415,7 @@ __global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const uint
       uint32_t r = part[0];
 #pragma unroll
       for (int w = 1; w < kThreads / 64; ++w) r = r > part[w] ? r : part[w];
-      if (r) atomicMax(amax_out, r << 16);
+      if (r) atomicMax(js.cur ? js.cur + (blockIdx.x & (kDelayedSlots - 1)) : amax_out, r << 16);
     }
   }
 }
@@ -396,7 +442,7 @@ __global__ __launch_bounds__(kThreads) void quantize_general_kernel(const uint16
   }
   if (amax_out) {
     m = wave_max_u32(m);
-    if ((threadIdx.x & 63) == 0 && m) atomicMax(amax_out, m << 16);
+    if ((threadIdx.x & 63) == 0 && m) atomicMax(js.cur ? js.cur + (blockIdx.x & (kDelayedSlots - 1)) : amax_out, m << 16);
   }
 }
 
@@ -541,8 +587,46 @@ extern "C" fog_status fog_quantize_jit(const void* x_bf16, int64_t rows, int64_t
     scale_partials_kernel<<<1, kThreads, 0, s>>>(ws, 0, (int)fmt, margin, amax, scale, scale_inv);
     return fog_launch_status();
   }
-  const JitScale js{ws, (int)blocks, (int)fmt, margin, amax, scale, scale_inv};
+  const JitScale js{ws, (int)blocks, (int)fmt, margin, amax, scale, scale_inv, nullptr, 0, 0, nullptr, nullptr};
   if (fmt == FOG_E4M3) launch_quantize<FOG_E4M3>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, nullptr, s, js);
   else                 launch_quantize<FOG_E5M2>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, nullptr, s, js);
+  return fog_launch_status();
+}
+
+extern "C" size_t fog_quantize_delayed_state(void) { return 3 * kDelayedSlots * sizeof(uint32_t); }
+
+extern "C" fog_status fog_quantize_delayed(const void* x_bf16, int64_t rows, int64_t cols, int64_t ldx, fog_fp8 fmt, int margin,
+                                           float* history, int history_len, int64_t step, void* state, size_t state_bytes,
+                                           uint8_t* q, int64_t ldq, uint8_t* qT, int64_t ldqT,
+                                           float* amax_prev, float* scale, float* scale_inv, void* stream) {
+  if (!history || !state || !scale) return FOG_ERR_NULL;
+  if (state_bytes < fog_quantize_delayed_state()) return FOG_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(state) & 3u) != 0) return FOG_ERR_ALIGN;
+  if (history_len < 1 || step < 0 || margin < -64 || margin > 64) return FOG_ERR_SHAPE;
+  const fog_status st = quantize_checks(x_bf16, rows, cols, ldx, fmt, q, ldq, qT, ldqT);
+  if (st != FOG_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  uint32_t* base = reinterpret_cast<uint32_t*>(state);
+  uint32_t* prev = base + ((step + 2) % 3) * kDelayedSlots;
+  uint32_t* cur = base + (step % 3) * kDelayedSlots;
+  uint32_t* next = base + ((step + 1) % 3) * kDelayedSlots;
+  const JitScale js{prev, kDelayedSlots, (int)fmt, margin, amax_prev, scale, scale_inv,
+                    history, history_len, (int)(step % history_len), cur, next};
+  if (rows == 0 || cols == 0) {   // nothing to cast: the history still advances, this pass's abs-max stays 0
+    delayed_scale_only_kernel<<<1, kThreads, 0, s>>>(js);
+    return fog_launch_status();
+  }
+  const uint16_t* x = reinterpret_cast<const uint16_t*>(x_bf16);
+  if (fmt == FOG_E4M3) launch_quantize<FOG_E4M3>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, cur, s, js);
+  else                 launch_quantize<FOG_E5M2>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, cur, s, js);
+  return fog_launch_status();
+}
+
+extern "C" fog_status fog_delayed_amax(const void* state, int64_t step, float* amax, void* stream) {
+  if (!state || !amax) return FOG_ERR_NULL;
+  if (step < 0) return FOG_ERR_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(state) & 3u) != 0) return FOG_ERR_ALIGN;
+  const uint32_t* cur = reinterpret_cast<const uint32_t*>(state) + (step % 3) * kDelayedSlots;
+  partials_max_kernel<<<1, kThreads, 0, (hipStream_t)stream>>>(cur, kDelayedSlots, amax);
   return fog_launch_status();
 }

@@ -28,6 +28,9 @@ SIGNATURES = {
     "fog_quantize": (_I, [_P, _I64, _I64, _I64, _I, _P, _P, _I64, _P, _I64, _P, _P]),
     "fog_quantize_jit": (_I, [_P, _I64, _I64, _I64, _I, _I, _P, _I64, _P, _I64, _P, _P, _P, _P, _SZ, _P]),
     "fog_quantize_jit_workspace": (_SZ, []),
+    "fog_quantize_delayed": (_I, [_P, _I64, _I64, _I64, _I, _I, _P, _I, _I64, _P, _SZ, _P, _I64, _P, _I64, _P, _P, _P, _P]),
+    "fog_quantize_delayed_state": (_SZ, []),
+    "fog_delayed_amax": (_I, [_P, _I64, _P, _P]),
     "fog_rmsnorm_quantize": (_I, [_P, _I64, _I64, _I64, _F, _I, _P, _P, _I64, _P, _P]),
     "fog_xielu_quantize": (_I, [_P, _I64, _I64, _I64, _F, _F, _I, _P, _P, _I64, _P, _P]),
     "fog_gelu_quantize": (_I, [_P, _I64, _I64, _I64, _I, _P, _P, _I64, _P, _P]),
@@ -113,6 +116,25 @@ def quantize_jit(x, fmt, amax_out, scale_out, scale_inv_out, workspace, q=None, 
 
 def quantize_jit_workspace():
     return load().fog_quantize_jit_workspace()
+
+
+def quantize_delayed(x, fmt, history, step, state, scale_out, scale_inv_out=None, q=None, qT=None, amax_prev=None, margin=0,
+                     stream=None):
+    rows, cols = x.shape
+    _check(load().fog_quantize_delayed(_ptr(x), rows, cols, x.stride(0), fmt, margin, _ptr(history), history.numel(), step,
+                                       _ptr(state), state.numel() * state.element_size(),
+                                       _ptr(q), q.stride(0) if q is not None else 0,
+                                       _ptr(qT), qT.stride(0) if qT is not None else 0,
+                                       _ptr(amax_prev), _ptr(scale_out), _ptr(scale_inv_out), _stream(stream)),
+           "fog_quantize_delayed")
+
+
+def quantize_delayed_state():
+    return load().fog_quantize_delayed_state()
+
+
+def delayed_amax(state, step, amax_out, stream=None):
+    _check(load().fog_delayed_amax(_ptr(state), step, _ptr(amax_out), _stream(stream)), "fog_delayed_amax")
 
 
 def rmsnorm_quantize(x, fmt, scale_t, q, gain=1.0, amax_out=None, stream=None):

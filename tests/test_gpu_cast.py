@@ -205,33 +205,111 @@ def test_quantize_jit_argument_errors():
     torch.cuda.synchronize()
 
 
-def test_delayed_scaling_flow_of_the_block_driver():
-    """Cast.run_delayed over five passes with changing data: the scale of pass t comes from the history of the
-    abs-maxes of passes < t (1 before any exists), the codes are the cast with that scale, the reported abs-max is
-    this pass's; all bit for bit against the oracle's history functions (Appendix E)."""
+def test_delayed_scaling_flows_of_the_block_driver():
+    """Cast.run_delayed (one launch per cast) and Cast.run_delayed_two_calls over five passes with changing data:
+    the scale of pass t comes from the history of the abs-maxes of passes < t (1 before any exists), the codes are
+    the cast with that scale, the abs-max of pass t reaches the history at pass t + 1; all bit for bit against the
+    oracle's history functions (Appendix E)."""
     from paper_2505_20524_amd import block
     rng = np.random.default_rng(77)
     rows, cols = 96, 160
-    for fmt, transpose in ((fp8.E4M3, True), (fp8.E5M2, False)):
-        xb0 = synth.f32_to_bf16_bits(rng.standard_normal((rows, cols)).astype(np.float32))
-        c = block.Cast(dev(xb0), fmt, transpose)
-        hist = np.zeros(1024, np.float32)
-        prev_amax = np.float32(0.0)
-        for t, gain in enumerate((1.0, 30.0, 0.01, 5.0, 5.0)):
-            xb = synth.f32_to_bf16_bits(rng.standard_normal((rows, cols)).astype(np.float32) * gain)
-            c.x.copy_(dev(xb))
-            c.run_delayed()
+    for one_launch in (True, False):
+        for fmt, transpose in ((fp8.E4M3, True), (fp8.E5M2, False)):
+            xb0 = synth.f32_to_bf16_bits(rng.standard_normal((rows, cols)).astype(np.float32))
+            c = block.Cast(dev(xb0), fmt, transpose)
+            hist = np.zeros(1024, np.float32)
+            prev_amax = np.float32(0.0)
+            for t, gain in enumerate((1.0, 30.0, 0.01, 5.0, 5.0)):
+                xb = synth.f32_to_bf16_bits(rng.standard_normal((rows, cols)).astype(np.float32) * gain)
+                c.x.copy_(dev(xb))
+                c.run_delayed() if one_launch else c.run_delayed_two_calls()
+                torch.cuda.synchronize()
+                if one_launch:
+                    hist[t % 1024] = prev_amax                      # a ring: the oldest entry is replaced
+                    assert np.float32(c.amax.item()) == prev_amax     # amax_prev output
+                else:
+                    hist = scaling.history_update(hist, prev_amax)    # newest first, everything shifts
+                rho, rinv = scaling.history_scale(hist, fmt)
+                assert np.float32(c.scale.item()).tobytes() == rho.tobytes(), t
+                assert np.float32(c.sinv.item()).tobytes() == rinv.tobytes(), t
+                want = scaling.quantize(xb, rho, fmt)
+                assert np.array_equal(c.q.cpu().numpy(), want), t
+                if transpose:
+                    assert np.array_equal(c.qT.cpu().numpy(), want.T), t
+                prev_amax = scaling.amax(xb)
+                if one_launch:
+                    am = torch.full((1,), -1.0, device="cuda")
+                    fog.delayed_amax(c.state, t, am)
+                    assert np.float32(am.item()) == prev_amax
+                else:
+                    assert np.float32(c.amax.item()) == prev_amax
+                assert np.array_equal(c.history.cpu().numpy(), hist)
+            # after the small third pass the scale still comes from the large second one: the history remembers
+            assert hist.max() == hist[2]
+
+
+@pytest.mark.parametrize("rows,cols,pad,transpose", [(64, 256, 0, False), (256, 384, 0, True), (37, 100, 4, True), (1500, 4096, 0, False),
+                                                     (2048, 2048, 0, True)])
+def test_quantize_delayed_short_history_forgets(rows, cols, pad, transpose):
+    """fog_quantize_delayed with a history of three entries over eight calls (one of them on an empty tensor): an old
+    large abs-max leaves the ring after three further calls; row-major, transposing and element-wise kernels, grids
+    above and below the 1024 slots of the state."""
+    rng = np.random.default_rng(rows + cols)
+    fmt = fp8.E4M3 if rows % 2 == 0 else fp8.E5M2
+    hist_d = torch.zeros(3, device="cuda")
+    state = torch.zeros(fog.quantize_delayed_state(), dtype=torch.uint8, device="cuda")
+    s, si, ap = (torch.zeros(1, device="cuda") for _ in range(3))
+    ring = np.zeros(3, np.float32)
+    prev = np.float32(0.0)
+    for t, gain in enumerate((1.0, 100.0, 1.0, 0.5, None, 2.0, 1.0, 1.0)):
+        ring[t % 3] = prev
+        rho, rinv = scaling.history_scale(ring, fmt, margin=1)
+        if gain is None:     # an empty tensor: the history advances, nothing is cast
+            fog.quantize_delayed(torch.zeros((0, cols), dtype=torch.int16, device="cuda"), fmt, hist_d, t, state, s, si, amax_prev=ap,
+                                 margin=1)
             torch.cuda.synchronize()
-            hist = scaling.history_update(hist, prev_amax)
-            rho, rinv = scaling.history_scale(hist, fmt)
-            assert np.float32(c.scale.item()).tobytes() == rho.tobytes(), t
-            assert np.float32(c.sinv.item()).tobytes() == rinv.tobytes(), t
-            want = scaling.quantize(xb, rho, fmt)
-            assert np.array_equal(c.q.cpu().numpy(), want), t
+            prev_next = np.float32(0.0)
+        else:
+            xb = synth.f32_to_bf16_bits(rng.standard_normal((rows, cols + pad)).astype(np.float32) * gain)
+            x = dev(xb)[:, :cols] if pad else dev(xb)
+            q = torch.full((rows, cols), 0xAA, dtype=torch.uint8, device="cuda")
+            qT = torch.full((cols, rows), 0xAA, dtype=torch.uint8, device="cuda") if transpose else None
+            fog.quantize_delayed(x, fmt, hist_d, t, state, s, si, q=q, qT=qT, amax_prev=ap, margin=1)
+            torch.cuda.synchronize()
+            want = scaling.quantize(xb[:, :cols], rho, fmt)
+            assert np.array_equal(q.cpu().numpy(), want), t
             if transpose:
-                assert np.array_equal(c.qT.cpu().numpy(), want.T), t
-            prev_amax = scaling.amax(xb)
-            assert np.float32(c.amax.item()) == prev_amax
-            assert np.array_equal(c.history.cpu().numpy(), hist)
-        # after the small third pass the scale still comes from the large second one: the history remembers
-        assert hist.max() == hist[2]
+                assert np.array_equal(qT.cpu().numpy(), want.T), t
+            prev_next = scaling.amax(xb[:, :cols])
+        assert np.float32(s.item()).tobytes() == rho.tobytes(), t
+        assert np.float32(si.item()).tobytes() == rinv.tobytes(), t
+        assert np.float32(ap.item()) == prev
+        assert np.array_equal(hist_d.cpu().numpy(), ring)
+        prev = prev_next
+    # the abs-max of the gain-100 pass (t = 1) entered at t = 2 and was replaced at t = 5
+    assert ring.max() < 20.0
+
+
+def test_quantize_delayed_argument_errors():
+    lib = fog.load()
+    st = torch.cuda.current_stream().cuda_stream
+    x = torch.zeros((4, 64), dtype=torch.int16, device="cuda")
+    q = torch.zeros((4, 64), dtype=torch.uint8, device="cuda")
+    h = torch.zeros(8, device="cuda")
+    state = torch.zeros(fog.quantize_delayed_state(), dtype=torch.uint8, device="cuda")
+    f = fscalar(1.0)
+    ok = [x.data_ptr(), 4, 64, 64, 0, 0, h.data_ptr(), 8, 0, state.data_ptr(), state.numel(), q.data_ptr(), 64, None, 0, None, f.data_ptr(),
+          None, st]
+
+    def with_(i, v):
+        t = list(ok)
+        t[i] = v
+        return lib.fog_quantize_delayed(*t)
+    assert lib.fog_quantize_delayed(*ok) == 0
+    assert with_(6, None) == 1 and with_(9, None) == 1 and with_(16, None) == 1 and with_(0, None) == 1 and with_(11, None) == 1
+    assert with_(7, 0) == 2 and with_(8, -1) == 2 and with_(5, 100) == 2 and with_(3, 32) == 2
+    assert with_(9, state.data_ptr() + 1) == 3 and with_(0, x.data_ptr() + 1) == 3
+    assert with_(4, 2) == 4
+    assert with_(10, 100) == 5
+    assert lib.fog_delayed_amax(None, 0, f.data_ptr(), st) == 1 and lib.fog_delayed_amax(state.data_ptr(), -1, f.data_ptr(), st) == 2
+    torch.cuda.synchronize()
