@@ -249,7 +249,7 @@ def test_delayed_scaling_flows_of_the_block_driver():
 
 
 @pytest.mark.parametrize("rows,cols,pad,transpose", [(64, 256, 0, False), (256, 384, 0, True), (37, 100, 4, True), (1500, 4096, 0, False),
-                                                     (2048, 2048, 0, True)])
+                                                     (2048, 2048, 0, True), (2048, 8192, 0, False), (4096, 4608, 0, True)])
 def test_quantize_delayed_short_history_forgets(rows, cols, pad, transpose):
     """fog_quantize_delayed with a history of three entries over eight calls (one of them on an empty tensor): an old
     large abs-max leaves the ring after three further calls; row-major, transposing and element-wise kernels, grids
