@@ -26,8 +26,9 @@ FOG_DEVICE void acc_pair(uint32_t w, float& s2, float& s4, uint32_t& mx) {
   s4 = __builtin_fmaf(a2, a2, __builtin_fmaf(b2, b2, s4));
 }
 
-// VEC: rows are 16-byte aligned and cols % 8 == 0.
-template <bool VEC, bool AMAX>
+// VEC: rows are 16-byte aligned and cols % 8 == 0.  RB > 1 (VEC only): cols == 4096 / RB exactly, a batch of
+// eight loads per lane then covers RB whole rows, so that short rows keep as many loads in flight as long ones.
+template <bool VEC, bool AMAX, int RB>
 __global__ __launch_bounds__(kThreads) void kurtosis_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx,
                                                             float inv_rows, float* __restrict__ out, uint32_t* __restrict__ amax_out) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -46,13 +47,18 @@ __global__ __launch_bounds__(kThreads) void kurtosis_kernel(const uint16_t* __re
     // sequence with the next batch requested before the current one is summed, across row ends too.
     const int64_t nvec = cols >> 3;
     const int64_t nb = (nvec + 511) >> 9;
+    constexpr int LPR = 8 / RB;   // loads per lane and row when RB > 1
     auto fetch = [&](int64_t r, int64_t b, uint4 (&v)[8]) {
-      const uint16_t* row = x + r * ldx;
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        const int64_t i = (b << 9) + 64 * k + lane;
         v[k] = make_uint4(0u, 0u, 0u, 0u);   // zeros add nothing to the sums or the maximum
-        if (i < nvec) v[k] = ld_nt16(row + 8 * i);
+        if (RB == 1) {
+          const int64_t i = (b << 9) + 64 * k + lane;
+          if (i < nvec) v[k] = ld_nt16(x + r * ldx + 8 * i);
+        } else {
+          const int64_t row = r * RB + k / LPR;
+          if (row < rows) v[k] = ld_nt16(x + row * ldx + 8 * (64 * (k % LPR) + lane));
+        }
       }
     };
     float s2 = 0.0f, s4 = 0.0f;
@@ -60,25 +66,31 @@ __global__ __launch_bounds__(kThreads) void kurtosis_kernel(const uint16_t* __re
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
         acc_pair<AMAX>(v[k].x, s2, s4, mx); acc_pair<AMAX>(v[k].y, s2, s4, mx); acc_pair<AMAX>(v[k].z, s2, s4, mx); acc_pair<AMAX>(v[k].w, s2, s4, mx);
+        if (RB > 1 && k % LPR == LPR - 1) {   // a row of the batch is complete (rows past the end sum to 0 and add nothing)
+          close_row(s2, s4);
+          s2 = s4 = 0.0f;
+        }
       }
-      if (last) {
+      if (RB == 1 && last) {
         close_row(s2, s4);
         s2 = s4 = 0.0f;
       }
     };
+    // with RB > 1 "r" counts groups of RB rows and a group is one batch
+    const int64_t units = RB == 1 ? rows : (rows + RB - 1) / RB;
     int64_t r = (int64_t)blockIdx.x * 4 + w, b = 0;
     uint4 va[8], vb[8];
-    if (r < rows) fetch(r, b, va);
-    while (r < rows) {
+    if (r < units) fetch(r, b, va);
+    while (r < units) {
       // (r1, b1): what follows (r, b)
       int64_t r1 = r, b1 = b + 1;
       if (b1 == nb) { r1 = r + rstep; b1 = 0; }
-      if (r1 < rows) fetch(r1, b1, vb);
+      if (r1 < units) fetch(r1, b1, vb);
       consume(va, b + 1 == nb);
-      if (r1 >= rows) break;
+      if (r1 >= units) break;
       int64_t r2 = r1, b2 = b1 + 1;
       if (b2 == nb) { r2 = r1 + rstep; b2 = 0; }
-      if (r2 < rows) fetch(r2, b2, va);
+      if (r2 < units) fetch(r2, b2, va);
       consume(vb, b1 + 1 == nb);
       r = r2;
       b = b2;
@@ -131,13 +143,19 @@ extern "C" fog_status fog_kurtosis(const void* x_bf16, int64_t rows, int64_t col
   if (ldx < cols) return FOG_ERR_SHAPE;
   if (reinterpret_cast<uintptr_t>(x_bf16) & 1u) return FOG_ERR_ALIGN;
   const bool vec = (reinterpret_cast<uintptr_t>(x_bf16) & 15u) == 0 && cols % 8 == 0 && ldx % 8 == 0;
-  int64_t blocks = (rows + 3) / 4;
+  const int rb = !vec ? 1 : cols == 2048 ? 2 : cols == 1024 ? 4 : cols == 512 ? 8 : 1;
+  int64_t blocks = ((rows + rb - 1) / rb + 3) / 4;
   if (blocks > 1024) blocks = 1024;   // four workgroups per CU are resident
   const uint16_t* x = reinterpret_cast<const uint16_t*>(x_bf16);
   const float inv = 1.0f / (float)rows;
-#define FOG_KURT(V, A) kurtosis_kernel<V, A><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, inv, kurt, am)
-  if (vec) { if (am) FOG_KURT(true, true); else FOG_KURT(true, false); }
-  else     { if (am) FOG_KURT(false, true); else FOG_KURT(false, false); }
+#define FOG_KURT(V, A, RB) kurtosis_kernel<V, A, RB><<<(int)blocks, kThreads, 0, s>>>(x, rows, cols, ldx, inv, kurt, am)
+#define FOG_KURT_A(V, RB) do { if (am) FOG_KURT(V, true, RB); else FOG_KURT(V, false, RB); } while (0)
+  if (!vec)         FOG_KURT_A(false, 1);
+  else if (rb == 2) FOG_KURT_A(true, 2);
+  else if (rb == 4) FOG_KURT_A(true, 4);
+  else if (rb == 8) FOG_KURT_A(true, 8);
+  else              FOG_KURT_A(true, 1);
+#undef FOG_KURT_A
 #undef FOG_KURT
   return fog_launch_status();
 }

@@ -30,7 +30,8 @@ def gpu_kurt(xb, view_cols=None):
 
 
 @pytest.mark.parametrize("rows,cols,pad", [(1, 8, 0), (7, 64, 0), (33, 100, 0), (64, 4096, 0), (130, 2056, 8), (5, 17, 3), (4096, 2048, 0),
-                                           (5000, 14336, 0), (9, 4104, 0), (4100, 8200, 8)])
+                                           (5000, 14336, 0), (9, 4104, 0), (4100, 8200, 8),
+                                           (4099, 1024, 0), (33, 2048, 0), (5, 512, 0), (40001, 512, 0), (17000, 1024, 8)])
 def test_kurtosis_parity(rows, cols, pad):
     rng = np.random.default_rng(rows + cols)
     x = rng.standard_normal((rows, cols + pad)).astype(np.float32)
