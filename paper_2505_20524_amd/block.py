@@ -139,7 +139,6 @@ class AttentionStep:
         self.flops_fwd = 4 * a.S * a.S * a.D // 2 * a.B * a.H      # causal: blocks at or below the diagonal
         self.flops_bwd = self.flops_fwd * 5 // 2
         self.flops = self.flops_fwd + self.flops_bwd
-        self.calibrated = False
 
     def run(self, timer=None, delayed=False):
         a, c = self.attn, self.c

@@ -313,3 +313,21 @@ def test_quantize_delayed_argument_errors():
     assert with_(10, 100) == 5
     assert lib.fog_delayed_amax(None, 0, f.data_ptr(), st) == 1 and lib.fog_delayed_amax(state.data_ptr(), -1, f.data_ptr(), st) == 2
     torch.cuda.synchronize()
+
+
+def test_block_driver_jit_cast_equals_the_three_separate_calls():
+    """Cast.run (fog_quantize_jit, two launches) and Cast.run_separate (fog_amax, fog_scale, fog_quantize) give the
+    same bytes and scalars, bit for bit."""
+    from paper_2505_20524_amd import block
+    rng = np.random.default_rng(3)
+    xb = synth.f32_to_bf16_bits(rng.standard_normal((256, 384)).astype(np.float32) * 7)
+    for fmt, transpose in ((fp8.E4M3, True), (fp8.E5M2, False)):
+        a, b = block.Cast(dev(xb), fmt, transpose), block.Cast(dev(xb), fmt, transpose)
+        a.run()
+        b.run_separate()
+        torch.cuda.synchronize()
+        assert torch.equal(a.q, b.q) and (not transpose or torch.equal(a.qT, b.qT))
+        for u, v in ((a.amax, b.amax), (a.scale, b.scale), (a.sinv, b.sinv)):
+            assert np.float32(u.item()).tobytes() == np.float32(v.item()).tobytes()
+        rho, _ = scaling.compute_scale(scaling.amax(xb), fmt)
+        assert np.array_equal(a.q.cpu().numpy(), scaling.quantize(xb, rho, fmt))
