@@ -129,6 +129,33 @@ fog_status fog_quantize_jit(const void* x_bf16, int64_t rows, int64_t cols, int6
 size_t fog_quantize_jit_workspace(void);
 
 /*
+ * fog_quantize_jit for up to four tensors in two launches (one abs-max pass over all of them, one cast
+ * pass over all of them) instead of two per tensor: a launch costs a few microseconds of ramp and tail
+ * whatever it does, which is a fifth of either pass over a 100 MB tensor.  Results are those of
+ * fog_quantize_jit on each job, bit for bit.
+ *   jobs   : HOST array of `count` (0..4) descriptions; the device buffers they name follow the rules
+ *            of fog_quantize_jit, restricted to what the fast kernels cover: x_bf16 [rows, cols]
+ *            contiguous (leading dimension cols) and 16-byte aligned, rows * cols a positive multiple of
+ *            16, q contiguous and 16-byte aligned, no transposed copy.
+ *   workspace : fog_quantize_jit_batch_workspace(count) bytes (4 KB per job), 4-byte aligned; contents on
+ *            entry do not matter.
+ * Errors: NULL, SHAPE (count outside 0..4, non-positive sizes, margin), ALIGN, WORKSPACE, UNSUPPORTED
+ * (format; rows * cols not a multiple of 16: use fog_quantize_jit for that tensor).
+ */
+typedef struct {
+  const void* x_bf16;
+  int64_t rows, cols;
+  fog_fp8 fmt;
+  int margin;
+  uint8_t* q;
+  float* amax;
+  float* scale;
+  float* scale_inv;   /* may be NULL */
+} fog_cast_job;
+fog_status fog_quantize_jit_batch(const fog_cast_job* jobs, int count, void* workspace, size_t workspace_bytes, void* stream);
+size_t fog_quantize_jit_batch_workspace(int count);
+
+/*
  * Delayed scaling in ONE launch per cast (Appendix E: the scale of a cast comes from the maximum of
  * the last history_len abs-maxes of the same tensor; Section 2: one pass over the data, against two
  * for just-in-time scaling).  Call number `step` (0, 1, 2, ... for one tensor, no gaps):

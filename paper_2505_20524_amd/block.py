@@ -1,9 +1,10 @@
 """Host-side driver of one pass of the hot path over a transformer block's GEMMs and attention.
 
 For every linear layer Y = X W^T of the block: just-in-time per-tensor scaling (abs-max -> scale ->
-cast) of X, W (E4M3) and dY (E5M2), the casts of X and dY fused with the transpose the
-weight-gradient product wants, then the three FP8 GEMMs (forward, data gradient, weight gradient).
-For attention: casts of Q, K, V (E4M3) and dO (E5M2), FP8 attention forward and backward.
+cast) of X, W (E4M3) and dY (E5M2), the three tensors in one batched call (two launches), then the
+three FP8 GEMMs (forward, data gradient, weight gradient; the weight gradient reads the row-major
+casts, or transposed copies from the fused cast + transpose where a config asks for them).
+For attention: casts of Q, K, V (E4M3) and dO (E5M2) in one batched call, FP8 attention forward and backward.
 All arithmetic happens in the library's HIP kernels; this module only owns device buffers
 (torch tensors) and the order of calls.  The elementwise operators between the GEMMs
 (normalisation, activation, rotary embedding, residuals) are not part of the path: each GEMM
@@ -79,6 +80,32 @@ class Cast:
         fog.quantize(self.x, self.fmt, self.scale, q=self.q, qT=self.qT)
 
 
+class CastBatch:
+    """Just-in-time casts of several tensors in two launches (fog_quantize_jit_batch); tensors the batched call does
+    not cover (a transposed copy wanted, a size that is not a multiple of 16) are cast one by one after it."""
+
+    def __init__(self, casts):
+        self.batched = [c for c in casts if c.qT is None and c.x.numel() % 16 == 0 and c.x.numel() > 0][:4]
+        self.single = [c for c in casts if not any(c is b for b in self.batched)]
+        self.jobs = fog.make_cast_jobs([(c.x, c.fmt, c.q, c.amax, c.scale, c.sinv) for c in self.batched])
+        self.ws = torch.empty(max(fog.quantize_jit_batch_workspace(len(self.batched)), 16), dtype=torch.uint8, device="cuda")
+        self.bytes = sum(c.bytes_jit for c in self.batched)
+
+    def run(self, timer=None, delayed=False):
+        if delayed:
+            for c in self.batched + self.single:
+                c.run_delayed(timer)
+            return
+        if self.batched:
+            if timer:
+                timer.begin("cast_jit", self.bytes, launches=len(self.batched))
+            fog.quantize_jit_batch(self.jobs, self.ws)
+            if timer:
+                timer.end()
+        for c in self.single:
+            c.run(timer)
+
+
 class LinearStep:
     """Casts and the three GEMMs of one linear layer.
 
@@ -99,12 +126,12 @@ class LinearStep:
         self.dX = torch.empty((M, K), dtype=torch.int16, device="cuda")
         self.dW = torch.empty((N, K), dtype=torch.int16, device="cuda")
         self.flops = 3 * 2 * M * N * K
+        self.casts = CastBatch([self.X, self.W, self.dY])
 
     def run(self, timer=None, delayed=False):
         lin = self.lin
         M, N, K = lin.M, lin.N, lin.K
-        for c in (self.X, self.W, self.dY):
-            c.run_delayed(timer) if delayed else c.run(timer)
+        self.casts.run(timer, delayed)
         # The three products are launched back to back and bracketed by ONE event pair (an event between two
         # launches costs a gap of several microseconds on the stream): the pair's time is that of three launches.
         if timer:
@@ -129,6 +156,7 @@ class AttentionStep:
         self.s = softmax_scale if softmax_scale is not None else 1.0 / math.sqrt(a.D)
         self.c = {name: Cast(_dev_bits(tensors[name].reshape(n, a.D)), E5M2 if name == "dO" else E4M3, False)
                   for name in ("Q", "K", "V", "dO")}
+        self.casts = CastBatch([self.c[name] for name in ("Q", "K", "V", "dO")])
         self.O = torch.empty((n, a.D), dtype=torch.int16, device="cuda")
         self.lse = torch.empty(n, device="cuda")
         self.dQ, self.dK, self.dV = (torch.empty((n, a.D), dtype=torch.int16, device="cuda") for _ in range(3))
@@ -142,15 +170,13 @@ class AttentionStep:
 
     def run(self, timer=None, delayed=False):
         a, c = self.attn, self.c
-        for name in ("Q", "K", "V"):
-            c[name].run_delayed(timer) if delayed else c[name].run(timer)
+        self.casts.run(timer, delayed)
         if timer:
             timer.begin("attn_fwd", self.flops_fwd)
         fog.fp8_attn_fwd(a.B, a.H, a.S, a.D, self.s, True, c["Q"].q, c["K"].q, c["V"].q, c["Q"].sinv, c["K"].sinv,
                          c["V"].sinv, self.scale_p, self.O, self.lse)
         if timer:
             timer.end()
-        c["dO"].run_delayed(timer) if delayed else c["dO"].run(timer)
         if timer:
             timer.begin("attn_bwd", self.flops_bwd)
         # delayed-style scale for dS: the abs-max this call reports sets the scale of the next call

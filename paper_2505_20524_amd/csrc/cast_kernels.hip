@@ -23,24 +23,24 @@ __global__ void zero_u32_kernel(uint32_t* p) { *p = 0u; }
 // one-workgroup kernel then reduces the words and derives the scale.  This form reads with ordinary
 // (cache-retaining) loads, because the cast pass re-reads the tensor right away, back to front.
 FOG_DEVICE void scale_from_amax(float a, int fmt, int margin, float* scale, float* scale_inv);
-FOG_DEVICE void publish_block_max(uint32_t r, uint32_t* out, bool partials) {
+FOG_DEVICE void publish_block_max(uint32_t r, uint32_t* out, bool partials, int bid) {
   if (partials) {
-    out[blockIdx.x] = r << 16;
+    out[bid] = r << 16;
     return;
   }
   // same-address atomics are served one at a time: skip the ones that cannot raise the maximum
   if (r && (r << 16) > __hip_atomic_load(out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(out, r << 16);
 }
 
+// Workgroup `bid` of `nb` over one contiguous tensor (a whole launch, or one job's share of a batched launch).
 template <bool PARTIALS>
-__global__ __launch_bounds__(kThreads) void amax_kernel(const uint4* __restrict__ x, int64_t nvec,
-                                                        const uint16_t* __restrict__ tail, int ntail,
-                                                        uint32_t* __restrict__ out) {
+FOG_DEVICE void amax_span(const uint4* __restrict__ x, int64_t nvec, const uint16_t* __restrict__ tail, int ntail,
+                          uint32_t* __restrict__ out, int bid, int nb) {
   // Every workgroup owns one contiguous span and walks it in batches of eight 16-byte loads per
   // thread; the next batch is requested before the current one is reduced, so loads never stop.
   constexpr int NL = 8;
-  const int64_t per = (nvec + gridDim.x - 1) / gridDim.x;
-  const int64_t b0 = per * blockIdx.x, b1 = b0 + per < nvec ? b0 + per : nvec;
+  const int64_t per = (nvec + nb - 1) / nb;
+  const int64_t b0 = per * bid, b1 = b0 + per < nvec ? b0 + per : nvec;
   uint32_t m[4] = {0, 0, 0, 0};
   int64_t i = b0 + threadIdx.x;
   uint4 v[NL];
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kThreads) void amax_kernel(const uint4* __restrict_
   }
   uint32_t mm = pkmax_abs_bf16(pkmax_abs_bf16(m[0], m[1]), pkmax_abs_bf16(m[2], m[3]));
   uint32_t h = (mm >> 16) > (mm & 0xFFFFu) ? (mm >> 16) : (mm & 0xFFFFu);
-  if (blockIdx.x == 0 && (int)threadIdx.x < ntail) {
+  if (bid == 0 && (int)threadIdx.x < ntail) {
     uint32_t t = tail[threadIdx.x] & 0x7FFFu;
     h = h > t ? h : t;
   }
@@ -88,8 +88,15 @@ __global__ __launch_bounds__(kThreads) void amax_kernel(const uint4* __restrict_
     uint32_t r = part[0];
 #pragma unroll
     for (int w = 1; w < kThreads / 64; ++w) r = r > part[w] ? r : part[w];
-    publish_block_max(r, out, PARTIALS);
+    publish_block_max(r, out, PARTIALS, bid);
   }
+}
+
+template <bool PARTIALS>
+__global__ __launch_bounds__(kThreads) void amax_kernel(const uint4* __restrict__ x, int64_t nvec,
+                                                        const uint16_t* __restrict__ tail, int ntail,
+                                                        uint32_t* __restrict__ out) {
+  amax_span<PARTIALS>(x, nvec, tail, ntail, out, (int)blockIdx.x, (int)gridDim.x);
 }
 
 // Abs-max of a matrix whose rows are not contiguous or not 16-byte aligned (slow, same result).
@@ -111,7 +118,7 @@ __global__ __launch_bounds__(kThreads) void amax_strided_kernel(const uint16_t* 
     uint32_t r = part[0];
 #pragma unroll
     for (int w = 1; w < kThreads / 64; ++w) r = r > part[w] ? r : part[w];
-    publish_block_max(r, out, PARTIALS);
+    publish_block_max(r, out, PARTIALS, (int)blockIdx.x);
   }
 }
 
@@ -173,7 +180,7 @@ struct JitScale {
   uint32_t* next;         // delayed scaling only: cleared by workgroup 0
 };
 constexpr int kDelayedSlots = 1024;
-FOG_DEVICE float scale_from_partials(const JitScale& js) {
+FOG_DEVICE float scale_from_partials(const JitScale& js, bool publisher) {
   uint32_t m = 0;
   for (int i = threadIdx.x; i < js.n; i += kThreads) m = m > js.part[i] ? m : js.part[i];
   uint32_t h = 0;   // maximum of the history entries that stay
@@ -182,7 +189,7 @@ FOG_DEVICE float scale_from_partials(const JitScale& js) {
       const uint32_t v = i == js.slot ? 0u : __float_as_uint(js.hist[i]);   // abs-maxes: non-negative floats order like their bits
       h = h > v ? h : v;
     }
-    if (blockIdx.x == 0)
+    if (publisher)
       for (int i = threadIdx.x; i < kDelayedSlots; i += kThreads) js.next[i] = 0u;
   }
   m = wave_max_u32(m);
@@ -206,7 +213,7 @@ FOG_DEVICE float scale_from_partials(const JitScale& js) {
     float sc, si;
     scale_from_amax(basis, js.fmt, js.margin, &sc, &si);
     rho_shared = sc;
-    if (blockIdx.x == 0) {
+    if (publisher) {
       if (js.amax) *js.amax = a;
       if (js.hist) js.hist[js.slot] = a;
       *js.scale = sc;
@@ -218,7 +225,7 @@ FOG_DEVICE float scale_from_partials(const JitScale& js) {
 }
 
 // One workgroup of the above without a cast (empty tensors), and the maximum of one buffer of maxima.
-__global__ __launch_bounds__(kThreads) void delayed_scale_only_kernel(JitScale js) { scale_from_partials(js); }
+__global__ __launch_bounds__(kThreads) void delayed_scale_only_kernel(JitScale js) { scale_from_partials(js, true); }
 __global__ __launch_bounds__(kThreads) void partials_max_kernel(const uint32_t* __restrict__ part, int n, float* __restrict__ amax) {
   uint32_t m = 0;
   for (int i = threadIdx.x; i < n; i += kThreads) m = m > part[i] ? m : part[i];
@@ -272,14 +279,14 @@ FOG_DEVICE uint2 cast8(uint4 v, float rho) {
 
 // Each thread turns 16 bf16 (two 16-byte loads) into 16 FP8 codes (one 16-byte store), two such
 // chunks per trip so that four loads are in flight.
+// Workgroup `bid` of `nb` over one tensor (a whole launch, or one job's share of a batched launch).
 template <int FMT, bool AMAX>
-__global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t* __restrict__ x, int64_t rows,
-                                                                 int64_t chunks_per_row, int64_t ldx,
-                                                                 const float* __restrict__ scale, uint8_t* __restrict__ q,
-                                                                 int64_t ldq, uint32_t* __restrict__ amax_out, JitScale js) {
-  const float rho = js.part ? scale_from_partials(js) : *scale;
+FOG_DEVICE void quantize_rows_body(const uint16_t* __restrict__ x, int64_t rows, int64_t chunks_per_row, int64_t ldx,
+                                   const float* __restrict__ scale, uint8_t* __restrict__ q, int64_t ldq,
+                                   uint32_t* __restrict__ amax_out, const JitScale& js, int bid, int nb) {
+  const float rho = js.part ? scale_from_partials(js, bid == 0) : *scale;
   const int64_t total = rows * chunks_per_row;
-  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  const int64_t stride = (int64_t)nb * kThreads;
   uint32_t m = 0;
   // Chunks are visited back to front: under just-in-time scaling the abs-max pass ran front to back
   // just before, so the END of the tensor is what the caches still hold.
@@ -303,7 +310,7 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t*
     uint2 lo = cast8<FMT>(a, rho), hi = cast8<FMT>(b, rho);
     st_nt16(dst, make_uint4(lo.x, lo.y, hi.x, hi.y));
   };
-  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  int64_t i = (int64_t)bid * kThreads + threadIdx.x;
   for (; i + stride < total; i += 2 * stride) {
     const uint16_t* s0 = src_of(i);
     const uint16_t* s1 = src_of(i + stride);
@@ -325,9 +332,61 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t*
       uint32_t r = part[0];
 #pragma unroll
       for (int w = 1; w < kThreads / 64; ++w) r = r > part[w] ? r : part[w];
-      if (r) atomicMax(js.cur ? js.cur + (blockIdx.x & (kDelayedSlots - 1)) : amax_out, r << 16);
+      if (r) atomicMax(js.cur ? js.cur + (bid & (kDelayedSlots - 1)) : amax_out, r << 16);
     }
   }
+}
+
+template <int FMT, bool AMAX>
+__global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t* __restrict__ x, int64_t rows,
+                                                                 int64_t chunks_per_row, int64_t ldx,
+                                                                 const float* __restrict__ scale, uint8_t* __restrict__ q,
+                                                                 int64_t ldq, uint32_t* __restrict__ amax_out, JitScale js) {
+  quantize_rows_body<FMT, AMAX>(x, rows, chunks_per_row, ldx, scale, q, ldq, amax_out, js, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// ---------------------------------------------------------------- several tensors per launch (just-in-time scaling)
+// A launch costs about 4 us of ramp and tail whatever it does, a fifth of what the abs-max or the cast of a
+// 100 MB tensor takes; fog_quantize_jit_batch therefore runs the abs-max pass of up to four contiguous
+// tensors as ONE launch and their cast pass as another.  Workgroups are dealt to the jobs in proportion to
+// their sizes; inside its job a workgroup does exactly what it does in the one-tensor kernels.
+constexpr int kBatchMax = 4;
+struct BatchJobs {
+  int count;
+  int amax_first[kBatchMax + 1];   // first workgroup of each job in the abs-max launch (prefix sums)
+  int cast_first[kBatchMax + 1];   // ... and in the cast launch, where the jobs run in reverse order
+  const uint16_t* x[kBatchMax];
+  int64_t n[kBatchMax];            // elements, a multiple of 16
+  uint8_t* q[kBatchMax];
+  int fmt[kBatchMax], margin[kBatchMax];
+  float* amax[kBatchMax];
+  float* scale[kBatchMax];
+  float* scale_inv[kBatchMax];
+};
+constexpr int kJitSlots = 1024;    // workspace words per job = most workgroups a job gets in the abs-max launch
+
+__global__ __launch_bounds__(kThreads) void amax_batch_kernel(BatchJobs b, uint32_t* __restrict__ ws) {
+  int j = 0;
+#pragma unroll
+  for (int k = 1; k < kBatchMax; ++k)
+    if (k < b.count && (int)blockIdx.x >= b.amax_first[k]) j = k;
+  const int nb = b.amax_first[j + 1] - b.amax_first[j];
+  amax_span<true>(reinterpret_cast<const uint4*>(b.x[j]), b.n[j] / 8, nullptr, 0, ws + j * kJitSlots, (int)blockIdx.x - b.amax_first[j], nb);
+}
+
+__global__ __launch_bounds__(kThreads) void quantize_batch_kernel(BatchJobs b, const uint32_t* __restrict__ ws) {
+  // position p in the launch order is job count - 1 - p: the tensor whose abs-max pass ran last is cast first
+  int p = 0;
+#pragma unroll
+  for (int k = 1; k < kBatchMax; ++k)
+    if (k < b.count && (int)blockIdx.x >= b.cast_first[k]) p = k;
+  const int j = b.count - 1 - p;
+  const int bid = (int)blockIdx.x - b.cast_first[p], nb = b.cast_first[p + 1] - b.cast_first[p];
+  const JitScale js{ws + j * kJitSlots, b.amax_first[j + 1] - b.amax_first[j], b.fmt[j], b.margin[j], b.amax[j], b.scale[j], b.scale_inv[j],
+                    nullptr, 0, 0, nullptr, nullptr};
+  const int64_t chunks = b.n[j] / 16;
+  if (b.fmt[j] == FOG_E4M3) quantize_rows_body<FOG_E4M3, false>(b.x[j], 1, chunks, chunks * 16, nullptr, b.q[j], chunks * 16, nullptr, js, bid, nb);
+  else                      quantize_rows_body<FOG_E5M2, false>(b.x[j], 1, chunks, chunks * 16, nullptr, b.q[j], chunks * 16, nullptr, js, bid, nb);
 }
 
 // ---------------------------------------------------------------- cast fused with transpose
@@ -358,7 +417,7 @@ __global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const uint
                                                                       uint8_t* __restrict__ qT, int64_t ldqT,
                                                                       uint32_t* __restrict__ amax_out, int tiles_c, JitScale js) {
   __shared__ __attribute__((aligned(16))) uint8_t tile[kTile * kTile];  // [col][row], chunk-swizzled
-  const float rho = js.part ? scale_from_partials(js) : *scale;
+  const float rho = js.part ? scale_from_partials(js, blockIdx.x == 0) : *scale;
   const int bid = gridDim.x - 1 - blockIdx.x;   // tiles back to front (see quantize_rows_kernel)
   const int64_t r0 = (int64_t)(bid / tiles_c) * kTile;
   const int64_t c0 = (int64_t)(bid % tiles_c) * kTile;
@@ -427,7 +486,7 @@ __global__ __launch_bounds__(kThreads) void quantize_general_kernel(const uint16
                                                                     uint8_t* __restrict__ q, int64_t ldq,
                                                                     uint8_t* __restrict__ qT, int64_t ldqT,
                                                                     uint32_t* __restrict__ amax_out, JitScale js) {
-  const float rho = js.part ? scale_from_partials(js) : *scale;
+  const float rho = js.part ? scale_from_partials(js, blockIdx.x == 0) : *scale;
   const int64_t total = rows * cols;
   uint32_t m = 0;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
@@ -628,5 +687,59 @@ extern "C" fog_status fog_delayed_amax(const void* state, int64_t step, float* a
   if ((reinterpret_cast<uintptr_t>(state) & 3u) != 0) return FOG_ERR_ALIGN;
   const uint32_t* cur = reinterpret_cast<const uint32_t*>(state) + (step % 3) * kDelayedSlots;
   partials_max_kernel<<<1, kThreads, 0, (hipStream_t)stream>>>(cur, kDelayedSlots, amax);
+  return fog_launch_status();
+}
+
+extern "C" size_t fog_quantize_jit_batch_workspace(int count) {
+  return count > 0 ? (size_t)count * kJitSlots * sizeof(uint32_t) : 0;
+}
+
+extern "C" fog_status fog_quantize_jit_batch(const fog_cast_job* jobs, int count, void* workspace, size_t workspace_bytes,
+                                             void* stream) {
+  if (count == 0) return FOG_OK;
+  if (!jobs || !workspace) return FOG_ERR_NULL;
+  if (count < 0 || count > kBatchMax) return FOG_ERR_SHAPE;
+  if (workspace_bytes < fog_quantize_jit_batch_workspace(count)) return FOG_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 3u) != 0) return FOG_ERR_ALIGN;
+  BatchJobs b;
+  b.count = count;
+  b.amax_first[0] = 0;
+  for (int j = 0; j < count; ++j) {
+    const fog_cast_job& t = jobs[j];
+    if (!t.x_bf16 || !t.q || !t.amax || !t.scale) return FOG_ERR_NULL;
+    if (t.rows <= 0 || t.cols <= 0 || t.margin < -64 || t.margin > 64) return FOG_ERR_SHAPE;
+    if (t.fmt != FOG_E4M3 && t.fmt != FOG_E5M2) return FOG_ERR_UNSUPPORTED;
+    if (!aligned16(t.x_bf16) || !aligned16(t.q)) return FOG_ERR_ALIGN;
+    const int64_t n = t.rows * t.cols;
+    if (n % 16 != 0) return FOG_ERR_UNSUPPORTED;
+    int64_t ab = (n / 8 + kThreads * 8 - 1) / (kThreads * 8);
+    if (ab > kJitSlots) ab = kJitSlots;
+    b.amax_first[j + 1] = b.amax_first[j] + (int)ab;
+    b.x[j] = reinterpret_cast<const uint16_t*>(t.x_bf16);
+    b.n[j] = n;
+    b.q[j] = t.q;
+    b.fmt[j] = (int)t.fmt;
+    b.margin[j] = t.margin;
+    b.amax[j] = t.amax;
+    b.scale[j] = t.scale;
+    b.scale_inv[j] = t.scale_inv;
+  }
+  b.cast_first[0] = 0;
+  for (int p = 0; p < count; ++p) {   // launch position p casts job count - 1 - p
+    const int64_t chunks = b.n[count - 1 - p] / 16;
+    int64_t cb = (chunks + 2 * kThreads - 1) / (2 * kThreads);
+    if (cb > 2048) cb = 2048;
+    b.cast_first[p + 1] = b.cast_first[p] + (int)cb;
+  }
+  for (int j = count; j < kBatchMax; ++j) {
+    b.amax_first[j + 1] = b.amax_first[count];
+    b.cast_first[j + 1] = b.cast_first[count];
+    b.x[j] = nullptr; b.n[j] = 0; b.q[j] = nullptr; b.fmt[j] = 0; b.margin[j] = 0;
+    b.amax[j] = b.scale[j] = b.scale_inv[j] = nullptr;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  uint32_t* ws = reinterpret_cast<uint32_t*>(workspace);
+  amax_batch_kernel<<<b.amax_first[count], kThreads, 0, s>>>(b, ws);
+  quantize_batch_kernel<<<b.cast_first[count], kThreads, 0, s>>>(b, ws);
   return fog_launch_status();
 }

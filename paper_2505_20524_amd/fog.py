@@ -28,6 +28,8 @@ SIGNATURES = {
     "fog_quantize": (_I, [_P, _I64, _I64, _I64, _I, _P, _P, _I64, _P, _I64, _P, _P]),
     "fog_quantize_jit": (_I, [_P, _I64, _I64, _I64, _I, _I, _P, _I64, _P, _I64, _P, _P, _P, _P, _SZ, _P]),
     "fog_quantize_jit_workspace": (_SZ, []),
+    "fog_quantize_jit_batch": (_I, [_P, _I, _P, _SZ, _P]),
+    "fog_quantize_jit_batch_workspace": (_SZ, [_I]),
     "fog_quantize_delayed": (_I, [_P, _I64, _I64, _I64, _I, _I, _P, _I, _I64, _P, _SZ, _P, _I64, _P, _I64, _P, _P, _P, _P]),
     "fog_quantize_delayed_state": (_SZ, []),
     "fog_delayed_amax": (_I, [_P, _I64, _P, _P]),
@@ -116,6 +118,32 @@ def quantize_jit(x, fmt, amax_out, scale_out, scale_inv_out, workspace, q=None, 
 
 def quantize_jit_workspace():
     return load().fog_quantize_jit_workspace()
+
+
+class CastJob(ctypes.Structure):
+    """Mirror of fog_cast_job."""
+    _fields_ = [("x_bf16", _P), ("rows", _I64), ("cols", _I64), ("fmt", _I), ("margin", _I), ("q", _P), ("amax", _P),
+                ("scale", _P), ("scale_inv", _P)]
+
+
+def make_cast_jobs(items, margin=0):
+    """items: (x, fmt, q, amax, scale, scale_inv) tuples of contiguous tensors -> ctypes array for quantize_jit_batch."""
+    arr = (CastJob * len(items))()
+    for job, (x, fmt, q, amax_t, scale_t, sinv_t) in zip(arr, items):
+        rows, cols = x.shape
+        job.x_bf16, job.rows, job.cols, job.fmt, job.margin = _ptr(x), rows, cols, fmt, margin
+        job.q, job.amax, job.scale, job.scale_inv = _ptr(q), _ptr(amax_t), _ptr(scale_t), _ptr(sinv_t)
+    return arr
+
+
+def quantize_jit_batch(jobs, workspace, stream=None):
+    """jobs: the array make_cast_jobs returns (it can be built once and reused while the tensors stay in place)."""
+    _check(load().fog_quantize_jit_batch(ctypes.cast(jobs, _P), len(jobs), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream)), "fog_quantize_jit_batch")
+
+
+def quantize_jit_batch_workspace(count):
+    return load().fog_quantize_jit_batch_workspace(count)
 
 
 def quantize_delayed(x, fmt, history, step, state, scale_out, scale_inv_out=None, q=None, qT=None, amax_prev=None, margin=0,

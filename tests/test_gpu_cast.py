@@ -331,3 +331,60 @@ def test_block_driver_jit_cast_equals_the_three_separate_calls():
             assert np.float32(u.item()).tobytes() == np.float32(v.item()).tobytes()
         rho, _ = scaling.compute_scale(scaling.amax(xb), fmt)
         assert np.array_equal(a.q.cpu().numpy(), scaling.quantize(xb, rho, fmt))
+
+
+@pytest.mark.parametrize("shapes", [[(1, 16)], [(64, 256), (8, 48)], [(300, 1024), (2, 8), (128, 4096)],
+                                    [(2048, 4096), (96, 160), (5000, 1024), (1, 16)], [(4100, 8192), (333, 1008)]])
+def test_quantize_jit_batch_equals_the_single_tensor_call(shapes):
+    """fog_quantize_jit_batch (two launches for up to four tensors) against fog_quantize_jit per tensor and against the
+    oracle: bytes, abs-max, scale and reciprocal scale bit for bit; mixed formats, sizes from 16 elements to more than
+    the largest grids take in one trip."""
+    rng = np.random.default_rng(len(shapes) * 100 + shapes[0][0])
+    items, refs = [], []
+    for k, (rows, cols) in enumerate(shapes):
+        fmt = fp8.E4M3 if k % 2 == 0 else fp8.E5M2
+        xb = synth.f32_to_bf16_bits(rng.standard_normal((rows, cols)).astype(np.float32) * (10.0 ** (k - 1)))
+        x = dev(xb)
+        q = torch.full((rows, cols), 0xAA, dtype=torch.uint8, device="cuda")
+        am, sc, si = (torch.full((1,), -1.0, device="cuda") for _ in range(3))
+        items.append((x, fmt, q, am, sc, si))
+        refs.append((xb, fmt))
+    ws = torch.full((fog.quantize_jit_batch_workspace(len(items)) // 4,), 0x7F7FFFFF, dtype=torch.int32, device="cuda")   # garbage on entry
+    fog.quantize_jit_batch(fog.make_cast_jobs(items, margin=1), ws)
+    torch.cuda.synchronize()
+    one_ws = torch.empty(fog.quantize_jit_workspace(), dtype=torch.uint8, device="cuda")
+    for (x, fmt, q, am, sc, si), (xb, _) in zip(items, refs):
+        a = scaling.amax(xb)
+        rho, rinv = scaling.compute_scale(a, fmt, margin=1)
+        assert np.float32(am.item()) == a
+        assert np.float32(sc.item()).tobytes() == rho.tobytes() and np.float32(si.item()).tobytes() == rinv.tobytes()
+        assert np.array_equal(q.cpu().numpy(), scaling.quantize(xb, rho, fmt))
+        q1 = torch.empty_like(q)
+        am1, sc1, si1 = (torch.zeros(1, device="cuda") for _ in range(3))
+        fog.quantize_jit(x, fmt, am1, sc1, si1, one_ws, q=q1, margin=1)
+        torch.cuda.synchronize()
+        assert torch.equal(q, q1) and am1.item() == am.item() and sc1.item() == sc.item() and si1.item() == si.item()
+
+
+def test_quantize_jit_batch_argument_errors():
+    lib = fog.load()
+    st = torch.cuda.current_stream().cuda_stream
+    x = torch.zeros((4, 64), dtype=torch.int16, device="cuda")
+    q = torch.zeros((4, 64), dtype=torch.uint8, device="cuda")
+    f = [torch.zeros(1, device="cuda") for _ in range(3)]
+    ws = torch.zeros(4 * 4096, dtype=torch.uint8, device="cuda")
+
+    def call(items, count=None, wsp=ws.data_ptr(), wsb=ws.numel(), **over):
+        jobs = fog.make_cast_jobs(items)
+        for k, v in over.items():
+            setattr(jobs[0], k, v)
+        import ctypes
+        return lib.fog_quantize_jit_batch(ctypes.cast(jobs, ctypes.c_void_p), len(items) if count is None else count, wsp, wsb, st)
+    good = (x, fp8.E4M3, q, f[0], f[1], f[2])
+    assert call([good]) == 0 and call([good], scale_inv=None) == 0 and call([], count=0) == 0
+    assert call([good], wsp=None) == 1 and call([good], x_bf16=None) == 1 and call([good], q=None) == 1 and call([good], amax=None) == 1
+    assert call([good] * 4, count=5) == 2 and call([good], rows=0) == 2 and call([good], margin=100) == 2
+    assert call([good], x_bf16=x.data_ptr() + 2) == 3 and call([good], wsp=ws.data_ptr() + 1) == 3
+    assert call([good], fmt=2) == 4 and call([good], cols=63) == 4
+    assert call([good, good], wsb=4096) == 5
+    torch.cuda.synchronize()
