@@ -168,7 +168,7 @@ __global__ __launch_bounds__(kThreads) void scale_partials_kernel(const uint32_t
 // the scale comes from the history's maximum, and this pass's own maxima go to `cur`, 1024 words that
 // the previous pass cleared; workgroup 0 clears `next` for the pass after this one.  Three buffers in
 // rotation: no word is read and written by different workgroups of one launch.
-struct JitScale {
+struct ScaleSource {
   const uint32_t* part;   // NULL: the scale is read from memory instead
   int n, fmt, margin;
   float* amax;
@@ -180,7 +180,7 @@ struct JitScale {
   uint32_t* next;         // delayed scaling only: cleared by workgroup 0
 };
 constexpr int kDelayedSlots = 1024;
-FOG_DEVICE float scale_from_partials(const JitScale& js, bool publisher) {
+FOG_DEVICE float scale_from_partials(const ScaleSource& js, bool publisher) {
   uint32_t m = 0;
   for (int i = threadIdx.x; i < js.n; i += kThreads) m = m > js.part[i] ? m : js.part[i];
   uint32_t h = 0;   // maximum of the history entries that stay
@@ -225,7 +225,7 @@ FOG_DEVICE float scale_from_partials(const JitScale& js, bool publisher) {
 }
 
 // One workgroup of the above without a cast (empty tensors), and the maximum of one buffer of maxima.
-__global__ __launch_bounds__(kThreads) void delayed_scale_only_kernel(JitScale js) { scale_from_partials(js, true); }
+__global__ __launch_bounds__(kThreads) void delayed_scale_only_kernel(ScaleSource js) { scale_from_partials(js, true); }
 __global__ __launch_bounds__(kThreads) void partials_max_kernel(const uint32_t* __restrict__ part, int n, float* __restrict__ amax) {
   uint32_t m = 0;
   for (int i = threadIdx.x; i < n; i += kThreads) m = m > part[i] ? m : part[i];
@@ -283,7 +283,7 @@ FOG_DEVICE uint2 cast8(uint4 v, float rho) {
 template <int FMT, bool AMAX>
 FOG_DEVICE void quantize_rows_body(const uint16_t* __restrict__ x, int64_t rows, int64_t chunks_per_row, int64_t ldx,
                                    const float* __restrict__ scale, uint8_t* __restrict__ q, int64_t ldq,
-                                   uint32_t* __restrict__ amax_out, const JitScale& js, int bid, int nb) {
+                                   uint32_t* __restrict__ amax_out, const ScaleSource& js, int bid, int nb) {
   const float rho = js.part ? scale_from_partials(js, bid == 0) : *scale;
   const int64_t total = rows * chunks_per_row;
   const int64_t stride = (int64_t)nb * kThreads;
@@ -341,7 +341,7 @@ template <int FMT, bool AMAX>
 __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t* __restrict__ x, int64_t rows,
                                                                  int64_t chunks_per_row, int64_t ldx,
                                                                  const float* __restrict__ scale, uint8_t* __restrict__ q,
-                                                                 int64_t ldq, uint32_t* __restrict__ amax_out, JitScale js) {
+                                                                 int64_t ldq, uint32_t* __restrict__ amax_out, ScaleSource js) {
   quantize_rows_body<FMT, AMAX>(x, rows, chunks_per_row, ldx, scale, q, ldq, amax_out, js, (int)blockIdx.x, (int)gridDim.x);
 }
 
@@ -382,7 +382,7 @@ __global__ __launch_bounds__(kThreads) void quantize_batch_kernel(BatchJobs b, c
     if (k < b.count && (int)blockIdx.x >= b.cast_first[k]) p = k;
   const int j = b.count - 1 - p;
   const int bid = (int)blockIdx.x - b.cast_first[p], nb = b.cast_first[p + 1] - b.cast_first[p];
-  const JitScale js{ws + j * kJitSlots, b.amax_first[j + 1] - b.amax_first[j], b.fmt[j], b.margin[j], b.amax[j], b.scale[j], b.scale_inv[j],
+  const ScaleSource js{ws + j * kJitSlots, b.amax_first[j + 1] - b.amax_first[j], b.fmt[j], b.margin[j], b.amax[j], b.scale[j], b.scale_inv[j],
                     nullptr, 0, 0, nullptr, nullptr};
   const int64_t chunks = b.n[j] / 16;
   if (b.fmt[j] == FOG_E4M3) quantize_rows_body<FOG_E4M3, false>(b.x[j], 1, chunks, chunks * 16, nullptr, b.q[j], chunks * 16, nullptr, js, bid, nb);
@@ -415,7 +415,7 @@ __global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const uint
                                                                       const float* __restrict__ scale,
                                                                       uint8_t* __restrict__ q, int64_t ldq,
                                                                       uint8_t* __restrict__ qT, int64_t ldqT,
-                                                                      uint32_t* __restrict__ amax_out, int tiles_c, JitScale js) {
+                                                                      uint32_t* __restrict__ amax_out, int tiles_c, ScaleSource js) {
   __shared__ __attribute__((aligned(16))) uint8_t tile[kTile * kTile];  // [col][row], chunk-swizzled
   const float rho = js.part ? scale_from_partials(js, blockIdx.x == 0) : *scale;
   const int bid = gridDim.x - 1 - blockIdx.x;   // tiles back to front (see quantize_rows_kernel)
@@ -485,7 +485,7 @@ __global__ __launch_bounds__(kThreads) void quantize_general_kernel(const uint16
                                                                     int64_t ldx, const float* __restrict__ scale,
                                                                     uint8_t* __restrict__ q, int64_t ldq,
                                                                     uint8_t* __restrict__ qT, int64_t ldqT,
-                                                                    uint32_t* __restrict__ amax_out, JitScale js) {
+                                                                    uint32_t* __restrict__ amax_out, ScaleSource js) {
   const float rho = js.part ? scale_from_partials(js, blockIdx.x == 0) : *scale;
   const int64_t total = rows * cols;
   uint32_t m = 0;
@@ -548,7 +548,7 @@ extern "C" fog_status fog_scale_delayed(float* history, int len, const float* ne
 
 template <int FMT>
 static void launch_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ldx, const float* scale, uint8_t* q,
-                            int64_t ldq, uint8_t* qT, int64_t ldqT, uint32_t* amax_out, hipStream_t s, JitScale js = JitScale{}) {
+                            int64_t ldq, uint8_t* qT, int64_t ldqT, uint32_t* amax_out, hipStream_t s, ScaleSource js = ScaleSource{}) {
   const bool base_ok = cols % 16 == 0 && ldx % 16 == 0 && aligned16(x) && (!q || (ldq % 16 == 0 && aligned16(q)));
   if (!qT && base_ok) {
     int64_t r = rows, cpr = cols / 16, lx = ldx, lq = ldq;
@@ -646,7 +646,7 @@ extern "C" fog_status fog_quantize_jit(const void* x_bf16, int64_t rows, int64_t
     scale_partials_kernel<<<1, kThreads, 0, s>>>(ws, 0, (int)fmt, margin, amax, scale, scale_inv);
     return fog_launch_status();
   }
-  const JitScale js{ws, (int)blocks, (int)fmt, margin, amax, scale, scale_inv, nullptr, 0, 0, nullptr, nullptr};
+  const ScaleSource js{ws, (int)blocks, (int)fmt, margin, amax, scale, scale_inv, nullptr, 0, 0, nullptr, nullptr};
   if (fmt == FOG_E4M3) launch_quantize<FOG_E4M3>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, nullptr, s, js);
   else                 launch_quantize<FOG_E5M2>(x, rows, cols, ldx, scale, q, ldq, qT, ldqT, nullptr, s, js);
   return fog_launch_status();
@@ -669,7 +669,7 @@ extern "C" fog_status fog_quantize_delayed(const void* x_bf16, int64_t rows, int
   uint32_t* prev = base + ((step + 2) % 3) * kDelayedSlots;
   uint32_t* cur = base + (step % 3) * kDelayedSlots;
   uint32_t* next = base + ((step + 1) % 3) * kDelayedSlots;
-  const JitScale js{prev, kDelayedSlots, (int)fmt, margin, amax_prev, scale, scale_inv,
+  const ScaleSource js{prev, kDelayedSlots, (int)fmt, margin, amax_prev, scale, scale_inv,
                     history, history_len, (int)(step % history_len), cur, next};
   if (rows == 0 || cols == 0) {   // nothing to cast: the history still advances, this pass's abs-max stays 0
     delayed_scale_only_kernel<<<1, kThreads, 0, s>>>(js);
