@@ -33,37 +33,106 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_GEMM_TRAFFIC_BYTES = {5: 7.940e8}
 
 
-def cpu_baseline(cfg):
-    """The oracle, as it stands, on a bounded sample: output rows of the first linear's forward GEMM."""
-    import numpy as np
-    from oracle import fp8, gemm, scaling
-    from paper_2505_20524_amd import synth
-    lin = cfg.linears[0] if cfg.linears else None
-    if lin is None:
-        return None
-    t = synth.linear_tensors(cfg, 0, want=("X", "W"))
-    q = {}
-    for name in ("X", "W"):
-        rho, rinv = scaling.compute_scale(scaling.amax(t[name]), fp8.E4M3)
-        q[name] = (scaling.quantize(t[name], rho, fp8.E4M3), rinv)
-    rows = np.arange(0, lin.M, max(1, lin.M // 256))[:256]
-    t0 = time.perf_counter()
-    reps = 0
-    while True:
-        gemm.fp8_gemm_rows(gemm.NT, q["X"][0], fp8.E4M3, q["X"][1], q["W"][0], fp8.E4M3, q["W"][1], rows)
-        reps += 1
-        dt = time.perf_counter() - t0
-        if dt > 10.0 or reps >= 50:
-            break
-    flops = 2.0 * len(rows) * lin.N * lin.K * reps
+def _host_threads():
+    """(threads the BLAS behind numpy uses, cores this process may run on)."""
+    affinity = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
     try:
         from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        blas = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
-        cores = os.cpu_count()
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": "%d of %d output rows of the %s forward GEMM (N=%d, K=%d), decode + float64 matmul, %d repeats, %.1f s"
-                      % (len(rows), lin.M, lin.name, lin.N, lin.K, reps, dt)}
+        blas = affinity
+    return min(blas, affinity), affinity
+
+
+def cpu_baseline(cfg):
+    """The oracle, as it stands, timed on bounded samples of the same workload, one per kernel class:
+    output rows of the first linear layer's forward GEMM (the headline figure, in the metric's unit), the
+    abs-max and the cast of a slice of that layer's activations, and one (batch, head) pair of attention
+    forward and backward.  About 20-30 s of CPU work in all."""
+    import numpy as np
+    from oracle import attention, bf16, fp8, gemm, scaling
+    from paper_2505_20524_amd import synth
+    blas_threads, affinity = _host_threads()
+    classes = {}
+    out = None
+    if cfg.linears:
+        lin = cfg.linears[0]
+        t = synth.linear_tensors(cfg, 0, want=("X", "W"))
+        # casts: a slice of X (the oracle's cast is element-wise numpy, one thread)
+        rows = max(1, min(lin.M, (1 << 22) // lin.K))
+        xs = t["X"][:rows]
+        t0 = time.perf_counter()
+        reps = 0
+        while True:
+            a = scaling.amax(xs)
+            reps += 1
+            dt_a = time.perf_counter() - t0
+            if dt_a > 1.0 or reps >= 50:
+                break
+        classes["amax"] = {"value": 2.0 * xs.size * reps / dt_a / 1e9, "unit": "GB/s", "cores": 1,
+                           "sample": "%d of %d rows of %s X, %d repeats, %.2f s" % (rows, lin.M, lin.name, reps, dt_a)}
+        rho, _ = scaling.compute_scale(a, fp8.E4M3)
+        t0 = time.perf_counter()
+        reps = 0
+        while True:
+            scaling.quantize(xs, rho, fp8.E4M3)
+            reps += 1
+            dt_q = time.perf_counter() - t0
+            if dt_q > 3.0 or reps >= 20:
+                break
+        classes["cast"] = {"value": 3.0 * xs.size * reps / dt_q / 1e9, "unit": "GB/s", "cores": 1,
+                           "sample": "%d of %d rows of %s X (2 B read + 1 B written per element), %d repeats, %.2f s"
+                                     % (rows, lin.M, lin.name, reps, dt_q)}
+        q = {}
+        for name in ("X", "W"):
+            rho, rinv = scaling.compute_scale(scaling.amax(t[name]), fp8.E4M3)
+            # whole operands, cast on row chunks (bounds the oracle's temporaries)
+            step = max(1, (1 << 22) // t[name].shape[1])
+            q[name] = (np.concatenate([scaling.quantize(t[name][r:r + step], rho, fp8.E4M3) for r in range(0, t[name].shape[0], step)]), rinv)
+        rows = np.arange(0, lin.M, max(1, lin.M // 256))[:256]
+        t0 = time.perf_counter()
+        reps = 0
+        while True:
+            gemm.fp8_gemm_rows(gemm.NT, q["X"][0], fp8.E4M3, q["X"][1], q["W"][0], fp8.E4M3, q["W"][1], rows)
+            reps += 1
+            dt = time.perf_counter() - t0
+            if dt > 10.0 or reps >= 50:
+                break
+        flops = 2.0 * len(rows) * lin.N * lin.K * reps
+        classes["gemm"] = {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": blas_threads,
+                           "sample": "%d of %d output rows of the %s forward GEMM (N=%d, K=%d), decode + float64 matmul, %d repeats, %.1f s"
+                                     % (len(rows), lin.M, lin.name, lin.N, lin.K, reps, dt)}
+        out = dict(classes["gemm"])
+    if cfg.attn is not None:
+        a = cfg.attn
+        rng = np.random.default_rng(0)
+        S = min(a.S, 4096)
+        # one head of synthetic codes of the config's sequence length (the oracle's cost does not depend on the values)
+        codes = lambda: rng.integers(0, 0x78, size=(S, a.D)).astype(np.uint8) | (rng.integers(0, 2, size=(S, a.D)).astype(np.uint8) << 7)
+        Q8, K8, V8, dO8 = codes(), codes(), codes(), codes()
+        sq = np.float32(1.0 / 64)
+        s = 1.0 / math.sqrt(a.D)
+        t0 = time.perf_counter()
+        O, lse, _ = attention.attn_fwd_head(Q8, K8, V8, sq, sq, sq, s, 448.0, True)
+        dt_f = time.perf_counter() - t0
+        fl = 4.0 * S * S * a.D / 2
+        classes["attn_fwd"] = {"value": fl / dt_f / 1e12, "unit": "TFLOP/s", "cores": blas_threads,
+                               "sample": "one (batch, head) pair, S=%d, D=%d, causal, %.2f s (FLOPs counted on the causal half)" % (S, a.D, dt_f)}
+        O_bits = bf16.f64_to_bits_rne(O)
+        dO_bits = bf16.f64_to_bits_rne(fp8.decode(dO8, fp8.E5M2) * 1e-4)
+        t0 = time.perf_counter()
+        attention.attn_bwd_head(Q8, K8, V8, sq, sq, sq, O_bits, dO_bits, dO8, np.float32(1e-4), lse.astype(np.float32), s, 448.0, 1024.0, True)
+        dt_b = time.perf_counter() - t0
+        classes["attn_bwd"] = {"value": 2.5 * fl / dt_b / 1e12, "unit": "TFLOP/s", "cores": blas_threads,
+                               "sample": "the same pair, backward, %.2f s" % dt_b}
+        if out is None:
+            out = dict(classes["attn_fwd"])
+    if out is None:
+        return None
+    out["kind"] = "oracle"
+    out["affinity_cores"] = affinity
+    out["classes"] = classes
+    return out
 
 
 def main():

@@ -24,7 +24,10 @@
  *   - Errors are returned as fog_status; nothing is thrown and nothing aborts.
  *     Argument errors are detected on the host before anything is launched, so a
  *     failing call has no effect on device memory.
- *   - Inputs must be finite.  FP8 codes are OCP E4M3 / E5M2 bytes.
+ *   - FP8 codes are OCP E4M3 / E5M2 bytes.  The casts (fog_quantize and its variants, the fused
+ *     producers) give a NaN input the NaN code 0x7F with the input's sign and saturate infinities; the
+ *     abs-max of a tensor that holds a NaN is NaN (and its scale therefore 1).  The GEMM and attention
+ *     entry points expect finite operands.
  */
 #ifndef FOG_H_
 #define FOG_H_
@@ -300,7 +303,8 @@ fog_status fog_kurtosis(const void* x_bf16, int64_t rows, int64_t cols, int64_t 
  *   scale_inv_A / _B : one float each (the reciprocal scales of the casts).
  *   C_bf16 : [M, N] bfloat16, leading dimension ldc.
  *   workspace : unused by the current kernels (fog_fp8_gemm_workspace returns 0); may be NULL.
- * Requirements: A, B 16-byte aligned, lda, ldb multiples of 16; C 4-byte aligned, ldc even;
+ * Requirements: A, B 16-byte aligned, lda, ldb multiples of 16; C 2-byte aligned, any ldc >= N (a
+ * 16-byte aligned C with ldc a multiple of 8 takes 16-byte stores, anything else element-wise ones);
  * the contiguous dimension of each operand a multiple of 16 (K for row-major-in-K operands,
  * M or N for the K-major operands of NN / TN).  M, N, K otherwise arbitrary; M == 0 or N == 0
  * is a no-op and K == 0 writes zeros.

@@ -508,21 +508,22 @@ extern "C" size_t fog_fp8_attn_workspace(int B, int H, int H_kv, int S, int D, i
   return (size_t)3 * B * H * S * sizeof(float);
 }
 
-extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int H_kv, int S, int D, float softmax_scale, int causal,
-                                       const uint8_t* Q, const uint8_t* K, const uint8_t* V,
-                                       const float* sinv_q, const float* sinv_k, const float* sinv_v,
-                                       const void* O_bf16, const void* dO_bf16, const uint8_t* dO_e5m2, const float* sinv_do,
-                                       const float* lse, const float* scale_p, const float* scale_ds,
-                                       void* dQ_bf16, void* dK_bf16, void* dV_bf16, float* amax_ds,
-                                       void* workspace, size_t workspace_bytes, void* stream) {
+// Argument checks shared by the two entry points (everything but the workspace); FOG_OK with *empty set
+// means there is nothing to compute.
+static fog_status bwd_checks(int B, int H, int H_kv, int S, int D, float softmax_scale,
+                             const uint8_t* Q, const uint8_t* K, const uint8_t* V,
+                             const float* sinv_q, const float* sinv_k, const float* sinv_v,
+                             const void* O_bf16, const void* dO_bf16, const uint8_t* dO_e5m2, const float* sinv_do,
+                             const float* lse, const float* scale_p, const float* scale_ds,
+                             void* dQ_bf16, void* dK_bf16, void* dV_bf16, bool* empty) {
+  *empty = false;
   if (B < 0 || H < 0 || H_kv < 0 || S < 0 || D < 0) return FOG_ERR_SHAPE;
   if ((H > 0) != (H_kv > 0) || (H_kv > 0 && H % H_kv != 0)) return FOG_ERR_SHAPE;
   if (!(softmax_scale > 0.0f)) return FOG_ERR_UNSUPPORTED;
   if (D != HD || S % STEP != 0) return FOG_ERR_UNSUPPORTED;
-  hipStream_t s = (hipStream_t)stream;
   if (B == 0 || H == 0 || S == 0) {
-    if (amax_ds) zero_u32b<<<1, 1, 0, s>>>(reinterpret_cast<uint32_t*>(amax_ds));
-    return fog_launch_status();
+    *empty = true;
+    return FOG_OK;
   }
   if (!Q || !K || !V || !sinv_q || !sinv_k || !sinv_v || !O_bf16 || !dO_bf16 || !dO_e5m2 || !sinv_do || !lse || !scale_p ||
       !scale_ds || !dQ_bf16 || !dK_bf16 || !dV_bf16)
@@ -530,17 +531,25 @@ extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int H_kv, int S, int D, flo
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O_bf16) || !aligned16(dO_bf16) || !aligned16(dO_e5m2) ||
       !aligned16(dQ_bf16) || !aligned16(dK_bf16) || !aligned16(dV_bf16))
     return FOG_ERR_ALIGN;
-  if (!workspace || workspace_bytes < fog_fp8_attn_workspace(B, H, H_kv, S, D, 1) || (reinterpret_cast<uintptr_t>(workspace) & 3u))
-    return FOG_ERR_WORKSPACE;
   if ((int64_t)(H / H_kv) * S * HD >= 0x7FFFFFFF) return FOG_ERR_UNSUPPORTED;   // a group of query heads is one 32-bit addressed buffer
   if ((int64_t)B * H > 0x7FFFFF || (int64_t)B * H * ((S + BLK - 1) / BLK) > 0x7FFFFFF0) return FOG_ERR_UNSUPPORTED;
+  return FOG_OK;
+}
+
+// The launches of the backward, on checked arguments; `ws` holds three floats per row.
+static fog_status bwd_launch(int B, int H, int H_kv, int S, float softmax_scale, int causal,
+                             const uint8_t* Q, const uint8_t* K, const uint8_t* V,
+                             const float* sinv_q, const float* sinv_k, const float* sinv_v,
+                             const void* O_bf16, const void* dO_bf16, const uint8_t* dO_e5m2, const float* sinv_do,
+                             const float* lse, const float* scale_p, const float* scale_ds,
+                             void* dQ_bf16, void* dK_bf16, void* dV_bf16, float* amax_ds, float* ws, hipStream_t s) {
   BwdArgs a;
   a.Q = Q; a.K = K; a.V = V; a.dO8 = dO_e5m2;
   a.O = reinterpret_cast<const uint16_t*>(O_bf16); a.dO = reinterpret_cast<const uint16_t*>(dO_bf16);
   a.sinv_q = sinv_q; a.sinv_k = sinv_k; a.sinv_v = sinv_v; a.sinv_do = sinv_do;
   a.lse = lse; a.scale_p = scale_p; a.scale_ds = scale_ds;
   a.dQ = reinterpret_cast<uint16_t*>(dQ_bf16); a.dK = reinterpret_cast<uint16_t*>(dK_bf16); a.dV = reinterpret_cast<uint16_t*>(dV_bf16);
-  a.amax_ds = reinterpret_cast<uint32_t*>(amax_ds); a.Dws = reinterpret_cast<float*>(workspace);
+  a.amax_ds = reinterpret_cast<uint32_t*>(amax_ds); a.Dws = ws;
   a.softmax_scale = softmax_scale;
   a.BH = B * H; a.S = S; a.nblk = (S + BLK - 1) / BLK;
   a.BHkv = B * H_kv; a.G = H / H_kv;
@@ -569,4 +578,26 @@ extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int H_kv, int S, int D, flo
   if (causal) { if (amax_ds) attn_bwd_dq_kernel<true, true><<<grid, kThreads, 0, s>>>(a); else attn_bwd_dq_kernel<true, false><<<grid, kThreads, 0, s>>>(a); }
   else        { if (amax_ds) attn_bwd_dq_kernel<false, true><<<grid, kThreads, 0, s>>>(a); else attn_bwd_dq_kernel<false, false><<<grid, kThreads, 0, s>>>(a); }
   return fog_launch_status();
+}
+
+extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int H_kv, int S, int D, float softmax_scale, int causal,
+                                       const uint8_t* Q, const uint8_t* K, const uint8_t* V,
+                                       const float* sinv_q, const float* sinv_k, const float* sinv_v,
+                                       const void* O_bf16, const void* dO_bf16, const uint8_t* dO_e5m2, const float* sinv_do,
+                                       const float* lse, const float* scale_p, const float* scale_ds,
+                                       void* dQ_bf16, void* dK_bf16, void* dV_bf16, float* amax_ds,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+  bool empty;
+  const fog_status st = bwd_checks(B, H, H_kv, S, D, softmax_scale, Q, K, V, sinv_q, sinv_k, sinv_v, O_bf16, dO_bf16, dO_e5m2,
+                                   sinv_do, lse, scale_p, scale_ds, dQ_bf16, dK_bf16, dV_bf16, &empty);
+  if (st != FOG_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  if (empty) {
+    if (amax_ds) zero_u32b<<<1, 1, 0, s>>>(reinterpret_cast<uint32_t*>(amax_ds));
+    return fog_launch_status();
+  }
+  if (!workspace || workspace_bytes < fog_fp8_attn_workspace(B, H, H_kv, S, D, 1) || (reinterpret_cast<uintptr_t>(workspace) & 3u))
+    return FOG_ERR_WORKSPACE;
+  return bwd_launch(B, H, H_kv, S, softmax_scale, causal, Q, K, V, sinv_q, sinv_k, sinv_v, O_bf16, dO_bf16, dO_e5m2, sinv_do, lse,
+                    scale_p, scale_ds, dQ_bf16, dK_bf16, dV_bf16, amax_ds, reinterpret_cast<float*>(workspace), s);
 }

@@ -306,12 +306,16 @@ extern "C" fog_status fog_fp8_attn_fwd(int B, int H, int H_kv, int S, int D, flo
   if (!(softmax_scale > 0.0f)) return FOG_ERR_UNSUPPORTED;
   if (D != HD || S % BKV != 0) return FOG_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
+  const bool empty = B == 0 || H == 0 || S == 0;
+  // every argument check comes before the first launch: a failing call leaves device memory untouched
+  if (!empty) {
+    if (!Q || !K || !V || !sinv_q || !sinv_k || !sinv_v || !scale_p || !O_bf16 || !lse) return FOG_ERR_NULL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O_bf16)) return FOG_ERR_ALIGN;
+    if ((int64_t)S * HD >= 0x7FFFFFFF) return FOG_ERR_UNSUPPORTED;
+    if ((int64_t)B * H > 0x7FFFFF || (int64_t)B * H * ((S + BQ - 1) / BQ) > 0x7FFFFFF0) return FOG_ERR_UNSUPPORTED;
+  }
   if (amax_p) zero_u32<<<1, 1, 0, s>>>(reinterpret_cast<uint32_t*>(amax_p));
-  if (B == 0 || H == 0 || S == 0) return fog_launch_status();
-  if (!Q || !K || !V || !sinv_q || !sinv_k || !sinv_v || !scale_p || !O_bf16 || !lse) return FOG_ERR_NULL;
-  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O_bf16)) return FOG_ERR_ALIGN;
-  if ((int64_t)S * HD >= 0x7FFFFFFF) return FOG_ERR_UNSUPPORTED;
-  if ((int64_t)B * H > 0x7FFFFF || (int64_t)B * H * ((S + BQ - 1) / BQ) > 0x7FFFFFF0) return FOG_ERR_UNSUPPORTED;
+  if (empty) return fog_launch_status();
   FwdArgs a;
   a.Q = Q; a.K = K; a.V = V;
   a.sinv_q = sinv_q; a.sinv_k = sinv_k; a.sinv_v = sinv_v; a.scale_p = scale_p;

@@ -272,8 +272,8 @@ __global__ __launch_bounds__(kThreads) void scale_delayed_kernel(float* hist, in
 template <int FMT>
 FOG_DEVICE uint2 cast8(uint4 v, float rho) {
   uint2 o;
-  o.x = cvt4_fp8<FMT>(bf16lo(v.x) * rho, bf16hi(v.x) * rho, bf16lo(v.y) * rho, bf16hi(v.y) * rho);
-  o.y = cvt4_fp8<FMT>(bf16lo(v.z) * rho, bf16hi(v.z) * rho, bf16lo(v.w) * rho, bf16hi(v.w) * rho);
+  o.x = cvt4_fp8_nan<FMT>(bf16lo(v.x) * rho, bf16hi(v.x) * rho, bf16lo(v.y) * rho, bf16hi(v.y) * rho);
+  o.y = cvt4_fp8_nan<FMT>(bf16lo(v.z) * rho, bf16hi(v.z) * rho, bf16lo(v.w) * rho, bf16hi(v.w) * rho);
   return o;
 }
 
@@ -495,7 +495,7 @@ __global__ __launch_bounds__(kThreads) void quantize_general_kernel(const uint16
     uint32_t a = w & 0x7FFFu;
     m = m > a ? m : a;
     float t = bf16lo(w) * rho;
-    uint8_t code = (uint8_t)(cvt4_fp8<FMT>(t, t, t, t) & 0xFFu);
+    uint8_t code = (uint8_t)(cvt4_fp8_nan<FMT>(t, t, t, t) & 0xFFu);
     if (q) q[r * ldq + c] = code;
     if (qT) qT[c * ldqT + r] = code;
   }

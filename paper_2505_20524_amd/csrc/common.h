@@ -47,6 +47,28 @@ FOG_DEVICE uint32_t cvt4_fp8(float a, float b, float c, float d) {
   return r;
 }
 
+// The same cast for tensors that may hold NaN (the bulk casts): the clamp above returns the smallest of
+// its operands for a NaN input, i.e. the largest finite code with a minus sign, so NaN inputs are patched
+// afterwards to the NaN code 0x7F with the input's sign.  Infinities saturate through the clamp.  The test
+// costs two unordered compares per four values; the patch runs only in waves that hold a NaN.
+template <int FMT>
+FOG_DEVICE uint32_t cvt4_fp8_nan(float a, float b, float c, float d, bool* saw_nan = nullptr) {
+  uint32_t r = cvt4_fp8<FMT>(a, b, c, d);
+  if (__builtin_expect(__builtin_isunordered(a, b) || __builtin_isunordered(c, d), 0)) {
+    if (saw_nan) *saw_nan = true;
+    if (a != a) r = (r & 0xFFFFFF00u) | 0x0000007Fu | ((__float_as_uint(a) >> 24) & 0x00000080u);
+    if (b != b) r = (r & 0xFFFF00FFu) | 0x00007F00u | ((__float_as_uint(b) >> 16) & 0x00008000u);
+    if (c != c) r = (r & 0xFF00FFFFu) | 0x007F0000u | ((__float_as_uint(c) >> 8) & 0x00800000u);
+    if (d != d) r = (r & 0x00FFFFFFu) | 0x7F000000u | (__float_as_uint(d) & 0x80000000u);
+  }
+  return r;
+}
+
+// Bit pattern of a thread's running abs-max (a non-negative float, kept with fmaxf, which drops NaN
+// operands) for the integer reductions that follow: a thread that saw a NaN contributes the NaN pattern,
+// which orders above every finite value and infinity, so a diverged tensor shows in the abs-max.
+FOG_DEVICE uint32_t amax_bits(float m, bool saw_nan) { return saw_nan ? 0x7FC00000u : __float_as_uint(m); }
+
 // Wave-wide (64 lanes) reductions through cross-lane shuffles.
 FOG_DEVICE uint32_t wave_max_u32(uint32_t v) {
 #pragma unroll

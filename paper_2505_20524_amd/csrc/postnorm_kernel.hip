@@ -83,8 +83,8 @@ __global__ __launch_bounds__(kThreads) void postnorm_rows_kernel(const uint16_t*
         st_nt16(out + r * ldo + col, o);
         if (q) {
           uint2 c8;
-          c8.x = cvt4_fp8<FMT>(bf16lo(o.x) * rho, bf16hi(o.x) * rho, bf16lo(o.y) * rho, bf16hi(o.y) * rho);
-          c8.y = cvt4_fp8<FMT>(bf16lo(o.z) * rho, bf16hi(o.z) * rho, bf16lo(o.w) * rho, bf16hi(o.w) * rho);
+          c8.x = cvt4_fp8_nan<FMT>(bf16lo(o.x) * rho, bf16hi(o.x) * rho, bf16lo(o.y) * rho, bf16hi(o.y) * rho);
+          c8.y = cvt4_fp8_nan<FMT>(bf16lo(o.z) * rho, bf16hi(o.z) * rho, bf16lo(o.w) * rho, bf16hi(o.w) * rho);
           st_nt8(q + r * ldq + col, c8);
         }
       }
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kThreads) void postnorm_general_kernel(const uint16
       m = m > mag ? m : mag;
       if (q) {
         const float t = bf16lo(b) * rho;
-        q[r * ldq + i] = (uint8_t)(cvt4_fp8<FMT>(t, t, t, t) & 0xFFu);
+        q[r * ldq + i] = (uint8_t)(cvt4_fp8_nan<FMT>(t, t, t, t) & 0xFFu);
       }
     }
   }

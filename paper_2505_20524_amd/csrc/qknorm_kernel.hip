@@ -19,16 +19,17 @@ FOG_DEVICE float inv_rms(float sumsq, float cols, float gain) {
   return sumsq > 0.0f ? gain / __builtin_sqrtf(sumsq / cols) : 0.0f;
 }
 
-FOG_DEVICE void block_amax(float m, uint32_t* amax_out) {
-  m = wave_max_f32(m);
-  __shared__ float part[kThreads / 64];
-  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+// Workgroup maximum raised into *amax_out; reduced on bit patterns (non-negative floats order like them,
+// and the NaN pattern of a thread that saw a NaN orders above everything).
+FOG_DEVICE void block_amax(float m, bool nan, uint32_t* amax_out) {
+  const uint32_t h = wave_max_u32(amax_bits(m, nan));
+  __shared__ uint32_t part[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = h;
   __syncthreads();
   if (threadIdx.x == 0) {
-    float r = part[0];
+    uint32_t b = part[0];
 #pragma unroll
-    for (int w = 1; w < kThreads / 64; ++w) r = fmaxf(r, part[w]);
-    const uint32_t b = __float_as_uint(r);   // non-negative floats order like their bit patterns
+    for (int w = 1; w < kThreads / 64; ++w) b = b > part[w] ? b : part[w];
     if (b > __hip_atomic_load(amax_out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(amax_out, b);
   }
 }
@@ -43,6 +44,7 @@ __global__ __launch_bounds__(kThreads) void qknorm_rows_kernel(const uint16_t* _
   const float rho = *scale;
   const int sub = threadIdx.x % LPR, rloc = threadIdx.x / LPR;
   float m = 0.0f;
+  bool nan = false;
   auto fetch = [&](int64_t r0, uint4 (&v)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -70,8 +72,8 @@ __global__ __launch_bounds__(kThreads) void qknorm_rows_kernel(const uint16_t* _
       }
       if (r < rows) {
         uint2 o;
-        o.x = cvt4_fp8<FMT>(y[0] * rho, y[1] * rho, y[2] * rho, y[3] * rho);
-        o.y = cvt4_fp8<FMT>(y[4] * rho, y[5] * rho, y[6] * rho, y[7] * rho);
+        o.x = cvt4_fp8_nan<FMT>(y[0] * rho, y[1] * rho, y[2] * rho, y[3] * rho, &nan);
+        o.y = cvt4_fp8_nan<FMT>(y[4] * rho, y[5] * rho, y[6] * rho, y[7] * rho, &nan);
         st_nt8(q + r * ldq + 8 * sub, o);
       }
     }
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(kThreads) void qknorm_rows_kernel(const uint16_t* _
     process(r1, vb);
     r0 = r2;
   }
-  if (amax_out) block_amax(m, amax_out);
+  if (amax_out) block_amax(m, nan, amax_out);
 }
 
 // Any row length: one wave per row, two passes over the row (the second is served from cache).
@@ -102,6 +104,7 @@ __global__ __launch_bounds__(kThreads) void qknorm_general_kernel(const uint16_t
   const float rho = *scale;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   float m = 0.0f;
+  bool nan = false;
   for (int64_t r = (int64_t)blockIdx.x * 4 + w; r < rows; r += (int64_t)gridDim.x * 4) {
     const uint16_t* row = x + r * ldx;
     float s = 0.0f;
@@ -115,10 +118,10 @@ __global__ __launch_bounds__(kThreads) void qknorm_general_kernel(const uint16_t
       const float y = bf16lo(row[i]) * inv;
       m = fmaxf(m, fabsf(y));
       const float t = y * rho;
-      q[r * ldq + i] = (uint8_t)(cvt4_fp8<FMT>(t, t, t, t) & 0xFFu);
+      q[r * ldq + i] = (uint8_t)(cvt4_fp8_nan<FMT>(t, t, t, t, &nan) & 0xFFu);
     }
   }
-  if (amax_out) block_amax(m, amax_out);
+  if (amax_out) block_amax(m, nan, amax_out);
 }
 
 template <int FMT>

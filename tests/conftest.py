@@ -27,3 +27,15 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Figures of the attention parity checks (see tests/parity.py), one line per checked tensor."""
+    try:
+        import parity
+    except Exception:
+        return
+    if parity.STATS:
+        terminalreporter.section("attention parity statistics")
+        for line in parity.STATS:
+            terminalreporter.write_line(line)

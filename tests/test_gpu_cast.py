@@ -388,3 +388,66 @@ def test_quantize_jit_batch_argument_errors():
     assert call([good], fmt=2) == 4 and call([good], cols=63) == 4
     assert call([good, good], wsb=4096) == 5
     torch.cuda.synchronize()
+
+
+def _with_non_finite(rows, cols, seed):
+    """bf16 bits of a normal matrix with NaN (both signs, a payload) and infinities planted at edge and interior places."""
+    rng = np.random.default_rng(seed)
+    xb = synth.f32_to_bf16_bits(rng.standard_normal((rows, cols)).astype(np.float32) * 5)
+    flat = xb.reshape(-1)
+    n = flat.size
+    spots = {0: 0x7FC0, n - 1: 0xFFC0, n // 2: 0x7F80, n // 3: 0xFF80, min(n - 1, 17): 0x7FA5, min(n - 1, 16 * 9 + 3): 0xFFFF}
+    for pos, bits in spots.items():
+        flat[pos] = bits
+    return xb
+
+
+@pytest.mark.parametrize("fmt", [fp8.E4M3, fp8.E5M2])
+@pytest.mark.parametrize("rows,cols,tr", [(64, 256, False), (256, 384, True), (33, 17, True), (1, 16, False), (1500, 1024, False)])
+def test_non_finite_inputs_keep_their_meaning(fmt, rows, cols, tr):
+    """NaN inputs become the format's NaN code with the input's sign and infinities saturate, exactly as the
+    oracle's cast defines them, on every cast path (rows, fused transpose, general, and the batched call);
+    the abs-max of such a tensor is not finite, so its scale is 1 by the scale rule."""
+    xb = _with_non_finite(rows, cols, rows + cols)
+    xd = dev(xb)
+    for rho in (1.0, 37.5):
+        want = scaling.quantize(xb, np.float32(rho), fmt)
+        assert (want == 0x7F).any() and (want == 0xFF).any()          # the oracle did produce NaN codes of both signs
+        q = torch.full((rows, cols), 0x55, dtype=torch.uint8, device="cuda")
+        qT = torch.full((cols, rows), 0x55, dtype=torch.uint8, device="cuda") if tr else None
+        am = torch.full((1,), -1.0, device="cuda")
+        fog.quantize(xd, fmt, fscalar(rho), q=q, qT=qT, amax_out=am)
+        assert np.array_equal(q.cpu().numpy(), want), rho
+        if tr:
+            assert np.array_equal(qT.cpu().numpy(), want.T)
+        assert np.isnan(am.item()) and np.isnan(scaling.amax(xb))
+    assert np.isnan(gpu_amax(xb))
+    # the one-call just-in-time cast: abs-max NaN -> scale 1 (the rule for a non-finite abs-max)
+    am, sc, si = (torch.full((1,), -1.0, device="cuda") for _ in range(3))
+    ws = torch.empty(fog.quantize_jit_workspace(), dtype=torch.uint8, device="cuda")
+    q = torch.full((rows, cols), 0x55, dtype=torch.uint8, device="cuda")
+    fog.quantize_jit(xd, fmt, am, sc, si, ws, q=q)
+    rho, rinv = scaling.compute_scale(scaling.amax(xb), fmt)
+    assert rho == 1.0 and np.float32(sc.item()) == rho and np.float32(si.item()) == rinv
+    assert np.array_equal(q.cpu().numpy(), scaling.quantize(xb, rho, fmt))
+    if (rows * cols) % 16 == 0:
+        q2 = torch.full((rows, cols), 0x55, dtype=torch.uint8, device="cuda")
+        jobs = fog.make_cast_jobs([(xd, fmt, q2, am, sc, si)])
+        wsb = torch.empty(fog.quantize_jit_batch_workspace(1), dtype=torch.uint8, device="cuda")
+        fog.quantize_jit_batch(jobs, wsb)
+        assert np.array_equal(q2.cpu().numpy(), scaling.quantize(xb, rho, fmt))
+        assert np.float32(sc.item()) == 1.0
+
+
+def test_only_infinities_saturate_and_give_scale_one():
+    xb = synth.f32_to_bf16_bits(np.linspace(-3, 3, 64 * 32, dtype=np.float32).reshape(64, 32))
+    xb[5, 7] = 0x7F80
+    xb[60, 0] = 0xFF80
+    for fmt in (fp8.E4M3, fp8.E5M2):
+        q = torch.zeros((64, 32), dtype=torch.uint8, device="cuda")
+        fog.quantize(dev(xb), fmt, fscalar(2.0), q=q)
+        got = q.cpu().numpy()
+        assert np.array_equal(got, scaling.quantize(xb, np.float32(2.0), fmt))
+        top = 0x7E if fmt == fp8.E4M3 else 0x7B
+        assert got[5, 7] == top and got[60, 0] == (top | 0x80)
+    assert gpu_amax(xb) == np.float32(np.inf)

@@ -107,3 +107,22 @@ def test_tails_small_magnitudes_and_errors():
     assert t(None, 0, 64, 64, 1.0, 0, f.data_ptr(), None, 64, f.data_ptr(), st) == 0
     torch.cuda.synchronize()
     assert f.item() == 0.0
+
+
+@pytest.mark.parametrize("kind", ["gelu", "tanh"])
+def test_nan_inputs_reach_the_codes_and_the_abs_max(kind):
+    """A NaN activation input gives the NaN code (not the largest finite code the clamp alone would produce;
+    the sign of a NaN that went through arithmetic is not defined) and a NaN abs-max, so a diverged tensor
+    stays visible to the scaling history."""
+    rng = np.random.default_rng(3)
+    for rows, cols in ((64, 256), (7, 17)):                      # the vector path and the element-wise path
+        xb = synth.f32_to_bf16_bits(rng.standard_normal((rows, cols)).astype(np.float32))
+        xb[0, 0] = 0x7FC0
+        xb[rows - 1, cols - 1] = 0xFFC0
+        xb[rows // 2, 5] = 0x7FA1
+        for fmt in (fp8.E4M3, fp8.E5M2):
+            got, am = run(kind, xb, cols, fmt, 100.0, 0.7, 0)
+            nan_codes = (got & 0x7F) == 0x7F
+            assert nan_codes[0, 0] and nan_codes[rows - 1, cols - 1] and nan_codes[rows // 2, 5]
+            assert nan_codes.sum() == 3
+            assert np.isnan(am)
