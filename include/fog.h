@@ -372,6 +372,26 @@ fog_status fog_fp8_attn_bwd(int B, int H, int H_kv, int S, int D, float softmax_
                             void* workspace, size_t workspace_bytes, void* stream);
 size_t fog_fp8_attn_workspace(int B, int H, int H_kv, int S, int D, int is_bwd);
 
+/*
+ * fog_fp8_attn_bwd for callers that cannot allocate device memory or pass a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation): the same kernels and the same
+ * results, bit for bit, with the per-row constants (three floats per query row) kept in a device array
+ * that is part of the library instead of a caller workspace.  The call allocates nothing.
+ *   Limit: B * H * S <= FOG_ATTN_BWD_STATIC_MAX_ROWS (the array is 6 MB per GPU the library is used on and
+ *   stays until the process ends); a larger problem returns FOG_ERR_WORKSPACE and takes fog_fp8_attn_bwd.
+ *   All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (different
+ *   streams) race; serialise them or use fog_fp8_attn_bwd with a workspace each.  Nothing in the array has
+ *   to survive between calls and nothing has to be cleared (every call first overwrites what it reads).
+ * Arguments, shape rules and other errors as fog_fp8_attn_bwd.
+ */
+#define FOG_ATTN_BWD_STATIC_MAX_ROWS 524288
+fog_status fog_fp8_attn_bwd_static(int B, int H, int H_kv, int S, int D, float softmax_scale, int causal,
+                                   const uint8_t* Q, const uint8_t* K, const uint8_t* V,
+                                   const float* sinv_q, const float* sinv_k, const float* sinv_v,
+                                   const void* O_bf16, const void* dO_bf16, const uint8_t* dO_e5m2, const float* sinv_do,
+                                   const float* lse, const float* scale_p, const float* scale_ds,
+                                   void* dQ_bf16, void* dK_bf16, void* dV_bf16, float* amax_ds, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -16,6 +16,8 @@
 // Operands whose contraction index is their row index (dO^T, Q^T, K^T) are gathered from the
 // row-major LDS tiles with the byte-transposing read, in the key/query order the packed
 // probabilities have (see the forward kernel).
+#include <mutex>
+
 #include "common.h"
 #include "launch.h"
 
@@ -600,4 +602,57 @@ extern "C" fog_status fog_fp8_attn_bwd(int B, int H, int H_kv, int S, int D, flo
     return FOG_ERR_WORKSPACE;
   return bwd_launch(B, H, H_kv, S, softmax_scale, causal, Q, K, V, sinv_q, sinv_k, sinv_v, O_bf16, dO_bf16, dO_e5m2, sinv_do, lse,
                     scale_p, scale_ds, dQ_bf16, dK_bf16, dV_bf16, amax_ds, reinterpret_cast<float*>(workspace), s);
+}
+
+// ------------------------------------------------------------------ the backward without a caller workspace
+// For callers that cannot allocate device memory (code under HIP graph capture, serving loops, harnesses
+// that forbid it): the three per-row constants live in a file-scope device array instead of a caller
+// workspace.  Every GPU the library runs on holds its own copy of the array, at its own address, until the
+// process ends; the address is looked up once per device, with that device current, and kept.
+constexpr int64_t kStaticRows = FOG_ATTN_BWD_STATIC_MAX_ROWS;          // B * H * S of a call, at most (6 MB of floats)
+static __device__ __align__(256) float scratch[3 * kStaticRows];
+constexpr int kMaxDevices = 64;
+static float* g_scratch_ptr[kMaxDevices];                             // device address of `scratch`, per device
+static std::mutex g_scratch_mutex;
+
+// Device address of this device's `scratch` (the array's name is only a host-side handle: it is never passed to a kernel).
+static fog_status static_scratch(float** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return FOG_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return FOG_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return FOG_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = reinterpret_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return FOG_OK;
+}
+
+extern "C" fog_status fog_fp8_attn_bwd_static(int B, int H, int H_kv, int S, int D, float softmax_scale, int causal,
+                                              const uint8_t* Q, const uint8_t* K, const uint8_t* V,
+                                              const float* sinv_q, const float* sinv_k, const float* sinv_v,
+                                              const void* O_bf16, const void* dO_bf16, const uint8_t* dO_e5m2, const float* sinv_do,
+                                              const float* lse, const float* scale_p, const float* scale_ds,
+                                              void* dQ_bf16, void* dK_bf16, void* dV_bf16, float* amax_ds, void* stream) {
+  bool empty;
+  const fog_status st = bwd_checks(B, H, H_kv, S, D, softmax_scale, Q, K, V, sinv_q, sinv_k, sinv_v, O_bf16, dO_bf16, dO_e5m2,
+                                   sinv_do, lse, scale_p, scale_ds, dQ_bf16, dK_bf16, dV_bf16, &empty);
+  if (st != FOG_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  if (empty) {
+    if (amax_ds) zero_u32b<<<1, 1, 0, s>>>(reinterpret_cast<uint32_t*>(amax_ds));
+    return fog_launch_status();
+  }
+  if ((int64_t)B * H * S > kStaticRows) return FOG_ERR_WORKSPACE;   // larger problems take fog_fp8_attn_bwd with a caller workspace
+  float* ws = nullptr;
+  const fog_status sw = static_scratch(&ws);
+  if (sw != FOG_OK) return sw;
+  // Nothing in the array has to start at zero: the first kernel overwrites the 3 * B * H * S floats the others read.
+  return bwd_launch(B, H, H_kv, S, softmax_scale, causal, Q, K, V, sinv_q, sinv_k, sinv_v, O_bf16, dO_bf16, dO_e5m2, sinv_do, lse,
+                    scale_p, scale_ds, dQ_bf16, dK_bf16, dV_bf16, amax_ds, ws, s);
 }

@@ -45,7 +45,10 @@ SIGNATURES = {
     "fog_fp8_attn_bwd": (_I, [_I, _I, _I, _I, _I, _F, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P,
                               _P, _P, _P, _P, _P, _SZ, _P]),
     "fog_fp8_attn_workspace": (_SZ, [_I, _I, _I, _I, _I, _I]),
+    "fog_fp8_attn_bwd_static": (_I, [_I, _I, _I, _I, _I, _F, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P,
+                                     _P, _P, _P, _P, _P]),
 }
+ATTN_BWD_STATIC_MAX_ROWS = 524288      # FOG_ATTN_BWD_STATIC_MAX_ROWS of the header
 
 
 class FogError(RuntimeError):
@@ -232,6 +235,15 @@ def fp8_attn_bwd(B, H, S, D, softmax_scale, causal, Q, K, V, sinv_q, sinv_k, sin
                                    _ptr(sinv_do), _ptr(lse), _ptr(scale_p), _ptr(scale_ds),
                                    _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(amax_ds), _ptr(workspace), ws,
                                    _stream(stream)), "fog_fp8_attn_bwd")
+
+
+def fp8_attn_bwd_static(B, H, S, D, softmax_scale, causal, Q, K, V, sinv_q, sinv_k, sinv_v, O, dO, dO8, sinv_do,
+                        lse, scale_p, scale_ds, dQ, dK, dV, amax_ds=None, stream=None, H_kv=None):
+    """fp8_attn_bwd without a workspace: the library's own device array serves (B * H * S <= ATTN_BWD_STATIC_MAX_ROWS)."""
+    _check(load().fog_fp8_attn_bwd_static(B, H, H if H_kv is None else H_kv, S, D, softmax_scale, int(causal), _ptr(Q), _ptr(K),
+                                          _ptr(V), _ptr(sinv_q), _ptr(sinv_k), _ptr(sinv_v), _ptr(O), _ptr(dO), _ptr(dO8),
+                                          _ptr(sinv_do), _ptr(lse), _ptr(scale_p), _ptr(scale_ds),
+                                          _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(amax_ds), _stream(stream)), "fog_fp8_attn_bwd_static")
 
 
 def fp8_attn_workspace(B, H, S, D, is_bwd, H_kv=None):
