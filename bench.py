@@ -141,6 +141,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5)
+    ap.add_argument("--cast-batching", choices=["layer", "weights", "step"], default="layer",
+                    help="how the just-in-time casts are grouped into batched calls (see block.Block)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--vendor-context", action="store_true",
                     help="also time the vendor library's FP8 GEMM (torch._scaled_mm) on the forward shapes: context only, "
@@ -160,7 +162,7 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
-    blk = block.Block(cfg)
+    blk = block.Block(cfg, cast_batching=args.cast_batching)
     torch.cuda.synchronize()
 
     if args.calibrate_copy:
@@ -321,7 +323,8 @@ def main():
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8_e4m3_e5m2", "data": "synthetic",
-        "config": {"workload": "config %d: %s" % (cfg.cid, cfg.label), "gflop_per_step": blk.flops / 1e9},
+        "config": {"workload": "config %d: %s" % (cfg.cid, cfg.label), "gflop_per_step": blk.flops / 1e9,
+                   "cast_batching": args.cast_batching},
         "frac_of_fp8_peak": value / PEAK_FP8_TFLOPS,
         "roofline": roofline, "kernels": kernels,
         "delayed_scaling": {"ms_per_step": delayed_ms, "value": blk.flops / (delayed_ms * 1e-3) / 1e12, "unit": "TFLOP/s",

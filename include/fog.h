@@ -132,19 +132,20 @@ fog_status fog_quantize_jit(const void* x_bf16, int64_t rows, int64_t cols, int6
 size_t fog_quantize_jit_workspace(void);
 
 /*
- * fog_quantize_jit for up to four tensors in two launches (one abs-max pass over all of them, one cast
- * pass over all of them) instead of two per tensor: a launch costs a few microseconds of ramp and tail
- * whatever it does, which is a fifth of either pass over a 100 MB tensor.  Results are those of
+ * fog_quantize_jit for up to FOG_CAST_BATCH_MAX tensors in two launches (one abs-max pass over all of them,
+ * one cast pass over all of them) instead of two per tensor: a launch costs a few microseconds of ramp and
+ * tail whatever it does, which is a fifth of either pass over a 100 MB tensor.  Results are those of
  * fog_quantize_jit on each job, bit for bit.
- *   jobs   : HOST array of `count` (0..4) descriptions; the device buffers they name follow the rules
+ *   jobs   : HOST array of `count` (0..FOG_CAST_BATCH_MAX) descriptions; the device buffers they name follow the rules
  *            of fog_quantize_jit, restricted to what the fast kernels cover: x_bf16 [rows, cols]
  *            contiguous (leading dimension cols) and 16-byte aligned, rows * cols a positive multiple of
  *            16, q contiguous and 16-byte aligned, no transposed copy.
  *   workspace : fog_quantize_jit_batch_workspace(count) bytes (4 KB per job), 4-byte aligned; contents on
  *            entry do not matter.
- * Errors: NULL, SHAPE (count outside 0..4, non-positive sizes, margin), ALIGN, WORKSPACE, UNSUPPORTED
+ * Errors: NULL, SHAPE (count outside 0..FOG_CAST_BATCH_MAX, non-positive sizes, margin), ALIGN, WORKSPACE, UNSUPPORTED
  * (format; rows * cols not a multiple of 16: use fog_quantize_jit for that tensor).
  */
+#define FOG_CAST_BATCH_MAX 32
 typedef struct {
   const void* x_bf16;
   int64_t rows, cols;
@@ -302,7 +303,13 @@ fog_status fog_kurtosis(const void* x_bf16, int64_t rows, int64_t cols, int64_t 
  *   A, B   : FP8 codes (fmtA / fmtB may differ: E5M2 gradients times E4M3 weights), lda / ldb.
  *   scale_inv_A / _B : one float each (the reciprocal scales of the casts).
  *   C_bf16 : [M, N] bfloat16, leading dimension ldc.
- *   workspace : unused by the current kernels (fog_fp8_gemm_workspace returns 0); may be NULL.
+ *   workspace : NULL, or fog_fp8_gemm_workspace(layout, M, N, K) bytes, 16-byte aligned.  The query returns 0
+ *            for most shapes.  For products with fewer output tiles (256 x 256) than the GPU has compute
+ *            units and a long contraction (the weight gradient of a small projection over many tokens) it
+ *            returns room for binary32 partial tiles: the call then cuts the contraction into chunks that
+ *            run side by side and adds them in a fixed order in a second kernel (deterministic; against the
+ *            unsplit kernel only the order of binary32 additions differs).  Without a workspace, or with a
+ *            smaller one, the unsplit kernel runs: never an error.
  * Requirements: A, B 16-byte aligned, lda, ldb multiples of 16; C 2-byte aligned, any ldc >= N (a
  * 16-byte aligned C with ldc a multiple of 8 takes 16-byte stores, anything else element-wise ones);
  * the contiguous dimension of each operand a multiple of 16 (K for row-major-in-K operands,

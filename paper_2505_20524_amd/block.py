@@ -85,7 +85,7 @@ class CastBatch:
     not cover (a transposed copy wanted, a size that is not a multiple of 16) are cast one by one after it."""
 
     def __init__(self, casts):
-        self.batched = [c for c in casts if c.qT is None and c.x.numel() % 16 == 0 and c.x.numel() > 0][:4]
+        self.batched = [c for c in casts if c.qT is None and c.x.numel() % 16 == 0 and c.x.numel() > 0][:fog.CAST_BATCH_MAX]
         self.single = [c for c in casts if not any(c is b for b in self.batched)]
         self.jobs = fog.make_cast_jobs([(c.x, c.fmt, c.q, c.amax, c.scale, c.sinv) for c in self.batched])
         self.ws = torch.empty(max(fog.quantize_jit_batch_workspace(len(self.batched)), 16), dtype=torch.uint8, device="cuda")
@@ -127,24 +127,33 @@ class LinearStep:
         self.dW = torch.empty((N, K), dtype=torch.int16, device="cuda")
         self.flops = 3 * 2 * M * N * K
         self.casts = CastBatch([self.X, self.W, self.dY])
+        # launches with fewer tiles than compute units are cut along the contraction through this workspace
+        # (one buffer serves the layer's three products, which run one after the other)
+        need = max(fog.fp8_gemm_workspace(fog.NT, M, N, K), fog.fp8_gemm_workspace(fog.NN, M, K, N),
+                   fog.fp8_gemm_workspace(fog.NT if transposed_wgrad else fog.TN, N, K, M))
+        self.gemm_ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
 
     def run(self, timer=None, delayed=False):
+        self.casts.run(timer, delayed)
+        self.compute(timer)
+
+    def compute(self, timer=None):
         lin = self.lin
         M, N, K = lin.M, lin.N, lin.K
-        self.casts.run(timer, delayed)
         # The three products are launched back to back and bracketed by ONE event pair (an event between two
         # launches costs a gap of several microseconds on the stream): the pair's time is that of three launches.
         if timer:
             timer.begin("gemm", 3 * 2 * M * N * K, launches=3)
         # forward  Y = X~ W~^T
-        fog.fp8_gemm(fog.NT, M, N, K, self.X.q, E4M3, self.X.sinv, self.W.q, E4M3, self.W.sinv, self.Y)
+        ws = self.gemm_ws
+        fog.fp8_gemm(fog.NT, M, N, K, self.X.q, E4M3, self.X.sinv, self.W.q, E4M3, self.W.sinv, self.Y, workspace=ws)
         # data gradient  dX = dY~ W~  (W~ is [N, K]: the contraction index N is its row index)
-        fog.fp8_gemm(fog.NN, M, K, N, self.dY.q, E5M2, self.dY.sinv, self.W.q, E4M3, self.W.sinv, self.dX)
+        fog.fp8_gemm(fog.NN, M, K, N, self.dY.q, E5M2, self.dY.sinv, self.W.q, E4M3, self.W.sinv, self.dX, workspace=ws)
         # weight gradient  dW = dY~^T X~  (contraction over the M tokens, the row index of both operands)
         if self.transposed_wgrad:
-            fog.fp8_gemm(fog.NT, N, K, M, self.dY.qT, E5M2, self.dY.sinv, self.X.qT, E4M3, self.X.sinv, self.dW)
+            fog.fp8_gemm(fog.NT, N, K, M, self.dY.qT, E5M2, self.dY.sinv, self.X.qT, E4M3, self.X.sinv, self.dW, workspace=ws)
         else:
-            fog.fp8_gemm(fog.TN, N, K, M, self.dY.q, E5M2, self.dY.sinv, self.X.q, E4M3, self.X.sinv, self.dW)
+            fog.fp8_gemm(fog.TN, N, K, M, self.dY.q, E5M2, self.dY.sinv, self.X.q, E4M3, self.X.sinv, self.dW, workspace=ws)
         if timer:
             timer.end()
 
@@ -169,8 +178,11 @@ class AttentionStep:
         self.flops = self.flops_fwd + self.flops_bwd
 
     def run(self, timer=None, delayed=False):
-        a, c = self.attn, self.c
         self.casts.run(timer, delayed)
+        self.compute(timer)
+
+    def compute(self, timer=None):
+        a, c = self.attn, self.c
         if timer:
             timer.begin("attn_fwd", self.flops_fwd)
         fog.fp8_attn_fwd(a.B, a.H, a.S, a.D, self.s, True, c["Q"].q, c["K"].q, c["V"].q, c["Q"].sinv, c["K"].sinv,
@@ -189,23 +201,51 @@ class AttentionStep:
 
 
 class Block:
-    """All linears and the attention of one synthetic config, resident on the GPU."""
+    """All linears and the attention of one synthetic config, resident on the GPU.
 
-    def __init__(self, cfg):
+    cast_batching says how the just-in-time casts are grouped into fog_quantize_jit_batch calls (two launches each):
+      "layer"   -- one call per linear layer (X, W, dY) and one for attention (Q, K, V, dO), each right before its products;
+      "weights" -- every weight of the block in one call at the start of the step (the weights all exist then), the
+                   activations and gradients per layer as above;
+      "step"    -- every tensor of the step in one call at its start.  The benchmark can do that because every product
+                   has its own resident inputs; a training step can only for tensors that exist at that point."""
+
+    def __init__(self, cfg, cast_batching="layer"):
         self.cfg = cfg
+        self.cast_batching = cast_batching
         # config 2 is stated with the fused cast + transpose for the weight gradient; the block configs leave the
         # arrangement open and use the TN product on the row-major casts
         self.linears = [LinearStep(lin, synth.linear_tensors(cfg, i), transposed_wgrad=(cfg.cid == 2))
                         for i, lin in enumerate(cfg.linears)]
         self.attn = AttentionStep(cfg.attn, synth.attention_tensors(cfg)) if cfg.attn is not None else None
         self.flops = sum(l.flops for l in self.linears) + (self.attn.flops if self.attn else 0)
+        self.pre = []          # batches cast at the start of the step
+        if cast_batching == "step":
+            casts = [c for l in self.linears for c in (l.X, l.W, l.dY)]
+            if self.attn:
+                casts += [self.attn.c[name] for name in ("Q", "K", "V", "dO")]
+            self.pre = [CastBatch(casts[i:i + fog.CAST_BATCH_MAX]) for i in range(0, len(casts), fog.CAST_BATCH_MAX)]
+        elif cast_batching == "weights":
+            ws = [l.W for l in self.linears]
+            self.pre = [CastBatch(ws[i:i + fog.CAST_BATCH_MAX]) for i in range(0, len(ws), fog.CAST_BATCH_MAX)]
+            for l in self.linears:
+                l.casts = CastBatch([l.X, l.dY])
+        elif cast_batching != "layer":
+            raise ValueError(cast_batching)
 
     def step(self, timer=None, delayed=False):
         """One pass of the path; delayed=True scales every cast from its abs-max history instead of just in time."""
+        for b in self.pre:
+            b.run(timer, delayed)
+        per_layer = self.cast_batching != "step"
         for l in self.linears:
-            l.run(timer, delayed)
+            if per_layer:
+                l.casts.run(timer, delayed)
+            l.compute(timer)
         if self.attn:
-            self.attn.run(timer, delayed)
+            if per_layer:
+                self.attn.casts.run(timer, delayed)
+            self.attn.compute(timer)
 
 
 class EventTimer:

@@ -347,10 +347,10 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const uint16_t*
 
 // ---------------------------------------------------------------- several tensors per launch (just-in-time scaling)
 // A launch costs about 4 us of ramp and tail whatever it does, a fifth of what the abs-max or the cast of a
-// 100 MB tensor takes; fog_quantize_jit_batch therefore runs the abs-max pass of up to four contiguous
+// 100 MB tensor takes; fog_quantize_jit_batch therefore runs the abs-max pass of up to kBatchMax contiguous
 // tensors as ONE launch and their cast pass as another.  Workgroups are dealt to the jobs in proportion to
 // their sizes; inside its job a workgroup does exactly what it does in the one-tensor kernels.
-constexpr int kBatchMax = 4;
+constexpr int kBatchMax = FOG_CAST_BATCH_MAX;
 struct BatchJobs {
   int count;
   int amax_first[kBatchMax + 1];   // first workgroup of each job in the abs-max launch (prefix sums)
@@ -367,9 +367,8 @@ constexpr int kJitSlots = 1024;    // workspace words per job = most workgroups 
 
 __global__ __launch_bounds__(kThreads) void amax_batch_kernel(BatchJobs b, uint32_t* __restrict__ ws) {
   int j = 0;
-#pragma unroll
-  for (int k = 1; k < kBatchMax; ++k)
-    if (k < b.count && (int)blockIdx.x >= b.amax_first[k]) j = k;
+  for (int k = 1; k < b.count; ++k)
+    if ((int)blockIdx.x >= b.amax_first[k]) j = k;
   const int nb = b.amax_first[j + 1] - b.amax_first[j];
   amax_span<true>(reinterpret_cast<const uint4*>(b.x[j]), b.n[j] / 8, nullptr, 0, ws + j * kJitSlots, (int)blockIdx.x - b.amax_first[j], nb);
 }
@@ -377,9 +376,8 @@ __global__ __launch_bounds__(kThreads) void amax_batch_kernel(BatchJobs b, uint3
 __global__ __launch_bounds__(kThreads) void quantize_batch_kernel(BatchJobs b, const uint32_t* __restrict__ ws) {
   // position p in the launch order is job count - 1 - p: the tensor whose abs-max pass ran last is cast first
   int p = 0;
-#pragma unroll
-  for (int k = 1; k < kBatchMax; ++k)
-    if (k < b.count && (int)blockIdx.x >= b.cast_first[k]) p = k;
+  for (int k = 1; k < b.count; ++k)
+    if ((int)blockIdx.x >= b.cast_first[k]) p = k;
   const int j = b.count - 1 - p;
   const int bid = (int)blockIdx.x - b.cast_first[p], nb = b.cast_first[p + 1] - b.cast_first[p];
   const ScaleSource js{ws + j * kJitSlots, b.amax_first[j + 1] - b.amax_first[j], b.fmt[j], b.margin[j], b.amax[j], b.scale[j], b.scale_inv[j],

@@ -29,6 +29,13 @@
 //
 // The MFMA is issued with the B fragment as first operand so that a lane ends up with four
 // consecutive output columns per register quad and can store 8 bytes of bf16 at a time.
+//
+// Contraction split.  A launch with fewer tiles than compute units leaves the rest of the chip idle
+// (the weight gradient of a 2048 x 2048 projection over 16384 tokens is 64 tiles of K = 16384).  With a
+// caller workspace such a product is cut along K into `splits` chunks: the unit of work becomes
+// (tile, chunk), every unit leaves its binary32 accumulators in the workspace, and a second kernel adds
+// the chunks of a tile in a fixed order, applies the scales and rounds once to bf16.  Deterministic (no
+// atomics); the sums differ from the unsplit kernel's only in the order of binary32 additions.
 #include "common.h"
 #include "launch.h"
 
@@ -60,6 +67,11 @@ struct GemmArgs {
   int tiles_m, tiles_n;
   int vec_store;  // C rows allow 16-byte stores
   uint32_t a_bytes, b_bytes;  // addressable span of each operand
+  // contraction split (splits == 1: none): work item = chunk * tiles + tile, chunk c covers
+  // contraction indices [c * k_chunk, min(K, (c + 1) * k_chunk)); partial holds splits * tiles blocks
+  // of 256 x 256 floats in the register order of the accumulators
+  int splits, k_chunk;
+  float* partial;
 };
 
 typedef __attribute__((address_space(3))) v2i* lds_v2i_ptr;
@@ -101,7 +113,8 @@ struct LoadPlan {
 };
 
 // K-contiguous operand: piece j covers tile rows 64 w + 8 j .. + 7; lane -> (row, LDS chunk position).
-FOG_DEVICE LoadPlan plan_kc(int64_t ld, int row0, int rows, int K) {
+// The plans cover contraction indices kb .. kb + K - 1 of the operand (a chunk of a split product, or all of it).
+FOG_DEVICE LoadPlan plan_kc(int64_t ld, int row0, int rows, int kb, int K) {
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int r8 = l >> 3, pos = l & 7;
   LoadPlan p;
@@ -115,12 +128,12 @@ FOG_DEVICE LoadPlan plan_kc(int64_t ld, int row0, int rows, int K) {
     // row = 64 w + 8 j + r8: the swizzle key (row >> 1) & 7 is (r8 >> 1) ^ 4 (j & 1)
     const int c = pos ^ (r8 >> 1) ^ (4 * par);  // global chunk that lives at LDS position pos of this row
     p.klim[par] = K - 16 * c;
-    p.off[par] = (uint32_t)((int64_t)(first + 8 * par) * ld + 16 * c);
+    p.off[par] = (uint32_t)((int64_t)(first + 8 * par) * ld + 16 * c + kb);
   }
   return p;
 }
 // K-major operand: piece j covers contraction rows 32 w + 4 j .. + 3 of the pair; lane -> (k, LDS chunk position).
-FOG_DEVICE LoadPlan plan_km(int64_t ld, int col0, int cols, int K) {
+FOG_DEVICE LoadPlan plan_km(int64_t ld, int col0, int cols, int kb, int K) {
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
   LoadPlan p;
   p.step = (uint32_t)(PAIR_K * ld);
@@ -132,7 +145,7 @@ FOG_DEVICE LoadPlan plan_km(int64_t ld, int col0, int cols, int K) {
     // k + 4 j: the swizzle key (k + 4 j) & 7 is ((l >> 4) & 7) ^ 4 (j & 1)
     const int c = (l & 15) ^ (l >> 4) ^ (4 * par);
     p.klim[par] = K - k;
-    p.off[par] = (col0 + 16 * c < cols) ? (uint32_t)((int64_t)(k + 4 * par) * ld + col0 + 16 * c) : OOB;  // cols % 16 == 0
+    p.off[par] = (col0 + 16 * c < cols) ? (uint32_t)((int64_t)(kb + k + 4 * par) * ld + col0 + 16 * c) : OOB;  // cols % 16 == 0
   }
   return p;
 }
@@ -243,13 +256,16 @@ FOG_DEVICE uint32_t cvt_pk_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-template <int LAYOUT, int FA, int FB>
+// SPLIT: the work items are (tile, contraction chunk) pairs and the epilogue leaves the binary32
+// accumulators in the workspace instead of writing C (see the header comment).
+template <int LAYOUT, int FA, int FB, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   constexpr bool A_KM = LAYOUT == FOG_TN;
   constexpr bool B_KM = LAYOUT != FOG_NT;
 
-  const TileWalk walk = tile_walk(g.tiles_m * g.tiles_n);
+  const int ntiles = g.tiles_m * g.tiles_n;
+  const TileWalk walk = tile_walk(SPLIT ? ntiles * g.splits : ntiles);
   if (walk.first >= walk.end) return;
 
   const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
@@ -269,8 +285,19 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
 #pragma unroll
   for (int r = 0; r < 16; ++r) zero16[r] = 0.0f;
 
-  const int nk = (g.K + BK - 1) / BK;
+  const int nk = ((SPLIT ? g.k_chunk : g.K) + BK - 1) / BK;   // every chunk of a split takes the steps of a full chunk
   const int nk4 = (nk + 3) & ~3;  // steps are handled four at a time (two pair stages); steps past K multiply zeros
+  // work item -> tile, first contraction index, number of contraction indices
+  auto item_range = [&](int item, int& logical, int& kb, int& klen) {
+    if (SPLIT) {
+      const int c = item / ntiles;
+      logical = item - c * ntiles;
+      kb = c * g.k_chunk;
+      klen = min(g.K - kb, g.k_chunk);
+    } else {
+      logical = item; kb = 0; klen = g.K;
+    }
+  };
 
 #define FOG_LOAD_A(j, k0, ST) issue_piece<A_KM>(pa, j, rsrc_a, k0, lds_w + RING_A + (ST) * OPERAND_BYTES + 1024u * (j))
 #define FOG_LOAD_B(j, k0, ST) issue_piece<B_KM>(pb, j, rsrc_b, k0, lds_w + RING_B + (ST) * OPERAND_BYTES + 1024u * (j))
@@ -364,10 +391,11 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
   // tile the first two pairs of the workgroup's next tile are already being fetched, so a new tile
   // starts with its data in LDS and its first fragments in registers, and the epilogue's stores
   // drain while the next tile computes.
-  int m0, n0;
-  tile_origin(walk.first, g.tiles_m, g.tiles_n, m0, n0);
-  LoadPlan pa = A_KM ? plan_km(g.lda, m0, g.M, g.K) : plan_kc(g.lda, m0, g.M, g.K);
-  LoadPlan pb = B_KM ? plan_km(g.ldb, n0, g.N, g.K) : plan_kc(g.ldb, n0, g.N, g.K);
+  int m0, n0, logical, kb, klen;
+  item_range(walk.first, logical, kb, klen);
+  tile_origin(logical, g.tiles_m, g.tiles_n, m0, n0);
+  LoadPlan pa = A_KM ? plan_km(g.lda, m0, g.M, kb, klen) : plan_kc(g.lda, m0, g.M, kb, klen);
+  LoadPlan pb = B_KM ? plan_km(g.ldb, n0, g.N, kb, klen) : plan_kc(g.ldb, n0, g.N, kb, klen);
   v8i fa[4], fa3, xb[4], yb[4];   // A fragments (row 3 twice), B fragments twice
   FOG_ISSUE_PAIR(0, 0);
   FOG_ISSUE_PAIR(PAIR_K, 1);
@@ -391,9 +419,10 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
       /* last four steps of this tile: the loads issued now belong to the next tile (all zero-fill  \
          if there is none, which keeps the outstanding-load count the waits assume) */              \
       if (next < walk.end) {                                                                         \
-        tile_origin(next, g.tiles_m, g.tiles_n, m0, n0);                                             \
-        pa = A_KM ? plan_km(g.lda, m0, g.M, g.K) : plan_kc(g.lda, m0, g.M, g.K);                     \
-        pb = B_KM ? plan_km(g.ldb, n0, g.N, g.K) : plan_kc(g.ldb, n0, g.N, g.K);                     \
+        item_range(next, logical, kb, klen);                                                         \
+        tile_origin(logical, g.tiles_m, g.tiles_n, m0, n0);                                          \
+        pa = A_KM ? plan_km(g.lda, m0, g.M, kb, klen) : plan_kc(g.lda, m0, g.M, kb, klen);           \
+        pb = B_KM ? plan_km(g.ldb, n0, g.N, kb, klen) : plan_kc(g.ldb, n0, g.N, kb, klen);           \
       } else {                                                                                       \
         pa.off[0] = pa.off[1] = pb.off[0] = pb.off[1] = OOB;                                         \
       }                                                                                              \
@@ -417,6 +446,21 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
     // Each 32 x 32 block is scaled, converted to bf16, parked in one of the wave's two LDS staging
     // buffers (alternating, so that the next block is converted while this one is written out) and
     // stored as 16-byte pieces, four lanes per 64-byte row segment: 32 coalesced stores per lane.
+    if (SPLIT) {
+      // The accumulators as they are: float4 number ((w * 16 + 4 i + j) * 4 + qd) * 64 + l of this item's block,
+      // i.e. 1 KB per wave and store instruction.  Waited for at once (the next item's prefetch is waited for
+      // with them, as on the edge-tile path below).
+      float4* dst = reinterpret_cast<float4*>(g.partial) + (int64_t)tile * (BM * BN / 4) + (w * 16) * 256 + l;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int qd = 0; qd < 4; ++qd)
+            dst[((4 * i + j) * 4 + qd) * 64] = make_float4(acc[i][j][4 * qd + 0], acc[i][j][4 * qd + 1], acc[i][j][4 * qd + 2], acc[i][j][4 * qd + 3]);
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      continue;
+    }
     const bool fast = g.vec_store != 0 && m_cur + BM <= g.M && n_cur + BN <= g.N;
     const int prow = l >> 2, piece = l & 3;   // this lane's row (+ 16 t) and 16-byte piece of a staged block
     if (fast) {
@@ -508,27 +552,111 @@ int compute_units() {
   return cus;
 }
 
+// Persistent grid for `total` work items: one workgroup per compute unit (a multiple of 8 so that every XCD
+// gets the same number), fewer when there are fewer items.  The launch takes ceil(total / grid) rounds
+// whatever happens; the smallest grid that still needs that many rounds leaves no workgroup idle in the last
+// one and, on a power-limited part, lets the busy CUs clock higher (896 tiles: 224 workgroups x 4 rounds
+// instead of 256 x 3.5).
+int persistent_grid(int64_t total, int* rounds_out = nullptr) {
+  int grid = (compute_units() / 8) * 8;
+  if (grid < 8) grid = 8;
+  const int64_t rounds = (total + grid - 1) / grid;
+  const int64_t need = (((total + rounds - 1) / rounds + 7) / 8) * 8;
+  if (grid > need) grid = (int)need;
+  if (rounds_out) *rounds_out = (int)rounds;
+  return grid;
+}
+
+// Split of the contraction (1 = none) for a product of `tiles` output tiles over K, from a cost model in
+// shader cycles: a K-step costs about 1100 cycles, the bf16 epilogue of a tile about 9000 (all CUs write at
+// once), the binary32 one twice that, and the reduce pass moves its bytes at about 2000 per cycle plus a
+// launch.  A split is only taken when the model promises a clear gain (measured: the 64-tile weight gradient of
+// a 2048 x 2048 projection over 16384 tokens 131 -> 72 us, the 128-tile data gradient 4096 x 2048 over 8192 81 ->
+// 74 us; a 192-tile product, which the model rejects, loses when forced: 179 -> 227 us).
+struct SplitPlan { int splits, k_chunk; };
+SplitPlan choose_split(int64_t M, int64_t N, int64_t K, int64_t tiles) {
+  SplitPlan best{1, (int)K};
+  if (tiles >= compute_units() || K < 1024) return best;
+  auto cost = [&](int splits, int64_t k_chunk) {
+    int rounds = 0;
+    persistent_grid(tiles * splits, &rounds);
+    const int64_t steps = ((k_chunk + BK - 1) / BK + 3) & ~(int64_t)3;
+    double c = (double)rounds * (steps * 1100.0 + (splits > 1 ? 18000.0 : 9000.0));
+    if (splits > 1) c += ((double)tiles * splits * BM * BN * 4 + 2.0 * M * N) / 2000.0 + 6000.0;
+    return c;
+  };
+#ifndef FOG_SPLIT_MIN_GAIN
+#define FOG_SPLIT_MIN_GAIN 0.93   /* a split must promise this fraction of the unsplit time, or less */
+#endif
+  const double unsplit = cost(1, K);
+  double best_cost = unsplit * FOG_SPLIT_MIN_GAIN;
+  for (int want = 2; want <= 16; ++want) {
+    const int64_t k_chunk = ((K + want - 1) / want + 255) / 256 * 256;
+    if (k_chunk < 512) break;
+    const int splits = (int)((K + k_chunk - 1) / k_chunk);
+    if (splits < 2) continue;
+    const double c = cost(splits, k_chunk);
+    if (c < best_cost) { best_cost = c; best = SplitPlan{splits, (int)k_chunk}; }
+  }
+  return best;
+}
+
+// Second pass of a split product: a workgroup owns one 32 x 32 block of C (the 256 float4 that one wave
+// wrote with four consecutive store instructions), adds the chunks in ascending order, scales, rounds to
+// bf16 and writes the block through LDS as 16-byte row pieces.
+__global__ __launch_bounds__(256) void gemm_split_reduce_kernel(GemmArgs g) {
+  __shared__ __attribute__((aligned(16))) uint8_t blk[32 * EPI_STRIDE];
+  const int ntiles = g.tiles_m * g.tiles_n;
+  const int logical = blockIdx.x >> 6, sub = blockIdx.x & 63;     // 64 blocks of 32 x 32 per tile: sub = w * 16 + 4 i + j
+  const int t = threadIdx.x, l = t & 63, qd = t >> 6;
+  const float4* src = reinterpret_cast<const float4*>(g.partial) + (int64_t)logical * (BM * BN / 4) + sub * 256 + t;
+  float4 acc = src[0];
+  for (int c = 1; c < g.splits; ++c) {
+    const float4 v = src[(int64_t)c * ntiles * (BM * BN / 4)];
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  const float alpha = (*g.sinv_a) * (*g.sinv_b);
+  *reinterpret_cast<uint2*>(blk + (l & 31) * EPI_STRIDE + 16 * qd + 8 * (l >> 5)) =
+      make_uint2(cvt_pk_bf16(acc.x * alpha, acc.y * alpha), cvt_pk_bf16(acc.z * alpha, acc.w * alpha));
+  __syncthreads();
+  int m0, n0;
+  tile_origin(logical, g.tiles_m, g.tiles_n, m0, n0);
+  const int w = sub >> 4, i = (sub >> 2) & 3, j = sub & 3;
+  const int mb = m0 + (w >> 1) * 128 + 32 * i, nb = n0 + (w & 1) * 128 + 32 * j;   // origin of the block in C
+  if (t < 128) {
+    const int row = t >> 2, piece = t & 3;
+    const int m = mb + row, n = nb + 8 * piece;
+    if (m < g.M && n < g.N) {
+      const uint4 v = *reinterpret_cast<const uint4*>(blk + row * EPI_STRIDE + 16 * piece);
+      uint16_t* dst = g.C + (int64_t)m * g.ldc + n;
+      if (g.vec_store && n + 8 <= g.N) {
+        *reinterpret_cast<uint4*>(dst) = v;
+      } else {
+        const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (n + e < g.N) dst[e] = (uint16_t)(wv[e >> 1] >> (16 * (e & 1)));
+      }
+    }
+  }
+}
+
 template <int LAYOUT, int FA, int FB>
 fog_status launch(const GemmArgs& g, hipStream_t s) {
-  auto kern = fp8_gemm_kernel<LAYOUT, FA, FB>;
-  static bool configured = false;  // per instantiation; the attribute is sticky for the process
+  static bool configured = false;  // per instantiation pair; the attribute is sticky for the process
   if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(fp8_gemm_kernel<LAYOUT, FA, FB, false>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(fp8_gemm_kernel<LAYOUT, FA, FB, true>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
       return FOG_ERR_HIP;
     configured = true;
   }
-  // Persistent grid: one workgroup per compute unit (a multiple of 8 so that every XCD gets the
-  // same number), fewer when there are fewer tiles.
-  const int total = g.tiles_m * g.tiles_n;
-  int grid = (compute_units() / 8) * 8;
-  if (grid < 8) grid = 8;
-  // The launch takes ceil(total / grid) rounds of tiles whatever happens; the smallest grid that still
-  // needs that many rounds leaves no workgroup idle in the last one and, on a power-limited part,
-  // lets the busy CUs clock higher (896 tiles: 224 workgroups x 4 rounds instead of 256 x 3.5).
-  const int rounds = (total + grid - 1) / grid;
-  const int need = (((total + rounds - 1) / rounds + 7) / 8) * 8;
-  if (grid > need) grid = need;
-  kern<<<grid, kThreads, LDS_BYTES, s>>>(g);
+  const int64_t tiles = (int64_t)g.tiles_m * g.tiles_n;
+  if (g.splits > 1) {
+    fp8_gemm_kernel<LAYOUT, FA, FB, true><<<persistent_grid(tiles * g.splits), kThreads, LDS_BYTES, s>>>(g);
+    gemm_split_reduce_kernel<<<(int)(tiles * 64), 256, 0, s>>>(g);
+  } else {
+    fp8_gemm_kernel<LAYOUT, FA, FB, false><<<persistent_grid(tiles), kThreads, LDS_BYTES, s>>>(g);
+  }
   return fog_launch_status();
 }
 
@@ -542,13 +670,17 @@ inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintp
 
 }  // namespace
 
-extern "C" size_t fog_fp8_gemm_workspace(fog_layout, int64_t, int64_t, int64_t) { return 0; }
+extern "C" size_t fog_fp8_gemm_workspace(fog_layout, int64_t M, int64_t N, int64_t K) {
+  if (M <= 0 || N <= 0 || K <= 0 || M > 0x7FFFFF00 || N > 0x7FFFFF00 || K > 0x7FFFFF00) return 0;
+  const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+  const SplitPlan sp = choose_split(M, N, K, tiles);
+  return sp.splits > 1 ? (size_t)sp.splits * tiles * BM * BN * sizeof(float) : 0;
+}
 
 extern "C" fog_status fog_fp8_gemm(fog_layout layout, int64_t M, int64_t N, int64_t K,
                                    const uint8_t* A, fog_fp8 fmtA, int64_t lda, const float* scale_inv_A,
                                    const uint8_t* B, fog_fp8 fmtB, int64_t ldb, const float* scale_inv_B,
                                    void* C_bf16, int64_t ldc, void* workspace, size_t workspace_bytes, void* stream) {
-  (void)workspace; (void)workspace_bytes;
   if (M < 0 || N < 0 || K < 0) return FOG_ERR_SHAPE;
   if (layout != FOG_NT && layout != FOG_NN && layout != FOG_TN) return FOG_ERR_UNSUPPORTED;
   if ((fmtA != FOG_E4M3 && fmtA != FOG_E5M2) || (fmtB != FOG_E4M3 && fmtB != FOG_E5M2)) return FOG_ERR_UNSUPPORTED;
@@ -578,6 +710,14 @@ extern "C" fog_status fog_fp8_gemm(fog_layout layout, int64_t M, int64_t N, int6
   const int64_t a_span = K > 0 ? (a_rows - 1) * lda + a_cols : 0, b_span = K > 0 ? (b_rows - 1) * ldb + b_cols : 0;
   if (a_span >= 0x7FFFFFFF || b_span >= 0x7FFFFFFF) return FOG_ERR_UNSUPPORTED;  // 32-bit buffer offsets
   g.a_bytes = (uint32_t)a_span; g.b_bytes = (uint32_t)b_span;
+  g.splits = 1; g.k_chunk = (int)K; g.partial = nullptr;
+  if (K > 0 && workspace && aligned(workspace, 16)) {
+    // the split the workspace query promised, when the caller brought that much
+    const SplitPlan sp = choose_split(M, N, K, (int64_t)g.tiles_m * g.tiles_n);
+    if (sp.splits > 1 && workspace_bytes >= (size_t)sp.splits * g.tiles_m * g.tiles_n * BM * BN * sizeof(float)) {
+      g.splits = sp.splits; g.k_chunk = sp.k_chunk; g.partial = reinterpret_cast<float*>(workspace);
+    }
+  }
   hipStream_t s = (hipStream_t)stream;
   if (K == 0) {
     int64_t blocks = (M * N + 255) / 256;

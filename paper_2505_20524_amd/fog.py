@@ -11,6 +11,7 @@ import torch
 
 E4M3, E5M2 = 0, 1
 NT, NN, TN = 0, 1, 2
+CAST_BATCH_MAX = 32          # FOG_CAST_BATCH_MAX of the header
 
 _LIB = None
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -334,16 +334,18 @@ def test_block_driver_jit_cast_equals_the_three_separate_calls():
 
 
 @pytest.mark.parametrize("shapes", [[(1, 16)], [(64, 256), (8, 48)], [(300, 1024), (2, 8), (128, 4096)],
-                                    [(2048, 4096), (96, 160), (5000, 1024), (1, 16)], [(4100, 8192), (333, 1008)]])
+                                    [(2048, 4096), (96, 160), (5000, 1024), (1, 16)], [(4100, 8192), (333, 1008)],
+                                    [(64 + 16 * k, 128 + 32 * (k % 5)) for k in range(19)] + [(3000, 2048)],     # a whole step's tensors in one call
+                                    [(16, 16 + 16 * k) for k in range(32)]])                                        # the most jobs a call takes
 def test_quantize_jit_batch_equals_the_single_tensor_call(shapes):
-    """fog_quantize_jit_batch (two launches for up to four tensors) against fog_quantize_jit per tensor and against the
+    """fog_quantize_jit_batch (two launches for up to 32 tensors) against fog_quantize_jit per tensor and against the
     oracle: bytes, abs-max, scale and reciprocal scale bit for bit; mixed formats, sizes from 16 elements to more than
     the largest grids take in one trip."""
     rng = np.random.default_rng(len(shapes) * 100 + shapes[0][0])
     items, refs = [], []
     for k, (rows, cols) in enumerate(shapes):
         fmt = fp8.E4M3 if k % 2 == 0 else fp8.E5M2
-        xb = synth.f32_to_bf16_bits(rng.standard_normal((rows, cols)).astype(np.float32) * (10.0 ** (k - 1)))
+        xb = synth.f32_to_bf16_bits(rng.standard_normal((rows, cols)).astype(np.float32) * (10.0 ** (k % 7 - 1)))
         x = dev(xb)
         q = torch.full((rows, cols), 0xAA, dtype=torch.uint8, device="cuda")
         am, sc, si = (torch.full((1,), -1.0, device="cuda") for _ in range(3))
@@ -372,7 +374,7 @@ def test_quantize_jit_batch_argument_errors():
     x = torch.zeros((4, 64), dtype=torch.int16, device="cuda")
     q = torch.zeros((4, 64), dtype=torch.uint8, device="cuda")
     f = [torch.zeros(1, device="cuda") for _ in range(3)]
-    ws = torch.zeros(4 * 4096, dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(33 * 4096, dtype=torch.uint8, device="cuda")
 
     def call(items, count=None, wsp=ws.data_ptr(), wsb=ws.numel(), **over):
         jobs = fog.make_cast_jobs(items)
@@ -383,7 +385,7 @@ def test_quantize_jit_batch_argument_errors():
     good = (x, fp8.E4M3, q, f[0], f[1], f[2])
     assert call([good]) == 0 and call([good], scale_inv=None) == 0 and call([], count=0) == 0
     assert call([good], wsp=None) == 1 and call([good], x_bf16=None) == 1 and call([good], q=None) == 1 and call([good], amax=None) == 1
-    assert call([good] * 4, count=5) == 2 and call([good], rows=0) == 2 and call([good], margin=100) == 2
+    assert call([good] * 33) == 2 and call([good], rows=0) == 2 and call([good], margin=100) == 2
     assert call([good], x_bf16=x.data_ptr() + 2) == 3 and call([good], wsp=ws.data_ptr() + 1) == 3
     assert call([good], fmt=2) == 4 and call([good], cols=63) == 4
     assert call([good, good], wsb=4096) == 5

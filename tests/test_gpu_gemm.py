@@ -175,3 +175,65 @@ def test_config2_full_size_all_three_products():
     ref = gemm.fp8_gemm(gemm.TN, dY[0], fp8.E5M2, dY[1], X[0], fp8.E4M3, X[1])                   # dW = dY^T X
     check_bf16(gpu(fog.TN, N, K, M, dv["dY"][0], 1, dv["dY"][2], dv["X"][0], 0, dv["X"][2]), ref, what="wgrad TN")
     check_bf16(gpu(fog.NT, N, K, M, dv["dY"][1], 1, dv["dY"][2], dv["X"][1], 0, dv["X"][2]), ref, what="wgrad NT(dY^T, X^T)")
+
+
+def run_gemm_ws(layout, a, fa, sa, b, fb, sb, M, N, K, ws_bytes=None):
+    """fog_fp8_gemm with the workspace the query asks for (or `ws_bytes`); returns (C bits, bytes the query asked for)."""
+    need = fog.fp8_gemm_workspace(layout, M, N, K)
+    n = need if ws_bytes is None else ws_bytes
+    ws = torch.full((max(n, 16),), 0xFF, dtype=torch.uint8, device="cuda") if n else None      # NaN patterns: a partial read before written would show
+    C = torch.full((M, N), 0x7FC0, dtype=torch.int16, device="cuda")
+    fog.fp8_gemm(layout, M, N, K, dev(a), fa, fscalar(sa), dev(b), fb, fscalar(sb), C, workspace=ws)
+    torch.cuda.synchronize()
+    return host_u16(C), need
+
+
+SPLIT_SHAPES = [   # few output tiles, long contraction: the launches the split is for
+    (gemm.TN, 2048, 2048, 16384),     # config 4: weight gradient of the output projection (64 tiles)
+    (gemm.NN, 4096, 2048, 8192),      # config 2: data gradient (128 tiles)
+    (gemm.NT, 256, 256, 32768),       # one tile
+    (gemm.NN, 1024, 1024, 8192),      # 16 tiles
+    (gemm.NT, 300, 200, 5008),        # ragged edges, contraction not a multiple of the chunk or of a K-step
+    (gemm.TN, 272, 528, 4112),        # K-major operands with a ragged contraction
+    (gemm.NN, 48, 1040, 12304),
+]
+
+
+@pytest.mark.parametrize("layout,M,N,K", SPLIT_SHAPES)
+def test_gemm_contraction_split(layout, M, N, K):
+    """With the workspace the query asks for, launches of few tiles are cut along the contraction (binary32 partial
+    tiles, reduced in a fixed order): same gate as the unsplit kernel, the same bits on a second call, and without a
+    workspace (or with one that is too small) the unsplit kernel answers inside the same gate."""
+    fa, fb = (fp8.E5M2, fp8.E4M3) if layout != gemm.NT else (fp8.E4M3, fp8.E4M3)
+    A8, sa, B8, sb = quantized_layer(M + 3 * N + K, M, N, K, fa, fb)
+    a, b = lay(layout, A8, B8)
+    ref = gemm.fp8_gemm(layout, a, fa, sa, b, fb, sb)
+    got, need = run_gemm_ws(layout, a, fa, sa, b, fb, sb, M, N, K)
+    assert need > 0 and need % (256 * 256 * 4) == 0, "the query did not ask for a split on this shape"
+    st = check_bf16(got, ref, what="split %d %dx%dx%d" % (layout, M, N, K))
+    assert st["max_steps"] <= 1
+    again, _ = run_gemm_ws(layout, a, fa, sa, b, fb, sb, M, N, K)
+    assert np.array_equal(got, again)                      # deterministic: no atomics, fixed order of the chunks
+    for small in (0, need - 1):
+        unsplit, _ = run_gemm_ws(layout, a, fa, sa, b, fb, sb, M, N, K, ws_bytes=small)
+        check_bf16(unsplit, ref, what="unsplit fallback")
+    # the two routes differ only in the order of binary32 additions: at most one bf16 step, on few elements
+    steps = np.abs(got.astype(np.int32) - unsplit.astype(np.int32))
+    assert steps.max() <= 1 and (steps > 0).mean() < 0.05
+
+
+def test_gemm_split_exact_integers_and_query():
+    """Small integers: every partial sum is exact, so split and unsplit give identical, exact results; shapes with
+    enough tiles ask for no workspace."""
+    rng = np.random.default_rng(11)
+    M, N, K = 256, 512, 16384
+    Ai = rng.integers(-2, 3, size=(M, K)); Bi = rng.integers(-2, 3, size=(N, K))
+    Ai[rng.random((M, K)) < 0.97] = 0; Bi[rng.random((N, K)) < 0.9] = 0
+    assert np.abs(Ai @ Bi.T).max() < 256
+    A8 = scaling.quantize(synth.f32_to_bf16_bits(Ai.astype(np.float32)), np.float32(1), fp8.E4M3)
+    B8 = scaling.quantize(synth.f32_to_bf16_bits(Bi.astype(np.float32)), np.float32(1), fp8.E4M3)
+    got, need = run_gemm_ws(gemm.NT, A8, fp8.E4M3, 0.5, B8, fp8.E4M3, 0.5, M, N, K)
+    assert need > 0
+    assert np.array_equal(synth.bf16_bits_to_f32(got).astype(np.float64), (Ai @ Bi.T) / 4.0)
+    for (layout, m, n, k) in [(gemm.NT, 8192, 12288, 4096), (gemm.TN, 14336, 4096, 8192), (gemm.NT, 512, 1024, 1024)]:
+        assert fog.fp8_gemm_workspace(layout, m, n, k) == 0

@@ -36,6 +36,7 @@ def test_binding_covers_the_header_and_pure_host_queries():
     from paper_2505_20524_amd import fog
     assert sorted(fog.SIGNATURES) == declared_symbols()
     lib = fog.load()
-    assert lib.fog_fp8_gemm_workspace(0, 4096, 8192, 2048) == 0
+    assert lib.fog_fp8_gemm_workspace(0, 4096, 8192, 2048) == 0              # 512 tiles: no split
+    assert lib.fog_fp8_gemm_workspace(2, 2048, 2048, 16384) % (256 * 256 * 4) == 0
     assert lib.fog_fp8_attn_workspace(4, 16, 16, 2048, 128, 1) >= 4 * 16 * 2048 * 4
     assert lib.fog_fp8_attn_workspace(4, 16, 16, 2048, 128, 0) == 0
