@@ -27,10 +27,6 @@ sys.path.insert(0, ROOT)
 
 PEAK_FP8_TFLOPS = 5033.0     # 256 CU x 4 SIMD x 2048 FLOP/clk x 2.4 GHz (dense FP8 MFMA)
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per fp8_gemm_kernel launch (average over the step's 15 launches), from two rocprofv3 --pmc
-# runs of this script (FETCH_SIZE, WRITE_SIZE), each scaled by the reading of a plain 1 GiB copy:
-# 668 MB read + 123 MB written.  Only measured for the default workload.
-MEASURED_GEMM_TRAFFIC_BYTES = {5: 7.940e8}
 
 
 def _host_threads():
@@ -147,6 +143,9 @@ def main():
     ap.add_argument("--vendor-context", action="store_true",
                     help="also time the vendor library's FP8 GEMM (torch._scaled_mm) on the forward shapes: context only, "
                          "never on the path and never part of `value`")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="also measure what the GPU sustains: a register-resident FP8 matrix-instruction loop on several operand "
+                         "bit patterns (constant, small codes, random bytes, the step's own operands) and plain HBM read / copy rates")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
@@ -192,7 +191,7 @@ def main():
     for _ in range(args.steps):
         blk.step(others)
     torch.cuda.synchronize()
-    summ = others.summary()
+    summ = others.summary(drop_outliers=True)
     # The same step under delayed scaling (the recipe of the paper's runs): every cast is one pass with the scale
     # from its abs-max history.  A second figure, not the headline (the metric is quoted on just-in-time scaling).
     for _ in range(max(args.warmup, 2)):
@@ -207,17 +206,17 @@ def main():
     for _ in range(args.steps):
         blk.step(dl, delayed=True)
     torch.cuda.synchronize()
-    summ["cast_delayed"] = dl.summary()["cast_delayed"]
+    summ["cast_delayed"] = dl.summary(drop_outliers=True)["cast_delayed"]
     summ[dominant] = timer.summary()[dominant]
     kernels = {}
     for kind, (n, work, ms) in summ.items():
         if kind in ("gemm", "attn_fwd", "attn_bwd"):
             ach = work / (ms * 1e-3) / 1e12
-            kernels[kind] = {"launches_per_step": n // args.steps, "avg_launch_ms": ms / n, "achieved": ach,
+            kernels[kind] = {"launches_per_step": max(1, round(n / args.steps)), "avg_launch_ms": ms / n, "achieved": ach,
                              "unit": "TFLOP/s", "frac": ach / PEAK_FP8_TFLOPS, "in_timed_region": kind == dominant}
         else:
             ach = work / (ms * 1e-3) / 1e9
-            kernels[kind] = {"launches_per_step": n // args.steps, "avg_launch_ms": ms / n, "achieved": ach,
+            kernels[kind] = {"launches_per_step": max(1, round(n / args.steps)), "avg_launch_ms": ms / n, "achieved": ach,
                              "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "in_timed_region": False}
     # Figures of kernels that are not steps of the timed path, each timed on its own after the timed region
     # (first repetition untimed): jobs = [(algorithmic bytes, call), ...].
@@ -235,6 +234,18 @@ def main():
         kernels[key] = {"launches": n, "avg_launch_ms": ms / n, "achieved": work / (ms * 1e-3) / 1e9,
                         "unit": "GB/s", "frac": work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "in_timed_step": False}
 
+    # The step's just-in-time casts again, back to back without the products between them.  Inside the step the abs-max
+    # pass that follows a GEMM also pays for the write-back of that GEMM's output (up to 235 MB of dirty lines leave
+    # the caches while it streams); alone, the same launches show what the cast kernels themselves sustain.
+    alone = block.EventTimer(only={"cast_jit"})
+    for rep in range(4):
+        per_layer = [] if blk.cast_batching == "step" else [l.casts for l in blk.linears] + ([blk.attn.casts] if blk.attn else [])
+        for b in blk.pre + per_layer:
+            b.run(alone if rep else None)
+    torch.cuda.synchronize()
+    n, work, ms = alone.summary()["cast_jit"]
+    kernels["cast_jit_without_gemms"] = {"launches": n, "avg_launch_ms": ms / n, "achieved": work / (ms * 1e-3) / 1e9, "unit": "GB/s",
+                                         "frac": work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "in_timed_step": False}
     am = torch.zeros(1, device="cuda")
     if blk.linears:
         # The kurtosis monitor (a diagnostic) over the activation inputs of every linear layer, alone and with
@@ -313,10 +324,65 @@ def main():
                 entry["vendor"] = None
                 entry["vendor_error"] = repr(e)[:200]
             context["shapes"].append(entry)
+    ceilings = None
+    if args.ceilings:
+        # What the part sustains, next to the published peaks the fractions above are taken against.  The matrix
+        # instruction issues every 64 cycles whatever its operands are; the clock it runs at depends on the power the
+        # operand bits draw, so the same loop is timed on four 64 KB operand patterns.
+        gen = torch.Generator(device="cuda"); gen.manual_seed(5)
+        rnd = lambda lo, hi: torch.randint(lo, hi, (65536,), dtype=torch.uint8, device="cuda", generator=gen)
+        sign = lambda: torch.randint(0, 2, (65536,), dtype=torch.uint8, device="cuda", generator=gen) << 7
+        patterns = {"one constant code (1.0)": torch.full((65536,), 0x38, dtype=torch.uint8, device="cuda"),
+                    "codes of small magnitude, random sign (0x20-0x4f)": rnd(0x20, 0x50) | sign(),
+                    "uniformly random finite codes": rnd(0, 0x7F) | sign()}
+        if blk.linears:
+            l0 = blk.linears[0]
+            patterns["the step's own operands (first 32 KB of X~ and of W~ of %s)" % l0.lin.name] = torch.cat(
+                [l0.X.q.reshape(-1)[:32768], l0.W.q.reshape(-1)[:32768]]).contiguous()
+        sink = torch.empty(1024 * 256, device="cuda")
+        ceilings = {"mfma_loop": {}}
+        for name, pat in patterns.items():
+            fog.probe_mfma_rate(pat, 2000, sink)
+            tf, ghz = fog.probe_mfma_rate(pat, 20000, sink)
+            ceilings["mfma_loop"][name] = {"tflops": tf, "frac_of_peak": tf / PEAK_FP8_TFLOPS, "mfma_clock_ghz": ghz}
+        # The attention forward's instruction mix without any memory traffic (see include/fog_probe.h): how far the matrix
+        # cores and the vector ALU overlap on this part, at one to three waves per SIMD.
+        ceilings["attention_loop_ns_per_wave_block"] = {}
+        for wps in (1, 2, 3):
+            t_all, t_mfma, t_valu = (fog.probe_attention_loop(w, wps, 3000, sink) for w in (0, 1, 2))
+            ceilings["attention_loop_ns_per_wave_block"]["%d waves per SIMD" % wps] = {
+                "everything": t_all, "matrix instructions only": t_mfma, "softmax arithmetic only": t_valu,
+                "matrix_core_share_of_everything": t_mfma / t_all}
+        # HBM: the abs-max kernel as a plain read (2 B per element) and a device copy, over buffers that do not fit the caches
+        big = torch.empty(1 << 30, dtype=torch.int16, device="cuda")            # 2 GiB
+        big.zero_()
+        amx = torch.zeros(1, device="cuda")
+        def rate(fn, nbytes, iters=5):
+            fn(); torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                fn()
+            e1.record(); torch.cuda.synchronize()
+            return nbytes * iters / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        ceilings["hbm_read_gbs"] = rate(lambda: fog.amax(big, amx), big.numel() * 2)
+        half = big.numel() // 2
+        ceilings["hbm_copy_gbs"] = rate(lambda: big[half:].copy_(big[:half]), half * 2 * 2)
+        del big
     g = kernels.get("gemm") or kernels.get("attn_fwd")
+    # HBM-side bytes per launch of the dominant kernel: read back from the rocprofv3 summary of this same command under
+    # profiles/ (two --pmc runs, FETCH_SIZE and WRITE_SIZE, scaled by a plain copy; written by paper_2505_20524_amd.profile_summary);
+    # null when the workload has no such summary.
+    from paper_2505_20524_amd import profile_summary
+    traffic = profile_summary.read_gemm_traffic(os.path.join(ROOT, "profiles"), cfg.cid) if "gemm" in kernels else None
+    gemm_alg = None
+    if blk.linears:
+        per = [(l.lin.M * l.lin.K + l.lin.N * l.lin.K + 2 * l.lin.M * l.lin.N) + (l.lin.M * l.lin.N + l.lin.N * l.lin.K + 2 * l.lin.M * l.lin.K)
+               + (l.lin.M * l.lin.N + l.lin.M * l.lin.K + 2 * l.lin.N * l.lin.K) for l in blk.linears]
+        gemm_alg = sum(per) / (3.0 * len(per))      # each operand read once (1 B per element), the bf16 result written once
     roofline = {"bound": "mfma", "kernel": "fp8_gemm_kernel" if "gemm" in kernels else "attn_fwd_kernel",
                 "achieved": g["achieved"], "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": g["frac"],
-                "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(cfg.cid) if "gemm" in kernels else None, "launches_per_step": g["launches_per_step"], "avg_launch_ms": g["avg_launch_ms"]}
+                "traffic": traffic, "launches_per_step": g["launches_per_step"], "avg_launch_ms": g["avg_launch_ms"]}
 
     out = {
         "metric": "FP8 TFLOP/s (block GEMMs fwd+dgrad+wgrad + FP8 causal attention fwd+bwd, casts in the timed step)",
@@ -325,13 +391,15 @@ def main():
         "dtype": "fp8_e4m3_e5m2", "data": "synthetic",
         "config": {"workload": "config %d: %s" % (cfg.cid, cfg.label), "gflop_per_step": blk.flops / 1e9,
                    "cast_batching": args.cast_batching},
-        "frac_of_fp8_peak": value / PEAK_FP8_TFLOPS,
+        "frac_of_fp8_peak": value / PEAK_FP8_TFLOPS, "gemm_algorithmic_bytes_per_launch": gemm_alg,
         "roofline": roofline, "kernels": kernels,
         "delayed_scaling": {"ms_per_step": delayed_ms, "value": blk.flops / (delayed_ms * 1e-3) / 1e12, "unit": "TFLOP/s",
                             "note": "same step with one-pass casts scaled from a 1024-entry abs-max history"},
     }
     if context is not None:
         out["context"] = context
+    if ceilings is not None:
+        out["ceilings"] = ceilings
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))

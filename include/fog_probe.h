@@ -1,0 +1,58 @@
+/*
+ * fog_probe.h -- measurement helpers of the benchmark, exported by the same library as the hot path
+ * (include/fog.h) but NOT part of it: nothing here is called by the kernels or by a training step.
+ * They measure what the GPU itself sustains, so that a kernel's fraction of the published peak can be
+ * read against the fraction a register-resident loop reaches on the same operand bits.
+ */
+#ifndef FOG_PROBE_H_
+#define FOG_PROBE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fog.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Register-resident FP8 matrix-instruction loop: every wave of a grid that fills the chip (one workgroup of
+ * four waves per compute unit) issues `iters` rounds of 16 independent v_mfma_f32_32x32x64_f8f6f4 (E4M3 x E4M3)
+ * on operand fragments it loaded once from `operand_bytes`; nothing but the matrix cores and the register
+ * file is used inside the loop.  The instruction issues every 64 cycles whatever the operands are, so the
+ * rate that comes out is the clock the part sustains under that load: the operand BIT PATTERNS set the
+ * power drawn and with it the clock.
+ *   operand_bytes : DEVICE pointer, 65536 bytes of FP8 codes (the caller chooses the pattern: one constant,
+ *                   codes of small magnitude, uniformly random bytes, ...), 16-byte aligned.
+ *   iters         : rounds per wave (each 16 instructions = 16 * 131072 flop per wave).
+ *   tflops        : HOST pointer, receives the achieved TFLOP/s (HIP events around the launch; the call
+ *                   synchronises the stream).
+ *   mfma_clock_ghz: HOST pointer or NULL, receives 64 cycles * instructions per wave / elapsed time: the clock
+ *                   at which the matrix cores ran if they never idled.
+ *   sink          : DEVICE pointer, 4 bytes per thread of the grid (compute units * 256 threads), receives a
+ *                   checksum so that the loop cannot be optimised away.
+ * Errors: NULL, SHAPE (iters < 1), ALIGN, HIP.
+ */
+fog_status fog_probe_mfma_rate(const uint8_t* operand_bytes, int iters, float* sink, size_t sink_bytes,
+                               double* tflops, double* mfma_clock_ghz, void* stream);
+
+/*
+ * The instruction mix of the attention forward's inner loop with NO memory traffic at all: per key block and wave,
+ * four score products (v_mfma_f32_32x32x64_f8f6f4 on register-resident fragments), the softmax arithmetic on the
+ * lane's 32 scores (max, fused multiply-add, exp2, row-sum add, two packed FP8 converts per four values) and four
+ * P V products.  Timed three ways on a grid of compute units * waves_per_simd workgroups of four waves:
+ *   what = 0 : everything;   what = 1 : the eight matrix instructions only;   what = 2 : the softmax arithmetic only.
+ * If the matrix cores and the vector ALU overlapped perfectly, time(0) would be max(time(1), time(2)); what the part
+ * does with this mix is an upper bound for any attention kernel built from these instructions.
+ *   ns_per_block : HOST pointer, receives nanoseconds per key block and wave, divided by waves_per_simd (the time a SIMD
+ *                  spends per wave-block).   sink : as in fog_probe_mfma_rate, compute units * waves_per_simd * 256 floats.
+ * Errors: NULL, SHAPE (iters < 1, waves_per_simd outside 1..3, what outside 0..2), WORKSPACE (sink too small), HIP.
+ */
+fog_status fog_probe_attention_loop(int what, int waves_per_simd, int iters, float* sink, size_t sink_bytes,
+                                    double* ns_per_block, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FOG_PROBE_H_ */

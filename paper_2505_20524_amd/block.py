@@ -272,10 +272,21 @@ class EventTimer:
         self.spans.append((kind, work, e0, e1, launches))
         self._open = None
 
-    def summary(self):
-        """kind -> (launches, total work, total milliseconds); call after a synchronize."""
+    def summary(self, drop_outliers=False):
+        """kind -> (launches, total work, total milliseconds); call after a synchronize.  drop_outliers: a span that took
+        more than ten times the median of the spans with the same kind and work (a stall of the host or of the box, not of
+        the kernel) is left out, work and time both."""
+        times = [(kind, work, e0.elapsed_time(e1), launches) for kind, work, e0, e1, launches in self.spans]
+        med = {}
+        if drop_outliers:
+            groups = {}
+            for kind, work, ms, _ in times:
+                groups.setdefault((kind, work), []).append(ms)
+            med = {k: sorted(v)[len(v) // 2] for k, v in groups.items()}
         out = {}
-        for kind, work, e0, e1, launches in self.spans:
-            n, w, ms = out.get(kind, (0, 0, 0.0))
-            out[kind] = (n + launches, w + work, ms + e0.elapsed_time(e1))
+        for kind, work, ms, launches in times:
+            if drop_outliers and ms > 10.0 * med[(kind, work)]:
+                continue
+            n, w, t = out.get(kind, (0, 0, 0.0))
+            out[kind] = (n + launches, w + work, t + ms)
         return out

@@ -445,7 +445,9 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
     //   column n = n_cur + wn + 32 j + 8 (r / 4) + 4 (l / 32) + (r % 4)
     // Each 32 x 32 block is scaled, converted to bf16, parked in one of the wave's two LDS staging
     // buffers (alternating, so that the next block is converted while this one is written out) and
-    // stored as 16-byte pieces, four lanes per 64-byte row segment: 32 coalesced stores per lane.
+    // stored as 16-byte pieces, four lanes per 64-byte row segment: 32 coalesced stores per lane.  The stores are
+    // non-temporal: a result of 100 to 235 MB cannot stay in the caches anyway, and as ordinary stores its dirty lines
+    // were written back during whatever kernel came next (the abs-max pass of the next layer ran a third slower).
     if (SPLIT) {
       // The accumulators as they are: float4 number ((w * 16 + 4 i + j) * 4 + qd) * 64 + l of this item's block,
       // i.e. 1 KB per wave and store instruction.  Waited for at once (the next item's prefetch is waited for
@@ -479,7 +481,7 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
             const uint4 v = *reinterpret_cast<const uint4*>(buf + (16 * t + prow) * EPI_STRIDE + 16 * piece);
-            *reinterpret_cast<uint4*>(cbase + (int64_t)(32 * i + 16 * t) * g.ldc + 32 * j) = v;
+            st_nt16(cbase + (int64_t)(32 * i + 16 * t) * g.ldc + 32 * j, v);
           }
         }
       }
@@ -630,7 +632,7 @@ __global__ __launch_bounds__(256) void gemm_split_reduce_kernel(GemmArgs g) {
       const uint4 v = *reinterpret_cast<const uint4*>(blk + row * EPI_STRIDE + 16 * piece);
       uint16_t* dst = g.C + (int64_t)m * g.ldc + n;
       if (g.vec_store && n + 8 <= g.N) {
-        *reinterpret_cast<uint4*>(dst) = v;
+        st_nt16(dst, v);
       } else {
         const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll

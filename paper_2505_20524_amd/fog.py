@@ -52,6 +52,13 @@ SIGNATURES = {
 ATTN_BWD_STATIC_MAX_ROWS = 524288      # FOG_ATTN_BWD_STATIC_MAX_ROWS of the header
 
 
+# measurement helpers of the benchmark (include/fog_probe.h): not part of the hot path
+PROBE_SIGNATURES = {
+    "fog_probe_mfma_rate": (_I, [_P, _I, _P, _SZ, _c.POINTER(_c.c_double), _c.POINTER(_c.c_double), _P]),
+    "fog_probe_attention_loop": (_I, [_I, _I, _I, _P, _SZ, _c.POINTER(_c.c_double), _P]),
+}
+
+
 class FogError(RuntimeError):
     def __init__(self, code, where):
         self.code = code
@@ -67,7 +74,7 @@ def load():
             raise RuntimeError("libfog.so is not built: run `python __graft_entry__.py` (hipcc, gfx950) first; "
                                "there is no fallback path")
         lib = ctypes.CDLL(LIB_PATH)
-        for name, (res, args) in SIGNATURES.items():
+        for name, (res, args) in list(SIGNATURES.items()) + list(PROBE_SIGNATURES.items()):
             fn = getattr(lib, name)
             fn.restype, fn.argtypes = res, args
         _LIB = lib
@@ -249,3 +256,20 @@ def fp8_attn_bwd_static(B, H, S, D, softmax_scale, causal, Q, K, V, sinv_q, sinv
 
 def fp8_attn_workspace(B, H, S, D, is_bwd, H_kv=None):
     return load().fog_fp8_attn_workspace(B, H, H if H_kv is None else H_kv, S, D, int(is_bwd))
+
+
+def probe_mfma_rate(operand_bytes, iters, sink, stream=None):
+    """(TFLOP/s, GHz) of a register-resident FP8 matrix-instruction loop on the given 64 KB of operand codes (fog_probe.h)."""
+    tf, ghz = _c.c_double(0.0), _c.c_double(0.0)
+    _check(load().fog_probe_mfma_rate(_ptr(operand_bytes), iters, _ptr(sink), sink.numel() * sink.element_size(),
+                                      _c.byref(tf), _c.byref(ghz), _stream(stream)), "fog_probe_mfma_rate")
+    return tf.value, ghz.value
+
+
+def probe_attention_loop(what, waves_per_simd, iters, sink, stream=None):
+    """ns a SIMD spends per wave and key block in the memory-free attention inner loop (fog_probe.h); what: 0 all, 1 matrix
+    instructions only, 2 softmax arithmetic only."""
+    ns = _c.c_double(0.0)
+    _check(load().fog_probe_attention_loop(what, waves_per_simd, iters, _ptr(sink), sink.numel() * sink.element_size(),
+                                           _c.byref(ns), _stream(stream)), "fog_probe_attention_loop")
+    return ns.value

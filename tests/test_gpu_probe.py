@@ -1,0 +1,40 @@
+"""GPU: the benchmark's measurement helper (include/fog_probe.h) runs, reports rates that are physically possible and
+rejects bad arguments.  It is not part of the hot path; this only keeps the benchmark's --ceilings leg honest."""
+import ctypes
+
+import pytest
+import torch
+
+from paper_2505_20524_amd import fog
+
+pytestmark = pytest.mark.gpu
+
+
+def test_mfma_rate_probe_reports_a_possible_rate_and_checks_arguments():
+    pat = torch.full((65536,), 0x38, dtype=torch.uint8, device="cuda")
+    sink = torch.empty(1024 * 256, device="cuda")
+    tf, ghz = fog.probe_mfma_rate(pat, 2000, sink)
+    assert 500.0 < tf < 5033.0 * 1.05          # below the published dense-FP8 peak (small margin for clock tolerance), far above a stall
+    assert 0.3 < ghz < 2.6
+    lib = fog.load()
+    st = torch.cuda.current_stream().cuda_stream
+    a, b = ctypes.c_double(0), ctypes.c_double(0)
+    call = lambda p, it, s, sb: lib.fog_probe_mfma_rate(p, it, s, sb, ctypes.byref(a), ctypes.byref(b), st)
+    assert call(None, 10, sink.data_ptr(), sink.numel() * 4) == 1
+    assert call(pat.data_ptr(), 0, sink.data_ptr(), sink.numel() * 4) == 2
+    assert call(pat.data_ptr() + 1, 10, sink.data_ptr(), sink.numel() * 4) == 3
+    assert call(pat.data_ptr(), 10, sink.data_ptr(), 64) == 5
+
+
+def test_attention_loop_probe_orders_its_three_timings():
+    sink = torch.empty(1024 * 256, device="cuda")
+    t_all, t_mfma, t_valu = (fog.probe_attention_loop(w, 2, 500, sink) for w in (0, 1, 2))
+    assert 0 < t_mfma <= t_all * 1.05 and 0 < t_valu <= t_all * 1.05        # a part cannot take longer than the whole
+    assert t_all <= (t_mfma + t_valu) * 1.15                                 # and the whole no longer than the parts in sequence
+    lib = fog.load()
+    ns = ctypes.c_double(0)
+    st = torch.cuda.current_stream().cuda_stream
+    assert lib.fog_probe_attention_loop(0, 4, 10, sink.data_ptr(), sink.numel() * 4, ctypes.byref(ns), st) == 2
+    assert lib.fog_probe_attention_loop(3, 1, 10, sink.data_ptr(), sink.numel() * 4, ctypes.byref(ns), st) == 2
+    assert lib.fog_probe_attention_loop(0, 1, 10, None, 0, ctypes.byref(ns), st) == 1
+    assert lib.fog_probe_attention_loop(0, 2, 10, sink.data_ptr(), 64, ctypes.byref(ns), st) == 5
