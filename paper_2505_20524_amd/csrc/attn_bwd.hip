@@ -321,7 +321,7 @@ __global__ __launch_bounds__(kThreads, MODE == 0 ? 1 : 2) void attn_bwd_dkdv_ker
             if (CLAMP_P) {
               pf[4 * qt + qd] = (int)cvt4_fp8<FOG_E4M3>(pq[0], pq[1], pq[2], pq[3]);
             } else {
-              uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(pq[0], pq[1], 0u, false);
+              uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(pq[0], pq[1], any_u32(), false);
               pf[4 * qt + qd] = (int)__builtin_amdgcn_cvt_pk_fp8_f32(pq[2], pq[3], pk, true);
             }
           }

@@ -240,7 +240,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
           const float e2 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 2], c, shift));
           const float e3 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 3], c, shift));
           l_run += (e0 + e1) + (e2 + e3);
-          uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(e0, e1, 0u, false);
+          uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(e0, e1, any_u32(), false);
           pf[4 * kt + qd] = (int)__builtin_amdgcn_cvt_pk_fp8_f32(e2, e3, pk, true);
         }
       }

@@ -25,12 +25,20 @@ FOG_DEVICE uint32_t f32_to_bf16(float f) {
 }
 FOG_DEVICE uint32_t pack_bf16x2(float lo, float hi) { return f32_to_bf16(lo) | (f32_to_bf16(hi) << 16); }
 
+// A register whose contents do not matter.  The packed FP8 converts write one half of their destination and keep the
+// other; a dword that both halves of are about to be written needs no initial value, and a literal 0 would cost a move.
+FOG_DEVICE uint32_t any_u32() {
+  uint32_t r;
+  asm volatile("" : "=v"(r));
+  return r;
+}
+
 // Saturating round-to-nearest-even cast of four floats to one dword of FP8 codes (byte i <- v_i).
 // The hardware convert rounds to nearest even but turns overflow into NaN / infinity, so the
 // magnitude is clamped to the largest finite value first.
 template <int FMT>
 FOG_DEVICE uint32_t cvt4_fp8(float a, float b, float c, float d) {
-  uint32_t r = 0;
+  uint32_t r = any_u32();
   if (FMT == FOG_E4M3) {
     const float mx = 448.0f;
     a = __builtin_amdgcn_fmed3f(a, -mx, mx); b = __builtin_amdgcn_fmed3f(b, -mx, mx);

@@ -76,6 +76,20 @@ def check_bf16(y_bits, oracle64, rel=REL, what="", max_flip_frac=0.02, slack=Non
     return dict(max_norm_err=float(err), flip_frac=flips, max_steps=worst)
 
 
+def check_gemm_elementwise(y_bits, oracle64, absdot64, what=""):
+    """Element-wise companion of the tensor-normalised gate, for GEMM outputs: every element, however small against the
+    tensor's maximum, must lie within half a bf16 step of its own oracle value plus what the accumulation can lose on THAT
+    element: 2^-12 of sum_k |a||b| (the matrix instruction keeps 13 places below the largest product of a group of eight;
+    binary32 adds of the group sums lose far less).  absdot64 = sinv_a sinv_b (|decode(A)| x |decode(B)|)."""
+    oracle64 = np.asarray(oracle64, dtype=np.float64)
+    y = bf16.bits_to_f64(y_bits)
+    tol = 2.0 ** -12 * np.asarray(absdot64, dtype=np.float64)
+    lo = bf16.f64_round(oracle64 - tol)
+    hi = bf16.f64_round(oracle64 + tol)
+    bad = (y < lo) | (y > hi)
+    assert not bad.any(), "%s: %d of %d elements outside their own half-step + accumulation bound" % (what, int(bad.sum()), bad.size)
+
+
 STATS = []     # one line per attention check: printed by the terminal summary of a GPU run
 
 # Bounds of the four statistics, frozen from measurement over every attention check of the GPU suite (290 checked

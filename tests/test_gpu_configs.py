@@ -20,7 +20,7 @@ import torch
 from oracle import attention, bf16, fp8, gemm, scaling
 from paper_2505_20524_amd import block, fog, synth
 import mfma_model
-from parity import check_attention, check_bf16, dev, fscalar, host_u16
+from parity import check_attention, check_bf16, check_gemm_elementwise, dev, fscalar, host_u16
 
 pytestmark = pytest.mark.gpu
 
@@ -174,3 +174,5 @@ def test_config1_end_to_end_on_its_own_tensors():
             assert np.array_equal(cst.q.cpu().numpy(), want), "%s bytes (%s)" % (name, route)
         stats = check_bf16(host_u16(Y), ref, what="config 1 Y (%s)" % route)
         assert stats["max_steps"] <= 1
+        mag = np.float64(ora["X"][3]) * np.float64(ora["W"][3]) * (np.abs(fp8.decode(ora["X"][0], fp8.E4M3)) @ np.abs(fp8.decode(ora["W"][0], fp8.E4M3)).T)
+        check_gemm_elementwise(host_u16(Y), ref, mag, what="config 1 Y (%s)" % route)
