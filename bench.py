@@ -258,12 +258,13 @@ def main():
     # the kernel gathering the contraction index with the transposing LDS read.  Over the activations and
     # output gradients of every linear layer (2 B read + 2 B written per element).
     if blk.linears and not blk.linears[0].transposed_wgrad:
-        big = max(l.X.x.numel() for l in blk.linears)
-        big = max(big, max(l.dY.x.numel() for l in blk.linears))
+        big = max(c.x.numel() for l in blk.linears for c in (l.X, l.dY) if c is not None)
         qT_store = torch.empty(big, dtype=torch.uint8, device="cuda")
         jobs = []
         for l in blk.linears:
             for c in (l.X, l.dY):
+                if c is None:
+                    continue
                 rows, cols = c.x.shape
                 qT = qT_store[: rows * cols].view(cols, rows)
                 jobs.append((4 * rows * cols, lambda c=c, qT=qT: fog.quantize(c.x, c.fmt, c.scale, q=c.q, qT=qT)))
@@ -377,15 +378,23 @@ def main():
     traffic = profile_summary.read_gemm_traffic(os.path.join(ROOT, "profiles"), cfg.cid) if "gemm" in kernels else None
     gemm_alg = None
     if blk.linears:
-        per = [(l.lin.M * l.lin.K + l.lin.N * l.lin.K + 2 * l.lin.M * l.lin.N) + (l.lin.M * l.lin.N + l.lin.N * l.lin.K + 2 * l.lin.M * l.lin.K)
-               + (l.lin.M * l.lin.N + l.lin.M * l.lin.K + 2 * l.lin.N * l.lin.K) for l in blk.linears]
-        gemm_alg = sum(per) / (3.0 * len(per))      # each operand read once (1 B per element), the bf16 result written once
+        # each operand read once (1 B per element), the bf16 result written once; forward-only layers launch one product
+        total, launches = 0, 0
+        for l in blk.linears:
+            M, N, K = l.lin.M, l.lin.N, l.lin.K
+            total += M * K + N * K + 2 * M * N
+            launches += 1
+            if l.backward:
+                total += (M * N + N * K + 2 * M * K) + (M * N + M * K + 2 * N * K)
+                launches += 2
+        gemm_alg = total / float(launches)
     roofline = {"bound": "mfma", "kernel": "fp8_gemm_kernel" if "gemm" in kernels else "attn_fwd_kernel",
                 "achieved": g["achieved"], "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": g["frac"],
                 "traffic": traffic, "launches_per_step": g["launches_per_step"], "avg_launch_ms": g["avg_launch_ms"]}
 
     out = {
-        "metric": "FP8 TFLOP/s (block GEMMs fwd+dgrad+wgrad + FP8 causal attention fwd+bwd, casts in the timed step)",
+        "metric": "FP8 TFLOP/s (block GEMMs fwd+dgrad+wgrad + FP8 causal attention fwd+bwd, casts in the timed step)" if cfg.backward
+                  else "FP8 TFLOP/s (forward GEMM, casts in the timed step)",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8_e4m3_e5m2", "data": "synthetic",

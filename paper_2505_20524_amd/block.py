@@ -115,14 +115,22 @@ class LinearStep:
     copies (fused cast + transpose) and dW is an NT product on them, the arrangement for hardware without a
     transposing read; same results bit for bit."""
 
-    def __init__(self, lin, tensors, transposed_wgrad=False):
+    def __init__(self, lin, tensors, transposed_wgrad=False, backward=True):
         self.lin = lin
         self.transposed_wgrad = transposed_wgrad
+        self.backward = backward          # False: the forward product only (config 1), X and W are the only casts
         M, N, K = lin.M, lin.N, lin.K
         self.X = Cast(_dev_bits(tensors["X"]), E4M3, transpose=transposed_wgrad)
         self.W = Cast(_dev_bits(tensors["W"]), E4M3, transpose=False)
-        self.dY = Cast(_dev_bits(tensors["dY"]), E5M2, transpose=transposed_wgrad)
         self.Y = torch.empty((M, N), dtype=torch.int16, device="cuda")
+        if not backward:
+            self.dY = self.dX = self.dW = None
+            self.flops = 2 * M * N * K
+            self.casts = CastBatch([self.X, self.W])
+            need = fog.fp8_gemm_workspace(fog.NT, M, N, K)
+            self.gemm_ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+            return
+        self.dY = Cast(_dev_bits(tensors["dY"]), E5M2, transpose=transposed_wgrad)
         self.dX = torch.empty((M, K), dtype=torch.int16, device="cuda")
         self.dW = torch.empty((N, K), dtype=torch.int16, device="cuda")
         self.flops = 3 * 2 * M * N * K
@@ -142,11 +150,16 @@ class LinearStep:
         M, N, K = lin.M, lin.N, lin.K
         # The three products are launched back to back and bracketed by ONE event pair (an event between two
         # launches costs a gap of several microseconds on the stream): the pair's time is that of three launches.
+        n_gemm = 3 if self.backward else 1
         if timer:
-            timer.begin("gemm", 3 * 2 * M * N * K, launches=3)
+            timer.begin("gemm", n_gemm * 2 * M * N * K, launches=n_gemm)
         # forward  Y = X~ W~^T
         ws = self.gemm_ws
         fog.fp8_gemm(fog.NT, M, N, K, self.X.q, E4M3, self.X.sinv, self.W.q, E4M3, self.W.sinv, self.Y, workspace=ws)
+        if not self.backward:
+            if timer:
+                timer.end()
+            return
         # data gradient  dX = dY~ W~  (W~ is [N, K]: the contraction index N is its row index)
         fog.fp8_gemm(fog.NN, M, K, N, self.dY.q, E5M2, self.dY.sinv, self.W.q, E4M3, self.W.sinv, self.dX, workspace=ws)
         # weight gradient  dW = dY~^T X~  (contraction over the M tokens, the row index of both operands)
@@ -215,13 +228,14 @@ class Block:
         self.cast_batching = cast_batching
         # config 2 is stated with the fused cast + transpose for the weight gradient; the block configs leave the
         # arrangement open and use the TN product on the row-major casts
-        self.linears = [LinearStep(lin, synth.linear_tensors(cfg, i), transposed_wgrad=(cfg.cid == 2))
+        self.linears = [LinearStep(lin, synth.linear_tensors(cfg, i, want=("X", "W", "dY") if cfg.backward else ("X", "W")),
+                                   transposed_wgrad=(cfg.cid == 2), backward=cfg.backward)
                         for i, lin in enumerate(cfg.linears)]
         self.attn = AttentionStep(cfg.attn, synth.attention_tensors(cfg)) if cfg.attn is not None else None
         self.flops = sum(l.flops for l in self.linears) + (self.attn.flops if self.attn else 0)
         self.pre = []          # batches cast at the start of the step
         if cast_batching == "step":
-            casts = [c for l in self.linears for c in (l.X, l.W, l.dY)]
+            casts = [c for l in self.linears for c in (l.X, l.W, l.dY) if c is not None]
             if self.attn:
                 casts += [self.attn.c[name] for name in ("Q", "K", "V", "dO")]
             self.pre = [CastBatch(casts[i:i + fog.CAST_BATCH_MAX]) for i in range(0, len(casts), fog.CAST_BATCH_MAX)]
@@ -229,7 +243,7 @@ class Block:
             ws = [l.W for l in self.linears]
             self.pre = [CastBatch(ws[i:i + fog.CAST_BATCH_MAX]) for i in range(0, len(ws), fog.CAST_BATCH_MAX)]
             for l in self.linears:
-                l.casts = CastBatch([l.X, l.dY])
+                l.casts = CastBatch([c for c in (l.X, l.dY) if c is not None])
         elif cast_batching != "layer":
             raise ValueError(cast_batching)
 
