@@ -494,7 +494,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(BwdArgs a) {
     }
   if (AMAX) {
     ds_max = wave_max_f32(ds_max) / rho_ds;   // the running maximum was taken on rho_ds dS
-    if (l == 0 && ds_max > 0.0f) atomicMax(a.amax_ds, __float_as_uint(ds_max));
+    // only a wave that would raise the maximum pays for the atomic (a stale read can only be too small)
+    if (l == 0 && ds_max > 0.0f && __float_as_uint(ds_max) > __hip_atomic_load(a.amax_ds, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(a.amax_ds, __float_as_uint(ds_max));
   }
 }
 

@@ -50,6 +50,13 @@ struct FwdArgs {
 };
 
 FOG_DEVICE float lane_xor32(float v) { return __shfl_xor(v, 32, 64); }
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+// max of a lane's value and that of lane ^ 32 (both lanes get it), exchanged inside the vector ALU
+// (v_permlane32_swap: no trip through LDS in the middle of the softmax's dependency chain)
+FOG_DEVICE float pair_max32(float v) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 
 // LDS chunk swizzles (16-byte chunks inside a 128-byte row), applied by choosing which global chunk
 // a lane of the direct load fetches.  K rows are read 32 consecutive rows at a time (same chunk):
@@ -78,10 +85,19 @@ template <bool CAUSAL>
 __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
   __shared__ __attribute__((aligned(1024))) uint8_t smem[NSTAGE * STAGE];
   const int bh = blockIdx.x % a.BH;
-  const int qb = a.nqb - 1 - blockIdx.x / a.BH;   // long rows (late query blocks) are launched first
+  const int pr = blockIdx.x / a.BH;
   const int t = threadIdx.x, w = t >> 6, l = t & 63, g = l >> 5;
   const int S = a.S;
   const uint8_t* Qh = a.Q + (int64_t)bh * S * HD;
+  // A workgroup takes a PAIR of query blocks, block nqb - 1 - pr and then block pr: under the causal mask
+  // the two together need 2 nqb + 2 key blocks whatever pr is, so every workgroup of a launch does the
+  // same amount of work and the fixed cost of starting one is paid once per pair.
+  for (int part = 0; part < 2; ++part) {
+  const int qb = part == 0 ? a.nqb - 1 - pr : pr;
+  if (part == 1) {
+    if (qb >= a.nqb - 1 - pr) break;   // odd number of query blocks: the middle one has no partner
+    __syncthreads();                   // every wave has finished reading the ring of the first block
+  }
 
   const int q0 = qb * BQ + 32 * w;           // first query of this wave
   const int q = q0 + (l & 31);
@@ -209,14 +225,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
             if (key > q) sc[kt][r] = -INFINITY;
           }
       }
-      float bm = fmaxf(fmaxf(sc[0][0], sc[0][1]), sc[1][0]);
+      float cm[4];   // four independent chains of eight scores (one chain of 32 is latency-bound)
 #pragma unroll
-      for (int r = 2; r < 16; r += 2) bm = fmaxf(fmaxf(bm, sc[0][r]), sc[0][r + 1]);
-#pragma unroll
-      for (int r = 1; r < 15; r += 2) bm = fmaxf(fmaxf(bm, sc[1][r]), sc[1][r + 1]);
-      bm = fmaxf(bm, sc[1][15]);
+      for (int ch = 0; ch < 4; ++ch) {
+        const v16f& x = sc[ch >> 1];
+        const int b = 8 * (ch & 1);
+        float m = fmaxf(fmaxf(x[b], x[b + 1]), x[b + 2]);
+        m = fmaxf(fmaxf(m, x[b + 3]), x[b + 4]);
+        m = fmaxf(fmaxf(m, x[b + 5]), x[b + 6]);
+        cm[ch] = fmaxf(m, x[b + 7]);
+      }
+      float bm = fmaxf(fmaxf(fmaxf(cm[0], cm[1]), cm[2]), cm[3]);
       raw_max = fmaxf(raw_max, bm);
-      bm = fmaxf(bm, lane_xor32(bm));
+      bm = pair_max32(bm);
       const float m_new = fmaxf(m_run, ceilf(bm * c));
       if (__any(m_new != m_run)) {
         const float alpha = exp2f(m_run - m_new);   // exact power of two (0 on the first block)
@@ -264,9 +285,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
     block(kb, sc, sn);
     if (kb + 1 < nkb) block(kb + 1, sn, sc);
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the ring is reused or the workgroup retires
 
-  if (!wave_on) return;
+  if (!wave_on) continue;
   // ---- epilogue: O = sinv_v O^T / (rho_p l);  lse = m + log2 l  (l_run holds rho_p l, split over two lanes)
   const float l_tot = l_run + lane_xor32(l_run);
   const float scale_o = (*a.sinv_v) / l_tot;
@@ -285,8 +306,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
     float rm = fmaxf(raw_max, lane_xor32(raw_max));
     float pm = exp2f(rm * c - m_run);                 // largest p of this row, in (1/2, 1]
     pm = wave_max_f32(pm);
-    if (l == 0) atomicMax(a.amax_p, __float_as_uint(pm));
+    // every wave of the launch ends here: only a wave that would raise the maximum pays for the atomic (a stale read can
+    // only be too small, which costs an atomic that changes nothing)
+    if (l == 0 && __float_as_uint(pm) > __hip_atomic_load(a.amax_p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(a.amax_p, __float_as_uint(pm));
   }
+  }   // part
 }
 
 __global__ void zero_u32(uint32_t* p) { *p = 0u; }
@@ -323,7 +347,7 @@ extern "C" fog_status fog_fp8_attn_fwd(int B, int H, int H_kv, int S, int D, flo
   a.softmax_scale = softmax_scale;
   a.BH = B * H; a.S = S; a.nqb = (S + BQ - 1) / BQ;
   a.G = H / H_kv;
-  const int grid = a.BH * a.nqb;
+  const int grid = a.BH * ((a.nqb + 1) / 2);   // one workgroup per pair of query blocks
   if (causal) attn_fwd_kernel<true><<<grid, kThreads, 0, s>>>(a);
   else        attn_fwd_kernel<false><<<grid, kThreads, 0, s>>>(a);
   return fog_launch_status();
