@@ -318,6 +318,10 @@ def main():
             entry = {"M": M, "N": N, "K": K}
             ms = timed(lambda: fog.fp8_gemm(fog.NT, M, N, K, l.X.q, fog.E4M3, one, l.W.q, fog.E4M3, one, l.Y))
             entry["this_library"] = 2.0 * M * N * K / ms / 1e9
+            if M % 256 == 0 and N % 256 == 0:
+                # the same launch with every tile's epilogue left out (measurement helper): what hiding the epilogues could gain
+                ms = timed(lambda: fog.probe_gemm_products_only(M, N, K, l.X.q, one, l.W.q, one, l.Y))
+                entry["this_library_products_only"] = 2.0 * M * N * K / ms / 1e9
             try:
                 ms = timed(lambda: torch._scaled_mm(a8, b8.t(), scale_a=one, scale_b=one, out_dtype=torch.bfloat16))
                 entry["vendor"] = 2.0 * M * N * K / ms / 1e9
@@ -347,13 +351,21 @@ def main():
             tf, ghz = fog.probe_mfma_rate(pat, 20000, sink)
             ceilings["mfma_loop"][name] = {"tflops": tf, "frac_of_peak": tf / PEAK_FP8_TFLOPS, "mfma_clock_ghz": ghz}
         # The attention forward's instruction mix without any memory traffic (see include/fog_probe.h): how far the matrix
-        # cores and the vector ALU overlap on this part, at one to three waves per SIMD.
+        # cores and the vector ALU overlap on this part, at one and two waves per SIMD.
         ceilings["attention_loop_ns_per_wave_block"] = {}
-        for wps in (1, 2, 3):
+        for wps in (1, 2):
             t_all, t_mfma, t_valu = (fog.probe_attention_loop(w, wps, 3000, sink) for w in (0, 1, 2))
             ceilings["attention_loop_ns_per_wave_block"]["%d waves per SIMD" % wps] = {
                 "everything": t_all, "matrix instructions only": t_mfma, "softmax arithmetic only": t_valu,
                 "matrix_core_share_of_everything": t_mfma / t_all}
+        # What one matrix instruction takes from the vector ALU of its own wave: shader cycles per slot (one matrix instruction
+        # followed by n vector operations, order pinned), and the same vector operations alone.
+        ceilings["cycles_per_mfma_slot"] = {}
+        for op, name in ((0, "v_fma_f32"), (1, "v_exp_f32"), (2, "v_cvt_pk_fp8_f32"), (3, "softmax quarter group (fma, exp, add, max3 | convert)")):
+            ceilings["cycles_per_mfma_slot"][name] = {
+                "vector_ops": [0, 4, 8, 16, 32],
+                "with_matrix_instruction": [fog.probe_mfma_coissue(op, n, True, 2000, sink) for n in (0, 4, 8, 16, 32)],
+                "vector_ops_alone": [fog.probe_mfma_coissue(op, n, False, 2000, sink) for n in (0, 4, 8, 16, 32)]}
         # HBM: the abs-max kernel as a plain read (2 B per element) and a device copy, over buffers that do not fit the caches
         big = torch.empty(1 << 30, dtype=torch.int16, device="cuda")            # 2 GiB
         big.zero_()

@@ -47,10 +47,38 @@ fog_status fog_probe_mfma_rate(const uint8_t* operand_bytes, int iters, float* s
  * does with this mix is an upper bound for any attention kernel built from these instructions.
  *   ns_per_block : HOST pointer, receives nanoseconds per key block and wave, divided by waves_per_simd (the time a SIMD
  *                  spends per wave-block).   sink : as in fog_probe_mfma_rate, compute units * waves_per_simd * 256 floats.
- * Errors: NULL, SHAPE (iters < 1, waves_per_simd outside 1..3, what outside 0..2), WORKSPACE (sink too small), HIP.
+ * Errors: NULL, SHAPE (iters < 1, waves_per_simd outside 1..2, what outside 0..2), WORKSPACE (sink too small), HIP.
  */
 fog_status fog_probe_attention_loop(int what, int waves_per_simd, int iters, float* sink, size_t sink_bytes,
                                     double* ns_per_block, void* stream);
+
+/*
+ * What a matrix instruction costs the vector ALU of its own wave.  One wave per SIMD; per trip eight independent
+ * v_mfma_f32_32x32x64_f8f6f4, each followed, in pinned program order, by `vector_ops` vector operations on registers
+ * of their own:
+ *   op = 0 : v_fma_f32;  1 : v_exp_f32;  2 : v_cvt_pk_fp8_f32;
+ *   op = 3 : a quarter of a softmax group (fma, exp, add, and a max3 or a packed convert in turn): 4 per matrix
+ *            instruction is the ratio of the attention forward at head dimension 128.
+ * with_mfma = 0 times the vector operations alone.  The result is shader cycles (the wave's cycle counter, averaged
+ * over the workgroups) per slot = one matrix instruction plus its vector operations: 64 while the vector work hides
+ * under the matrix instruction, then a line whose intercept is what the matrix instruction takes from the vector ALU.
+ *   vector_ops : 0, 4, 8, 16 or 32.      cycles_per_slot : HOST pointer.
+ *   sink : DEVICE pointer, 8-byte aligned, compute units * 256 floats + compute units * 8 bytes.
+ * Errors: NULL, SHAPE, ALIGN, WORKSPACE, HIP.  Synchronises the stream.
+ */
+fog_status fog_probe_mfma_coissue(int op, int vector_ops, int with_mfma, int iters, float* sink, size_t sink_bytes,
+                                  double* cycles_per_slot, void* stream);
+
+/*
+ * The NT product of fog_fp8_gemm (E4M3 x E4M3) with the epilogue of every tile left out: the same kernel, the same
+ * operand loads and matrix instructions, but no tile is scaled, converted, staged or stored (C stays untouched).
+ * Timed next to fog_fp8_gemm on the same operands it shows what the epilogues cost a launch, which is what a kernel
+ * that hid them completely under the next tile's products could gain.  Asynchronous on `stream`, like fog_fp8_gemm.
+ *   M, N multiples of 256, K of 16; pointers as for fog_fp8_gemm with C 16-byte aligned and ldc a multiple of 8.
+ * Errors: SHAPE, NULL, UNSUPPORTED (sizes the fast path does not cover), ALIGN, HIP.
+ */
+fog_status fog_probe_gemm_products_only(int64_t M, int64_t N, int64_t K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
+                                        const float* scale_inv_A, const float* scale_inv_B, void* C_bf16, int64_t ldc, void* stream);
 
 #ifdef __cplusplus
 }

@@ -223,9 +223,11 @@ class Block:
       "step"    -- every tensor of the step in one call at its start.  The benchmark can do that because every product
                    has its own resident inputs; a training step can only for tensors that exist at that point."""
 
-    def __init__(self, cfg, cast_batching="layer"):
+    def __init__(self, cfg, cast_batching="layer", attention_at=None):
         self.cfg = cfg
         self.cast_batching = cast_batching
+        # position of attention among the linear layers (index of the layer it runs before; None = after the last)
+        self.attention_at = attention_at
         # config 2 is stated with the fused cast + transpose for the weight gradient; the block configs leave the
         # arrangement open and use the TN product on the row-major casts
         self.linears = [LinearStep(lin, synth.linear_tensors(cfg, i, want=("X", "W", "dY") if cfg.backward else ("X", "W")),
@@ -252,14 +254,18 @@ class Block:
         for b in self.pre:
             b.run(timer, delayed)
         per_layer = self.cast_batching != "step"
-        for l in self.linears:
-            if per_layer:
-                l.casts.run(timer, delayed)
-            l.compute(timer)
-        if self.attn:
+        def attention():
             if per_layer:
                 self.attn.casts.run(timer, delayed)
             self.attn.compute(timer)
+        for i, l in enumerate(self.linears):
+            if self.attn and self.attention_at == i:
+                attention()
+            if per_layer:
+                l.casts.run(timer, delayed)
+            l.compute(timer)
+        if self.attn and (self.attention_at is None or self.attention_at >= len(self.linears)):
+            attention()
 
 
 class EventTimer:

@@ -38,6 +38,7 @@
 // atomics); the sums differ from the unsplit kernel's only in the order of binary32 additions.
 #include "common.h"
 #include "launch.h"
+#include "../../include/fog_probe.h"
 
 namespace {
 
@@ -258,7 +259,9 @@ FOG_DEVICE uint32_t cvt_pk_bf16(float lo, float hi) {
 
 // SPLIT: the work items are (tile, contraction chunk) pairs and the epilogue leaves the binary32
 // accumulators in the workspace instead of writing C (see the header comment).
-template <int LAYOUT, int FA, int FB, bool SPLIT>
+// PRODUCTS_ONLY (measurement helper fog_probe_gemm_products_only, never the product path): interior tiles skip
+// their epilogue, so that the launch shows what the conversion, staging and stores of the finished tiles cost.
+template <int LAYOUT, int FA, int FB, bool SPLIT, bool PRODUCTS_ONLY = false>
 __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   constexpr bool A_KM = LAYOUT == FOG_TN;
@@ -464,6 +467,14 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
       continue;
     }
     const bool fast = g.vec_store != 0 && m_cur + BM <= g.M && n_cur + BN <= g.N;
+    if (PRODUCTS_ONLY && fast) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) asm volatile("" ::"v"(acc[i][j]));   // the products stay, their results go nowhere
+      stores_pending = false;
+      continue;
+    }
     const int prow = l >> 2, piece = l & 3;   // this lane's row (+ 16 t) and 16-byte piece of a staged block
     if (fast) {
       uint16_t* cbase = g.C + (int64_t)(m_cur + wm + prow) * g.ldc + (n_cur + wn + 8 * piece);
@@ -732,4 +743,33 @@ extern "C" fog_status fog_fp8_gemm(fog_layout layout, int64_t M, int64_t N, int6
     case FOG_NN: return launch_fmt<FOG_NN>(g, fmtA, fmtB, s);
     default: return launch_fmt<FOG_TN>(g, fmtA, fmtB, s);
   }
+}
+
+// Measurement helper (include/fog_probe.h): the NT product of E4M3 operands with the epilogue of every tile left out.
+extern "C" fog_status fog_probe_gemm_products_only(int64_t M, int64_t N, int64_t K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
+                                                   const float* scale_inv_A, const float* scale_inv_B, void* C_bf16, int64_t ldc, void* stream) {
+  if (M <= 0 || N <= 0 || K <= 0) return FOG_ERR_SHAPE;
+  if (!A || !B || !C_bf16 || !scale_inv_A || !scale_inv_B) return FOG_ERR_NULL;
+  if (M % BM != 0 || N % BN != 0 || K % 16 != 0 || M > 0x7FFFFF00 || N > 0x7FFFFF00 || K > 0x7FFFFF00) return FOG_ERR_UNSUPPORTED;
+  if (lda < K || ldb < K || ldc < N) return FOG_ERR_SHAPE;
+  if (!aligned(A, 16) || !aligned(B, 16) || lda % 16 != 0 || ldb % 16 != 0 || !aligned(C_bf16, 16) || ldc % 8 != 0) return FOG_ERR_ALIGN;
+  GemmArgs g;
+  g.A = A; g.B = B; g.C = reinterpret_cast<uint16_t*>(C_bf16);
+  g.sinv_a = scale_inv_A; g.sinv_b = scale_inv_B;
+  g.lda = lda; g.ldb = ldb; g.ldc = ldc;
+  g.M = (int)M; g.N = (int)N; g.K = (int)K;
+  g.tiles_m = (int)(M / BM); g.tiles_n = (int)(N / BN);
+  g.vec_store = 1;
+  const int64_t a_span = (M - 1) * lda + K, b_span = (N - 1) * ldb + K;
+  if (a_span >= 0x7FFFFFFF || b_span >= 0x7FFFFFFF) return FOG_ERR_UNSUPPORTED;
+  g.a_bytes = (uint32_t)a_span; g.b_bytes = (uint32_t)b_span;
+  g.splits = 1; g.k_chunk = (int)K; g.partial = nullptr;
+  static bool configured = false;
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(fp8_gemm_kernel<FOG_NT, 0, 0, false, true>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+      return FOG_ERR_HIP;
+    configured = true;
+  }
+  fp8_gemm_kernel<FOG_NT, 0, 0, false, true><<<persistent_grid((int64_t)g.tiles_m * g.tiles_n), kThreads, LDS_BYTES, (hipStream_t)stream>>>(g);
+  return fog_launch_status();
 }

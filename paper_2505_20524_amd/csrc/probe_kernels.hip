@@ -46,8 +46,59 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(const uint8_t* __restric
 }
 
 // WHAT 0: score products, softmax arithmetic, P V products; 1: the products only; 2: the arithmetic only.
+// One key block; SC holds this block's scores, SN receives the next block's (the caller swaps them: no copies).
 template <int WHAT>
-__global__ __launch_bounds__(256) void attention_loop_kernel(float* __restrict__ sink, int iters) {
+__device__ __forceinline__ void attention_block(v8i* kf, const v8i* qf, const v8i* vf, const v16f& zero16, v16f* sc, v16f* sn,
+                                                v16f* o, float& l_run, float& m_run, float c, int it) {
+  if (WHAT != 2) {   // the next block's scores
+    asm volatile("" : "+v"(kf[0]), "+v"(kf[1]));   // the fragments "change" every block: the products stay in the loop
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      sn[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf[kt], qf[0], zero16, 0, 0, 0, 0, 0, 0);
+      sn[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf[kt], qf[1], sn[kt], 0, 0, 0, 0, 0, 0);
+    }
+  }
+  v8i pf;
+  if (WHAT != 1) {   // this block's softmax arithmetic
+    float cm[4];
+#pragma unroll
+    for (int ch = 0; ch < 4; ++ch) {
+      const v16f& x = sc[ch >> 1];
+      const int b = 8 * (ch & 1);
+      float m = fmaxf(fmaxf(x[b], x[b + 1]), x[b + 2]);
+      m = fmaxf(fmaxf(m, x[b + 3]), x[b + 4]);
+      m = fmaxf(fmaxf(m, x[b + 5]), x[b + 6]);
+      cm[ch] = fmaxf(m, x[b + 7]);
+    }
+    m_run = fmaxf(m_run, fmaxf(fmaxf(fmaxf(cm[0], cm[1]), cm[2]), cm[3]) * c);
+    const float shift = 3.0f - m_run;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 0], c, shift));
+        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 1], c, shift));
+        const float e2 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 2], c, shift));
+        const float e3 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 3], c, shift));
+        l_run += (e0 + e1) + (e2 + e3);
+        const uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(e0, e1, any_u32(), false);
+        pf[4 * kt + qd] = (int)__builtin_amdgcn_cvt_pk_fp8_f32(e2, e3, pk, true);
+      }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pf[i] = 0x38383838 + it;
+  }
+  if (WHAT != 2) {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) o[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vf[d], pf, o[d], 0, 0, 0, 0, 0, 0);
+  } else {
+    asm volatile("" ::"v"(pf));
+    sn[0][it & 15] += 1e-3f;   // keeps the arithmetic loop-variant
+  }
+}
+
+template <int WHAT>
+__global__ __launch_bounds__(256, 2) void attention_loop_kernel(float* __restrict__ sink, int iters) {
   const int t = threadIdx.x;
   v8i kf[2], qf[2], vf[4];
 #pragma unroll
@@ -68,54 +119,84 @@ __global__ __launch_bounds__(256) void attention_loop_kernel(float* __restrict__
   }
   float l_run = 0.0f, m_run = 0.0f;
   const float c = 1e-6f;
-  for (int it = 0; it < iters; ++it) {
-    if (WHAT != 2) {   // the next block's scores
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-        sn[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf[kt], qf[0], zero16, 0, 0, 0, 0, 0, 0);
-        sn[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf[kt], qf[1], sn[kt], 0, 0, 0, 0, 0, 0);
-      }
-    }
-    v8i pf;
-    if (WHAT != 1) {   // this block's softmax arithmetic
-      float bm = fmaxf(fmaxf(sc[0][0], sc[0][1]), sc[1][0]);
-#pragma unroll
-      for (int r = 2; r < 16; r += 2) bm = fmaxf(fmaxf(bm, sc[0][r]), sc[0][r + 1]);
-#pragma unroll
-      for (int r = 1; r < 15; r += 2) bm = fmaxf(fmaxf(bm, sc[1][r]), sc[1][r + 1]);
-      m_run = fmaxf(m_run, bm * c);
-      const float shift = 3.0f - m_run;
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) {
-          const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 0], c, shift));
-          const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 1], c, shift));
-          const float e2 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 2], c, shift));
-          const float e3 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 3], c, shift));
-          l_run += (e0 + e1) + (e2 + e3);
-          const uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(e0, e1, 0u, false);
-          pf[4 * kt + qd] = (int)__builtin_amdgcn_cvt_pk_fp8_f32(e2, e3, pk, true);
-        }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) pf[i] = __float_as_int(sc[i >> 2][i & 3]);
-    }
-    if (WHAT != 2) {
-#pragma unroll
-      for (int d = 0; d < 4; ++d) o[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vf[d], pf, o[d], 0, 0, 0, 0, 0, 0);
-      sc[0] = sn[0]; sc[1] = sn[1];
-    } else {
-      asm volatile("" ::"v"(pf));
-      sc[0][it & 15] += 1e-3f;   // keeps the arithmetic loop-variant
-    }
+  for (int it = 0; it < iters; it += 2) {   // two blocks per trip: the score registers swap roles
+    attention_block<WHAT>(kf, qf, vf, zero16, sc, sn, o, l_run, m_run, c, it);
+    attention_block<WHAT>(kf, qf, vf, zero16, sn, sc, o, l_run, m_run, c, it + 1);
   }
   float s = l_run + m_run;
 #pragma unroll
   for (int d = 0; d < 4; ++d)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s += o[d][r];
+    for (int r = 0; r < 16; ++r) s += o[d][r] + sc[d & 1][r] + sn[d & 1][r];
   sink[(size_t)blockIdx.x * 256 + t] = s;
+}
+
+// One wave per SIMD; per trip eight independent matrix instructions, each followed (order pinned) by NV vector
+// operations on registers of their own.  OP 0: v_fma_f32, 1: v_exp_f32, 2: v_cvt_pk_fp8_f32, 3: a quarter of a softmax
+// group (fma, exp, add, and a max3 or a packed convert in turn).  MFMA false: the vector operations alone.
+template <int OP, int NV, bool MFMA>
+__global__ __launch_bounds__(256) void coissue_kernel(float* __restrict__ sink, int iters, long long* __restrict__ cycles) {
+  const int t = threadIdx.x;
+  v8i a[2], b[2];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[0][i] = 0x30313233 + t * (i + 1); a[1][i] = 0x2c2d2e2f + t * (i + 3);
+    b[0][i] = 0x34353637 ^ (t << i); b[1][i] = 0x31323334 ^ (t << (i + 1));
+  }
+  v16f acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+  float x[8], y[4] = {0, 0, 0, 0}, z[4] = {1, 1, 1, 1}, u[4] = {0, 0, 0, 0}, m3[2] = {0, 0};
+  uint32_t pq[4] = {0, 0, 0, 0};
+#pragma unroll
+  for (int i = 0; i < 8; ++i) x[i] = 0.001f * (t + i);
+  const long long c0 = __builtin_readcyclecounter();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (MFMA) acc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[j & 1], b[(j >> 1) & 1], acc[j], 0, 0, 0, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        if (OP == 0) asm volatile("v_fma_f32 %0, %0, %1, %0" : "+v"(x[v & 7]) : "v"(x[(v + 1) & 7]));
+        if (OP == 1) asm volatile("v_exp_f32 %0, %0" : "+v"(x[v & 7]));
+        if (OP == 2) asm volatile("v_cvt_pk_fp8_f32 %0, %1, %2" : "=v"(pq[v & 3]) : "v"(x[v & 7]), "v"(x[(v + 1) & 7]));
+        if (OP == 3) {
+          asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(y[v & 3]) : "v"(x[v & 7]), "v"(x[(v + 1) & 7]), "v"(x[(v + 2) & 7]));
+          asm volatile("v_exp_f32 %0, %1" : "=v"(z[v & 3]) : "v"(y[(v + 2) & 3]));
+          asm volatile("v_add_f32 %0, %1, %2" : "=v"(u[v & 3]) : "v"(z[(v + 2) & 3]), "v"(u[(v + 1) & 3]));
+          if (v & 1) asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(m3[(v >> 1) & 1]) : "v"(x[v & 7]), "v"(x[(v + 3) & 7]), "v"(m3[((v >> 1) + 1) & 1]));
+          else asm volatile("v_cvt_pk_fp8_f32 %0, %1, %2" : "=v"(pq[(v >> 1) & 3]) : "v"(z[v & 3]), "v"(z[(v + 1) & 3]));
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  const long long c1 = __builtin_readcyclecounter();
+  float s = y[0] + y[1] + y[2] + y[3] + z[0] + z[1] + z[2] + z[3] + u[0] + u[1] + u[2] + u[3] + m3[0] + m3[1];
+  s += (float)(pq[0] ^ pq[1] ^ pq[2] ^ pq[3]);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) s += x[i];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[j][r];
+  sink[(size_t)blockIdx.x * 256 + t] = s;
+  if (t == 0) cycles[blockIdx.x] = c1 - c0;
+}
+
+template <int OP, bool MFMA>
+void coissue_launch(int nv, int grid, float* sink, int iters, long long* cycles, hipStream_t s) {
+  switch (nv) {
+    case 0:  coissue_kernel<OP, 0, MFMA><<<grid, 256, 0, s>>>(sink, iters, cycles); break;
+    case 4:  coissue_kernel<OP, 4, MFMA><<<grid, 256, 0, s>>>(sink, iters, cycles); break;
+    case 8:  coissue_kernel<OP, 8, MFMA><<<grid, 256, 0, s>>>(sink, iters, cycles); break;
+    case 16: coissue_kernel<OP, 16, MFMA><<<grid, 256, 0, s>>>(sink, iters, cycles); break;
+    default: coissue_kernel<OP, 32, MFMA><<<grid, 256, 0, s>>>(sink, iters, cycles); break;
+  }
 }
 
 }  // namespace
@@ -123,7 +204,7 @@ __global__ __launch_bounds__(256) void attention_loop_kernel(float* __restrict__
 extern "C" fog_status fog_probe_attention_loop(int what, int waves_per_simd, int iters, float* sink, size_t sink_bytes,
                                                double* ns_per_block, void* stream) {
   if (!sink || !ns_per_block) return FOG_ERR_NULL;
-  if (iters < 1 || waves_per_simd < 1 || waves_per_simd > 3 || what < 0 || what > 2) return FOG_ERR_SHAPE;
+  if (iters < 1 || waves_per_simd < 1 || waves_per_simd > 2 || what < 0 || what > 2) return FOG_ERR_SHAPE;
   int dev = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
     return FOG_ERR_HIP;
@@ -178,5 +259,47 @@ extern "C" fog_status fog_probe_mfma_rate(const uint8_t* operand_bytes, int iter
   const double per_wave = 16.0 * iters;                        // instructions per wave
   *tflops = per_wave * 131072.0 * 4.0 * cus / (ms * 1e-3) / 1e12;
   if (mfma_clock_ghz) *mfma_clock_ghz = per_wave * 64.0 / (ms * 1e-3) / 1e9;
+  return FOG_OK;
+}
+
+extern "C" fog_status fog_probe_mfma_coissue(int op, int vector_ops, int with_mfma, int iters, float* sink, size_t sink_bytes,
+                                             double* cycles_per_slot, void* stream) {
+  if (!sink || !cycles_per_slot) return FOG_ERR_NULL;
+  if (iters < 1 || op < 0 || op > 3) return FOG_ERR_SHAPE;
+  if (vector_ops != 0 && vector_ops != 4 && vector_ops != 8 && vector_ops != 16 && vector_ops != 32) return FOG_ERR_SHAPE;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    return FOG_ERR_HIP;
+  // the sink's tail holds one cycle count per workgroup (8 bytes each, 8-byte aligned)
+  const size_t sink_floats = (size_t)cus * 256;
+  const size_t cyc_off = (sink_floats * sizeof(float) + 7) & ~(size_t)7;
+  if (sink_bytes < cyc_off + (size_t)cus * sizeof(long long)) return FOG_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(sink) & 7u) != 0) return FOG_ERR_ALIGN;
+  long long* cycles = reinterpret_cast<long long*>(reinterpret_cast<char*>(sink) + cyc_off);
+  hipStream_t s = (hipStream_t)stream;
+  auto launch = [&](int n) {
+    if (with_mfma) {
+      if (op == 0) coissue_launch<0, true>(vector_ops, cus, sink, n, cycles, s);
+      else if (op == 1) coissue_launch<1, true>(vector_ops, cus, sink, n, cycles, s);
+      else if (op == 2) coissue_launch<2, true>(vector_ops, cus, sink, n, cycles, s);
+      else coissue_launch<3, true>(vector_ops, cus, sink, n, cycles, s);
+    } else {
+      if (op == 0) coissue_launch<0, false>(vector_ops, cus, sink, n, cycles, s);
+      else if (op == 1) coissue_launch<1, false>(vector_ops, cus, sink, n, cycles, s);
+      else if (op == 2) coissue_launch<2, false>(vector_ops, cus, sink, n, cycles, s);
+      else coissue_launch<3, false>(vector_ops, cus, sink, n, cycles, s);
+    }
+  };
+  launch(iters < 32 ? iters : 32);   // warm-up
+  launch(iters);
+  fog_status st = fog_launch_status();
+  if (st != FOG_OK) return st;
+  if (hipStreamSynchronize(s) != hipSuccess) return FOG_ERR_HIP;
+  static thread_local long long host[1024];
+  const int n = cus < 1024 ? cus : 1024;
+  if (hipMemcpy(host, cycles, (size_t)n * sizeof(long long), hipMemcpyDeviceToHost) != hipSuccess) return FOG_ERR_HIP;
+  double sum = 0.0;
+  for (int i = 0; i < n; ++i) sum += (double)host[i];
+  *cycles_per_slot = sum / n / iters / 8.0;
   return FOG_OK;
 }

@@ -56,6 +56,8 @@ ATTN_BWD_STATIC_MAX_ROWS = 524288      # FOG_ATTN_BWD_STATIC_MAX_ROWS of the hea
 PROBE_SIGNATURES = {
     "fog_probe_mfma_rate": (_I, [_P, _I, _P, _SZ, _c.POINTER(_c.c_double), _c.POINTER(_c.c_double), _P]),
     "fog_probe_attention_loop": (_I, [_I, _I, _I, _P, _SZ, _c.POINTER(_c.c_double), _P]),
+    "fog_probe_mfma_coissue": (_I, [_I, _I, _I, _I, _P, _SZ, _c.POINTER(_c.c_double), _P]),
+    "fog_probe_gemm_products_only": (_I, [_I64, _I64, _I64, _P, _I64, _P, _I64, _P, _P, _P, _I64, _P]),
 }
 
 
@@ -273,3 +275,17 @@ def probe_attention_loop(what, waves_per_simd, iters, sink, stream=None):
     _check(load().fog_probe_attention_loop(what, waves_per_simd, iters, _ptr(sink), sink.numel() * sink.element_size(),
                                            _c.byref(ns), _stream(stream)), "fog_probe_attention_loop")
     return ns.value
+
+
+def probe_mfma_coissue(op, vector_ops, with_mfma, iters, sink, stream=None):
+    """Shader cycles per slot (one matrix instruction + vector_ops vector operations, order pinned), one wave per SIMD."""
+    cyc = _c.c_double(0.0)
+    _check(load().fog_probe_mfma_coissue(op, vector_ops, int(with_mfma), iters, _ptr(sink), sink.numel() * sink.element_size(),
+                                         _c.byref(cyc), _stream(stream)), "fog_probe_mfma_coissue")
+    return cyc.value
+
+
+def probe_gemm_products_only(M, N, K, A, sinv_a, B, sinv_b, C, stream=None):
+    """fog_fp8_gemm's NT product of E4M3 operands without any tile's epilogue (fog_probe.h); C is not written."""
+    _check(load().fog_probe_gemm_products_only(M, N, K, _ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(sinv_a), _ptr(sinv_b),
+                                               _ptr(C), C.stride(0), _stream(stream)), "fog_probe_gemm_products_only")

@@ -34,7 +34,46 @@ def test_attention_loop_probe_orders_its_three_timings():
     lib = fog.load()
     ns = ctypes.c_double(0)
     st = torch.cuda.current_stream().cuda_stream
-    assert lib.fog_probe_attention_loop(0, 4, 10, sink.data_ptr(), sink.numel() * 4, ctypes.byref(ns), st) == 2
+    assert lib.fog_probe_attention_loop(0, 3, 10, sink.data_ptr(), sink.numel() * 4, ctypes.byref(ns), st) == 2
     assert lib.fog_probe_attention_loop(3, 1, 10, sink.data_ptr(), sink.numel() * 4, ctypes.byref(ns), st) == 2
     assert lib.fog_probe_attention_loop(0, 1, 10, None, 0, ctypes.byref(ns), st) == 1
     assert lib.fog_probe_attention_loop(0, 2, 10, sink.data_ptr(), 64, ctypes.byref(ns), st) == 5
+
+
+def test_coissue_probe_shows_the_matrix_instruction_and_checks_arguments():
+    sink = torch.empty(1024 * 256 + 4096, device="cuda")
+    alone = fog.probe_mfma_coissue(0, 0, True, 500, sink)
+    assert 60.0 < alone < 80.0                       # 16 passes of 4 cycles, back to back
+    few = fog.probe_mfma_coissue(0, 4, True, 500, sink)
+    many = fog.probe_mfma_coissue(0, 32, True, 500, sink)
+    bare = fog.probe_mfma_coissue(0, 32, False, 500, sink)
+    assert few < alone * 1.15                        # a few vector operations hide under the matrix instruction
+    assert bare < many < bare + 64.0                 # and many of them hide most of the matrix instruction in turn
+    lib = fog.load()
+    cyc = ctypes.c_double(0)
+    st = torch.cuda.current_stream().cuda_stream
+    call = lambda op, n, p, sb: lib.fog_probe_mfma_coissue(op, n, 1, 10, p, sb, ctypes.byref(cyc), st)
+    assert call(4, 4, sink.data_ptr(), sink.numel() * 4) == 2
+    assert call(0, 5, sink.data_ptr(), sink.numel() * 4) == 2
+    assert call(0, 4, None, 0) == 1
+    assert call(0, 4, sink.data_ptr() + 4, sink.numel() * 4 - 4) == 3
+    assert call(0, 4, sink.data_ptr(), 64) == 5
+
+
+def test_products_only_gemm_probe_runs_writes_nothing_and_checks_arguments():
+    M, N, K = 512, 768, 1024
+    g = torch.Generator(device="cuda"); g.manual_seed(3)
+    A = torch.randint(0, 0x78, (M, K), dtype=torch.uint8, device="cuda", generator=g)
+    B = torch.randint(0, 0x78, (N, K), dtype=torch.uint8, device="cuda", generator=g)
+    one = torch.ones(1, device="cuda")
+    C = torch.full((M, N), 0x1234, dtype=torch.int16, device="cuda")
+    fog.probe_gemm_products_only(M, N, K, A, one, B, one, C)
+    torch.cuda.synchronize()
+    assert bool((C == 0x1234).all())                  # no tile has an epilogue: C is untouched
+    lib = fog.load()
+    st = torch.cuda.current_stream().cuda_stream
+    call = lambda m, n, k, a, c: lib.fog_probe_gemm_products_only(m, n, k, a, K, B.data_ptr(), K, one.data_ptr(), one.data_ptr(), c, N, st)
+    assert call(M + 1, N, K, A.data_ptr(), C.data_ptr()) == 4
+    assert call(M, N, K, None, C.data_ptr()) == 1
+    assert call(M, N, K, A.data_ptr() + 1, C.data_ptr()) == 3
+    assert call(0, N, K, A.data_ptr(), C.data_ptr()) == 2
