@@ -85,20 +85,10 @@ template <bool CAUSAL>
 __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
   __shared__ __attribute__((aligned(1024))) uint8_t smem[NSTAGE * STAGE];
   const int bh = blockIdx.x % a.BH;
-  const int pr = blockIdx.x / a.BH;
+  const int qb = a.nqb - 1 - blockIdx.x / a.BH;   // long rows (late query blocks) are launched first
   const int t = threadIdx.x, w = t >> 6, l = t & 63, g = l >> 5;
   const int S = a.S;
   const uint8_t* Qh = a.Q + (int64_t)bh * S * HD;
-  // A workgroup takes a PAIR of query blocks, block nqb - 1 - pr and then block pr: under the causal mask
-  // the two together need 2 nqb + 2 key blocks whatever pr is, so every workgroup of a launch does the
-  // same amount of work and the fixed cost of starting one is paid once per pair.
-  for (int part = 0; part < 2; ++part) {
-  const int qb = part == 0 ? a.nqb - 1 - pr : pr;
-  if (part == 1) {
-    if (qb >= a.nqb - 1 - pr) break;   // odd number of query blocks: the middle one has no partner
-    __syncthreads();                   // every wave has finished reading the ring of the first block
-  }
-
   const int q0 = qb * BQ + 32 * w;           // first query of this wave
   const int q = q0 + (l & 31);
   const bool wave_on = q0 < S;               // S is a multiple of 64, so a wave is all in or all out
@@ -285,9 +275,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
     block(kb, sc, sn);
     if (kb + 1 < nkb) block(kb + 1, sn, sc);
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the ring is reused or the workgroup retires
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
 
-  if (!wave_on) continue;
+  if (!wave_on) return;
   // ---- epilogue: O = sinv_v O^T / (rho_p l);  lse = m + log2 l  (l_run holds rho_p l, split over two lanes)
   const float l_tot = l_run + lane_xor32(l_run);
   const float scale_o = (*a.sinv_v) / l_tot;
@@ -310,7 +300,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
     // only be too small, which costs an atomic that changes nothing)
     if (l == 0 && __float_as_uint(pm) > __hip_atomic_load(a.amax_p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(a.amax_p, __float_as_uint(pm));
   }
-  }   // part
 }
 
 __global__ void zero_u32(uint32_t* p) { *p = 0u; }
@@ -347,7 +336,7 @@ extern "C" fog_status fog_fp8_attn_fwd(int B, int H, int H_kv, int S, int D, flo
   a.softmax_scale = softmax_scale;
   a.BH = B * H; a.S = S; a.nqb = (S + BQ - 1) / BQ;
   a.G = H / H_kv;
-  const int grid = a.BH * ((a.nqb + 1) / 2);   // one workgroup per pair of query blocks
+  const int grid = a.BH * a.nqb;
   if (causal) attn_fwd_kernel<true><<<grid, kThreads, 0, s>>>(a);
   else        attn_fwd_kernel<false><<<grid, kThreads, 0, s>>>(a);
   return fog_launch_status();
