@@ -168,6 +168,28 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_rowdot_kernel(const uint16_
   }
 }
 
+// Largest magnitude among the 32 values of a lane's two score tiles (NaN operands are dropped by the maximum), as four
+// independent chains, and the clamp of those values to the finite range of E5M2.
+FOG_DEVICE float block_absmax(const v16f* x) {
+  float cm[4];
+#pragma unroll
+  for (int ch = 0; ch < 4; ++ch) {
+    const v16f& t = x[ch >> 1];
+    const int b = 8 * (ch & 1);
+    float m = fmaxf(fmaxf(fabsf(t[b]), fabsf(t[b + 1])), fabsf(t[b + 2]));
+    m = fmaxf(fmaxf(m, fabsf(t[b + 3])), fabsf(t[b + 4]));
+    m = fmaxf(fmaxf(m, fabsf(t[b + 5])), fabsf(t[b + 6]));
+    cm[ch] = fmaxf(m, fabsf(t[b + 7]));
+  }
+  return fmaxf(fmaxf(fmaxf(cm[0], cm[1]), cm[2]), cm[3]);
+}
+FOG_DEVICE void clamp_block(v16f* x) {
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) x[kt][r] = __builtin_amdgcn_fmed3f(x[kt][r], -57344.0f, 57344.0f);
+}
+
 // ------------------------------------------------------------------ kernel 1: dK, dV
 // Ring stage: Q tile, dO tile, then 64 lse and 64 D values.  Five direct loads per thread and stage.
 constexpr int KV_STAGE = 2 * TILE + 512;
@@ -310,12 +332,12 @@ __global__ __launch_bounds__(kThreads, MODE == 0 ? 1 : 2) void attn_bwd_dkdv_ker
           float4 dd = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
           if (WANT_DK) dd = *reinterpret_cast<const float4*>(srow + 64 + qi);
           const float lsv[4] = {ls.x, ls.y, ls.z, ls.w}, ddv[4] = {dd.x, dd.y, dd.z, dd.w};
-          float pq[4], ds[4];
+          float pq[4];
 #pragma unroll
           for (int b = 0; b < 4; ++b) {
             const int r = 4 * qd + b;
-            pq[b] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[qt][r], c, -lsv[b]));   // rho_p P
-            if (WANT_DK) ds[b] = pq[b] * __builtin_fmaf(dp[qt][r], cdpk, -ddv[b]);    // rho_ds dS
+            pq[b] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[qt][r], c, -lsv[b]));            // rho_p P
+            if (WANT_DK) dp[qt][r] = pq[b] * __builtin_fmaf(dp[qt][r], cdpk, -ddv[b]);        // rho_ds dS, left in the registers of dP
           }
           if (WANT_DV) {
             if (CLAMP_P) {
@@ -325,8 +347,19 @@ __global__ __launch_bounds__(kThreads, MODE == 0 ? 1 : 2) void attn_bwd_dkdv_ker
               pf[4 * qt + qd] = (int)__builtin_amdgcn_cvt_pk_fp8_f32(pq[2], pq[3], pk, true);
             }
           }
-          if (WANT_DK) dsf[4 * qt + qd] = (int)cvt4_fp8<FOG_E5M2>(ds[0], ds[1], ds[2], ds[3]);
         }
+      }
+      if (WANT_DK) {
+        // the clamp before the cast of dS runs only when the block holds a magnitude above the largest finite E5M2 value
+        // (see the dQ kernel); finding that out costs half an instruction per value, the clamp one
+        if (__builtin_expect(__any(block_absmax(dp) > 57344.0f), 0)) clamp_block(dp);
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+          for (int qd = 0; qd < 4; ++qd) {
+            const uint32_t pk = __builtin_amdgcn_cvt_pk_bf8_f32(dp[qt][4 * qd + 0], dp[qt][4 * qd + 1], any_u32(), false);
+            dsf[4 * qt + qd] = (int)__builtin_amdgcn_cvt_pk_bf8_f32(dp[qt][4 * qd + 2], dp[qt][4 * qd + 3], pk, true);
+          }
       }
       // dV^T += dO^T P~ ;  dK^T += Q^T dS~   (contraction over the 64 queries of this step)
 #pragma unroll
@@ -459,22 +492,28 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(BwdArgs a) {
         for (int r = 0; r < 16; ++r)
           if (kbase + 32 * kt + 8 * (r >> 2) + 4 * g + (r & 3) > q) st[kt][r] = -INFINITY;
     }
+    // rho_ds dS = (rho_ds P) (dP - D), left in the registers of dP
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][r], c, -lse));   // rho_ds P
+        dp[kt][r] = e * __builtin_fmaf(dp[kt][r], cdp, -Dq);
+      }
+    const float bm = block_absmax(dp);
+    ds_max = fmaxf(ds_max, bm);
+    // The hardware convert turns overflow into infinity, so magnitudes above the largest finite E5M2 value have to be clamped
+    // first; whether any of the block's 32 values per lane needs that is known from the block maximum (which the abs-max of dS
+    // wants anyway), and with a scale fitted to the tensor none does: the clamp (one instruction per value) runs only then.
+    if (__builtin_expect(__any(bm > 57344.0f), 0)) clamp_block(dp);
     v8i dsf;
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+    for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int qd = 0; qd < 4; ++qd) {
-        float ds[4];
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const int r = 4 * qd + b;
-          const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][r], c, -lse));   // rho_ds P
-          ds[b] = e * __builtin_fmaf(dp[kt][r], cdp, -Dq);                                // rho_ds dS
-          if (AMAX) ds_max = fmaxf(ds_max, fabsf(ds[b]));
-        }
-        dsf[4 * kt + qd] = (int)cvt4_fp8<FOG_E5M2>(ds[0], ds[1], ds[2], ds[3]);
+        const uint32_t pk = __builtin_amdgcn_cvt_pk_bf8_f32(dp[kt][4 * qd + 0], dp[kt][4 * qd + 1], any_u32(), false);
+        dsf[4 * kt + qd] = (int)__builtin_amdgcn_cvt_pk_bf8_f32(dp[kt][4 * qd + 2], dp[kt][4 * qd + 3], pk, true);
       }
-    }
     // dQ^T += K^T dS~^T  (contraction over the 64 keys of this step)
 #pragma unroll
     for (int d = 0; d < 4; ++d)

@@ -106,7 +106,7 @@ def test_forward_fog_softmax_scale_and_q_zero():
         assert np.abs(lse[0, h] - np.log2(np.arange(1, S + 1))).max() < 1e-5
 
 
-def run_bwd(c, B, H, S, s, causal, heads, do_bits, rho_p=448.0):
+def run_bwd(c, B, H, S, s, causal, heads, do_bits, rho_p=448.0, ds_scale_factor=1.0):
     """Feeds the ORACLE's forward results (O rounded to bf16, lse rounded to binary32) to both sides.
     Under grouped-query attention dK and dV of a key/value head are checked when all the query heads of
     its group are in `heads`: the oracle's per-head contributions are summed in float64 (the kernel sums
@@ -131,6 +131,7 @@ def run_bwd(c, B, H, S, s, causal, heads, do_bits, rho_p=448.0):
                                     s, rho_p, 1.0, causal, True, False)
         amax_ds = max(amax_ds, float(r[3]))
     rho_ds, _ = scaling.compute_scale(np.float32(amax_ds), fp8.E5M2)
+    rho_ds = np.float32(rho_ds * ds_scale_factor)     # > 1: a stale (delayed) scale, the largest dS saturate
     dQ = torch.full((B, H, S, 128), 0x7FC0, dtype=torch.int16, device="cuda")
     dK, dV = (torch.full((B, Hkv, S, 128), 0x7FC0, dtype=torch.int16, device="cuda") for _ in range(2))
     am = torch.full((1,), -1.0, device="cuda")
@@ -169,6 +170,16 @@ def test_backward_parity(B, H, S, causal):
     q, k, v, do = synth.small_attention(2000 + S, B, H, S)
     c = cast_all(q, k, v, do)
     run_bwd(c, B, H, S, 1 / math.sqrt(128), causal, [(b, h) for b in range(B) for h in range(H)], do)
+
+
+@pytest.mark.parametrize("factor", [4.0, 64.0])
+def test_backward_with_a_stale_ds_scale_saturates_like_the_oracle(factor):
+    """A scale of dS several times too large (delayed scaling after the gradients grew): rho_ds dS exceeds the largest
+    finite E5M2 value in some key blocks and not in others, so both the clamped and the unclamped form of the cast run."""
+    B, H, S = 1, 2, 320
+    q, k, v, do = synth.small_attention(2600 + int(factor), B, H, S)
+    c = cast_all(q, k, v, do)
+    run_bwd(c, B, H, S, 1 / math.sqrt(128), True, [(b, h) for b in range(B) for h in range(H)], do, ds_scale_factor=factor)
 
 
 def gqa_case(seed, B, H, Hkv, S):
