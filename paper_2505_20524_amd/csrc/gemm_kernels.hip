@@ -67,6 +67,7 @@ struct GemmArgs {
   int M, N, K;
   int tiles_m, tiles_n;
   int vec_store;  // C rows allow 16-byte stores
+  int wide_store; // interior tiles are stored as whole 128-byte lines (launches of several tiles per workgroup)
   uint32_t a_bytes, b_bytes;  // addressable span of each operand
   // contraction split (splits == 1: none): work item = chunk * tiles + tile, chunk c covers
   // contraction indices [c * k_chunk, min(K, (c + 1) * k_chunk)); partial holds splits * tiles blocks
@@ -476,7 +477,37 @@ __global__ __launch_bounds__(kThreads) void fp8_gemm_kernel(GemmArgs g) {
       continue;
     }
     const int prow = l >> 2, piece = l & 3;   // this lane's row (+ 16 t) and 16-byte piece of a staged block
-    if (fast) {
+    if (fast && g.wide_store) {
+      // Launches in which a workgroup computes several tiles: two neighbouring 32 x 32 blocks are staged together, so that a
+      // store instruction covers 8 rows of 128 bytes (whole lines of C) instead of 16 rows of 64 bytes.  One staging buffer per
+      // wave (LDS operations of a wave execute in order, so refilling it needs no wait); the longer dependency chain per block
+      // is hidden by the next tile's products, which is why single-tile launches keep the narrow form below.
+      constexpr int WIDE = 128 + 8;   // row stride of the staged 32 x 64 block: rows 34 banks apart
+      const int row8 = l >> 3, piece8 = l & 7;
+      uint16_t* cbase = g.C + (int64_t)(m_cur + wm + row8) * g.ldc + (n_cur + wn + 8 * piece8);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int jp = 0; jp < 2; ++jp) {
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj) {
+            const int j = 2 * jp + jj;
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+              const float v0 = acc[i][j][4 * qd + 0] * alpha, v1 = acc[i][j][4 * qd + 1] * alpha;
+              const float v2 = acc[i][j][4 * qd + 2] * alpha, v3 = acc[i][j][4 * qd + 3] * alpha;
+              *reinterpret_cast<uint2*>(epi + (l & 31) * WIDE + 64 * jj + 16 * qd + 8 * (l >> 5)) = make_uint2(cvt_pk_bf16(v0, v1), cvt_pk_bf16(v2, v3));
+            }
+          }
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const uint2 lo = *reinterpret_cast<const uint2*>(epi + (8 * t + row8) * WIDE + 16 * piece8);
+            const uint2 hi = *reinterpret_cast<const uint2*>(epi + (8 * t + row8) * WIDE + 16 * piece8 + 8);
+            st_nt16(cbase + (int64_t)(32 * i + 8 * t) * g.ldc + 64 * jp, make_uint4(lo.x, lo.y, hi.x, hi.y));
+          }
+        }
+      }
+    } else if (fast) {
       uint16_t* cbase = g.C + (int64_t)(m_cur + wm + prow) * g.ldc + (n_cur + wn + 8 * piece);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -718,6 +749,7 @@ extern "C" fog_status fog_fp8_gemm(fog_layout layout, int64_t M, int64_t N, int6
   g.tiles_n = (int)((N + BN - 1) / BN);
   if ((int64_t)g.tiles_m * g.tiles_n > 0x7FFFFFF0) return FOG_ERR_UNSUPPORTED;
   g.vec_store = aligned(C_bf16, 16) && ldc % 8 == 0;
+  g.wide_store = (int64_t)g.tiles_m * g.tiles_n >= 2 * (int64_t)compute_units();
   // addressable span of each operand (last row may be shorter than the leading dimension)
   const int64_t a_rows = layout == FOG_TN ? K : M, b_rows = layout == FOG_NT ? N : K;
   const int64_t a_span = K > 0 ? (a_rows - 1) * lda + a_cols : 0, b_span = K > 0 ? (b_rows - 1) * ldb + b_cols : 0;
@@ -760,6 +792,7 @@ extern "C" fog_status fog_probe_gemm_products_only(int64_t M, int64_t N, int64_t
   g.M = (int)M; g.N = (int)N; g.K = (int)K;
   g.tiles_m = (int)(M / BM); g.tiles_n = (int)(N / BN);
   g.vec_store = 1;
+  g.wide_store = 0;
   const int64_t a_span = (M - 1) * lda + K, b_span = (N - 1) * ldb + K;
   if (a_span >= 0x7FFFFFFF || b_span >= 0x7FFFFFFF) return FOG_ERR_UNSUPPORTED;
   g.a_bytes = (uint32_t)a_span; g.b_bytes = (uint32_t)b_span;
