@@ -18,12 +18,13 @@
 // with the byte-transposing read (ds_read_b64_tr_b8) from the row-major V tile.
 // Row statistics are per lane (a lane owns one query) plus one exchange with lane ^ 32.
 //
-// Pipeline.  K and V blocks stream from global memory straight into a 4-stage LDS ring
-// (buffer_load ... lds), two blocks in flight.  The scores of block j+1 are issued to the matrix
-// core before the softmax of block j runs on the vector ALU, so the two overlap inside a wave; two
-// workgroups per CU (two waves per SIMD) overlap the rest.  The softmax costs about 4 vector
-// instructions per score (max3, fma, exp2, add, half a convert): with FP8 the kernel is bound by
-// the vector ALU, not by the matrix core.
+// Pipeline.  K and V blocks stream from global memory straight into a 3-stage LDS ring (buffer_load ... lds), two
+// blocks in flight.  A wave takes a block through scores, softmax and P V one after the other and keeps a single
+// set of score registers: 168 registers per lane, so THREE workgroups share a CU (three waves per SIMD) and one
+// wave's exponentials and converts run under another's matrix instructions and LDS waits.  (Producing the next
+// block's scores ahead of the softmax needs a second score set, 229 registers and two waves per SIMD: 5 % slower.)
+// The softmax costs about 4 vector instructions per score (max3, fma, exp2, add, half a convert): with FP8 the
+// kernel is bound by the vector ALU's issue, not by the matrix core.
 #include "common.h"
 #include "launch.h"
 
@@ -35,7 +36,7 @@ constexpr int BKV = 64;        // keys per step
 constexpr int HD = 128;        // head dimension
 constexpr int TILE_BYTES = BKV * HD;         // 8 KB: one K or V block, 16-byte chunks swizzled (see below)
 constexpr int STAGE = 2 * TILE_BYTES;        // K then V
-constexpr int NSTAGE = 4;
+constexpr int NSTAGE = 3;
 constexpr uint32_t OOB = 0x80000000u;
 
 typedef __attribute__((address_space(3))) v2i* lds_v2i_ptr;
@@ -82,7 +83,7 @@ FOG_DEVICE v4i make_rsrc(const void* base, uint32_t bytes) {
 }
 
 template <bool CAUSAL>
-__global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
+__global__ __launch_bounds__(kThreads, 3) void attn_fwd_kernel(FwdArgs a) {
   __shared__ __attribute__((aligned(1024))) uint8_t smem[NSTAGE * STAGE];
   const int bh = blockIdx.x % a.BH;
   const int qb = a.nqb - 1 - blockIdx.x / a.BH;   // long rows (late query blocks) are launched first
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
   const uint32_t lds_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(uintptr_t)smem + 2048u * w));
   auto issue = [&](int kb) {   // block kb -> stage kb % 4; blocks past the end fetch zeros (keeps the wait counts uniform)
     const uint32_t adv = kb < nkb ? (uint32_t)kb * (BKV * HD) : OOB;
-    const uint32_t base = lds_w + (uint32_t)(kb & (NSTAGE - 1)) * STAGE;
+    const uint32_t base = lds_w + (uint32_t)(kb % NSTAGE) * STAGE;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       load_to_lds(rsrc_k, off_k[j] + adv, base + 1024u * j);
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
   float raw_max = -INFINITY;  // this lane's share of max_j (Q K^T)_ij, before scaling
 
   auto scores = [&](int kb, v16f* st) {   // st[kt][r] = sum_d K[key][d] Q[q][d], key = 64 kb + 32 kt + 8 (r/4) + 4 g + (r%4)
-    const uint8_t* sk = smem + (kb & (NSTAGE - 1)) * STAGE;
+    const uint8_t* sk = smem + (kb % NSTAGE) * STAGE;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
@@ -190,21 +191,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
   FOG_SETTLE(qf[0]); FOG_SETTLE(qf[1]);
   issue(0);
   issue(1);
-  issue(2);
-  __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt = 8: block 0 has landed (4 direct loads per thread and block)
-  __syncthreads();
-  v16f sc[2], sn[2];
-  if (nkb_wave > 0) scores(0, sc);
+  v16f sc[2];
 
-  // One key block: SC holds this block's scores, SN receives the next block's.
-  auto block = [&](int kb, v16f* sc, v16f* sn) {
-    // block kb + 1 landed (blocks kb + 2 may be in flight: vmcnt = 4), own LDS reads done (lgkmcnt = 0)
+  // One key block.
+  auto block = [&](int kb, v16f* sc) {
+    // block kb landed (block kb + 1 may be in flight: vmcnt = 4), own LDS reads done (lgkmcnt = 0)
     __builtin_amdgcn_s_waitcnt(0x0074);
     __syncthreads();
-    issue(kb + 3);   // into the stage of block kb - 1, which every wave finished reading before the barrier
-    const bool cur = kb < nkb_wave, nxt = kb + 1 < nkb_wave;
-    if (nxt) scores(kb + 1, sn);       // matrix core works on the next block's scores ...
-    if (cur) {                         // ... while the vector ALU does this block's softmax
+    issue(kb + 2);   // into the stage of block kb - 1, which every wave finished reading before the barrier
+    if (kb < nkb_wave) {               // this wave needs the block: scores, softmax, P V
+      scores(kb, sc);
       const int key0 = kb * BKV;
       if (CAUSAL && key0 + BKV - 1 > q0) {   // causal mask on blocks that reach past the wave's first query
 #pragma unroll
@@ -257,7 +253,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
       }
       // O^T += V^T P^T.  Byte 4 qd' + b of dword (4 kt + qd') of pf is key key0 + 32 kt + 8 qd' + 4 g + b;
       // the V^T fragment lists its 32 keys in the same order (read r covers rows 16 r + vrow).
-      const uint8_t* sv = smem + (kb & (NSTAGE - 1)) * STAGE + TILE_BYTES;
+      const uint8_t* sv = smem + (kb % NSTAGE) * STAGE + TILE_BYTES;
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
         v8i vf;
@@ -271,10 +267,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdArgs a) {
       }
     }
   };
-  for (int kb = 0; kb < nkb; kb += 2) {   // two blocks per trip so that the score registers just swap roles
-    block(kb, sc, sn);
-    if (kb + 1 < nkb) block(kb + 1, sn, sc);
-  }
+  for (int kb = 0; kb < nkb; ++kb) block(kb, sc);
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
 
   if (!wave_on) return;
