@@ -351,9 +351,9 @@ def main():
             tf, ghz = fog.probe_mfma_rate(pat, 20000, sink)
             ceilings["mfma_loop"][name] = {"tflops": tf, "frac_of_peak": tf / PEAK_FP8_TFLOPS, "mfma_clock_ghz": ghz}
         # The attention forward's instruction mix without any memory traffic (see include/fog_probe.h): how far the matrix
-        # cores and the vector ALU overlap on this part, at one and two waves per SIMD.
+        # cores and the vector ALU overlap on this part, at one to three waves per SIMD.
         ceilings["attention_loop_ns_per_wave_block"] = {}
-        for wps in (1, 2):
+        for wps in (1, 2, 3):
             t_all, t_mfma, t_valu = (fog.probe_attention_loop(w, wps, 3000, sink) for w in (0, 1, 2))
             ceilings["attention_loop_ns_per_wave_block"]["%d waves per SIMD" % wps] = {
                 "everything": t_all, "matrix instructions only": t_mfma, "softmax arithmetic only": t_valu,

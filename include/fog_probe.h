@@ -47,7 +47,7 @@ fog_status fog_probe_mfma_rate(const uint8_t* operand_bytes, int iters, float* s
  * does with this mix is an upper bound for any attention kernel built from these instructions.
  *   ns_per_block : HOST pointer, receives nanoseconds per key block and wave, divided by waves_per_simd (the time a SIMD
  *                  spends per wave-block).   sink : as in fog_probe_mfma_rate, compute units * waves_per_simd * 256 floats.
- * Errors: NULL, SHAPE (iters < 1, waves_per_simd outside 1..2, what outside 0..2), WORKSPACE (sink too small), HIP.
+ * Errors: NULL, SHAPE (iters < 1, waves_per_simd outside 1..3, what outside 0..2), WORKSPACE (sink too small), HIP.
  */
 fog_status fog_probe_attention_loop(int what, int waves_per_simd, int iters, float* sink, size_t sink_bytes,
                                     double* ns_per_block, void* stream);

@@ -46,20 +46,22 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(const uint8_t* __restric
 }
 
 // WHAT 0: score products, softmax arithmetic, P V products; 1: the products only; 2: the arithmetic only.
-// One key block; SC holds this block's scores, SN receives the next block's (the caller swaps them: no copies).
+// One key block the way the forward kernel takes it: scores into the one set of score registers, softmax, P V.
 template <int WHAT>
-__device__ __forceinline__ void attention_block(v8i* kf, const v8i* qf, const v8i* vf, const v16f& zero16, v16f* sc, v16f* sn,
+__device__ __forceinline__ void attention_block(v8i* kf, const v8i* qf, const v8i* vf, const v16f& zero16, v16f* sc,
                                                 v16f* o, float& l_run, float& m_run, float c, int it) {
-  if (WHAT != 2) {   // the next block's scores
+  if (WHAT != 2) {
     asm volatile("" : "+v"(kf[0]), "+v"(kf[1]));   // the fragments "change" every block: the products stay in the loop
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
-      sn[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf[kt], qf[0], zero16, 0, 0, 0, 0, 0, 0);
-      sn[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf[kt], qf[1], sn[kt], 0, 0, 0, 0, 0, 0);
+      sc[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf[kt], qf[0], zero16, 0, 0, 0, 0, 0, 0);
+      sc[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf[kt], qf[1], sc[kt], 0, 0, 0, 0, 0, 0);
     }
+  } else {
+    sc[0][it & 15] += 1e-3f;   // keeps the arithmetic loop-variant
   }
   v8i pf;
-  if (WHAT != 1) {   // this block's softmax arithmetic
+  if (WHAT != 1) {
     float cm[4];
 #pragma unroll
     for (int ch = 0; ch < 4; ++ch) {
@@ -93,12 +95,11 @@ __device__ __forceinline__ void attention_block(v8i* kf, const v8i* qf, const v8
     for (int d = 0; d < 4; ++d) o[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vf[d], pf, o[d], 0, 0, 0, 0, 0, 0);
   } else {
     asm volatile("" ::"v"(pf));
-    sn[0][it & 15] += 1e-3f;   // keeps the arithmetic loop-variant
   }
 }
 
 template <int WHAT>
-__global__ __launch_bounds__(256, 2) void attention_loop_kernel(float* __restrict__ sink, int iters) {
+__global__ __launch_bounds__(256, 3) void attention_loop_kernel(float* __restrict__ sink, int iters) {
   const int t = threadIdx.x;
   v8i kf[2], qf[2], vf[4];
 #pragma unroll
@@ -108,26 +109,22 @@ __global__ __launch_bounds__(256, 2) void attention_loop_kernel(float* __restric
 #pragma unroll
     for (int d = 0; d < 4; ++d) vf[d][i] = 0x38393a3b + i * 0x01010101 + d * 0x02020202;
   }
-  v16f o[4], sc[2], sn[2], zero16;
+  v16f o[4], sc[2], zero16;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     zero16[r] = 0.0f;
 #pragma unroll
     for (int d = 0; d < 4; ++d) o[d][r] = 0.0f;
     sc[0][r] = 0.001f * (r + t); sc[1][r] = 0.002f * (r + t);
-    sn[0][r] = sc[0][r]; sn[1][r] = sc[1][r];
   }
   float l_run = 0.0f, m_run = 0.0f;
   const float c = 1e-6f;
-  for (int it = 0; it < iters; it += 2) {   // two blocks per trip: the score registers swap roles
-    attention_block<WHAT>(kf, qf, vf, zero16, sc, sn, o, l_run, m_run, c, it);
-    attention_block<WHAT>(kf, qf, vf, zero16, sn, sc, o, l_run, m_run, c, it + 1);
-  }
+  for (int it = 0; it < iters; ++it) attention_block<WHAT>(kf, qf, vf, zero16, sc, o, l_run, m_run, c, it);
   float s = l_run + m_run;
 #pragma unroll
   for (int d = 0; d < 4; ++d)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s += o[d][r] + sc[d & 1][r] + sn[d & 1][r];
+    for (int r = 0; r < 16; ++r) s += o[d][r] + sc[d & 1][r];
   sink[(size_t)blockIdx.x * 256 + t] = s;
 }
 
@@ -204,7 +201,7 @@ void coissue_launch(int nv, int grid, float* sink, int iters, long long* cycles,
 extern "C" fog_status fog_probe_attention_loop(int what, int waves_per_simd, int iters, float* sink, size_t sink_bytes,
                                                double* ns_per_block, void* stream) {
   if (!sink || !ns_per_block) return FOG_ERR_NULL;
-  if (iters < 1 || waves_per_simd < 1 || waves_per_simd > 2 || what < 0 || what > 2) return FOG_ERR_SHAPE;
+  if (iters < 1 || waves_per_simd < 1 || waves_per_simd > 3 || what < 0 || what > 2) return FOG_ERR_SHAPE;
   int dev = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
     return FOG_ERR_HIP;

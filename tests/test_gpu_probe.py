@@ -34,7 +34,7 @@ def test_attention_loop_probe_orders_its_three_timings():
     lib = fog.load()
     ns = ctypes.c_double(0)
     st = torch.cuda.current_stream().cuda_stream
-    assert lib.fog_probe_attention_loop(0, 3, 10, sink.data_ptr(), sink.numel() * 4, ctypes.byref(ns), st) == 2
+    assert lib.fog_probe_attention_loop(0, 4, 10, sink.data_ptr(), sink.numel() * 4, ctypes.byref(ns), st) == 2
     assert lib.fog_probe_attention_loop(3, 1, 10, sink.data_ptr(), sink.numel() * 4, ctypes.byref(ns), st) == 2
     assert lib.fog_probe_attention_loop(0, 1, 10, None, 0, ctypes.byref(ns), st) == 1
     assert lib.fog_probe_attention_loop(0, 2, 10, sink.data_ptr(), 64, ctypes.byref(ns), st) == 5
