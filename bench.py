@@ -221,14 +221,17 @@ def main():
     # Figures of kernels that are not steps of the timed path, each timed on its own after the timed region
     # (first repetition untimed): jobs = [(algorithmic bytes, call), ...].
     def side_figure(key, jobs, reps=4):
+        # one event pair around a whole pass over the jobs, launched back to back: an event between two launches
+        # costs a gap of 6-10 us on the stream, a fifth of what these kernels take on the step's tensors
         t = block.EventTimer()
+        total = sum(work for work, _ in jobs)
         for rep in range(reps):
-            for work, fn in jobs:
-                if rep:
-                    t.begin(key, work)
+            if rep:
+                t.begin(key, total, launches=len(jobs))
+            for _, fn in jobs:
                 fn()
-                if rep:
-                    t.end()
+            if rep:
+                t.end()
         torch.cuda.synchronize()
         n, work, ms = t.summary()[key]
         kernels[key] = {"launches": n, "avg_launch_ms": ms / n, "achieved": work / (ms * 1e-3) / 1e9,
