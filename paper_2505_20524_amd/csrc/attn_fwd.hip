@@ -38,6 +38,7 @@ constexpr int TILE_BYTES = BKV * HD;         // 8 KB: one K or V block, 16-byte 
 constexpr int STAGE = 2 * TILE_BYTES;        // K then V
 constexpr int NSTAGE = 3;
 constexpr uint32_t OOB = 0x80000000u;
+template <int N> struct Stg { static constexpr int value = N; };
 
 typedef __attribute__((address_space(3))) v2i* lds_v2i_ptr;
 
@@ -131,9 +132,12 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_kernel(FwdArgs a) {
     off_v[j] = (uint32_t)(row * HD + ((cpos ^ swz_v(row)) << 4));
   }
   const uint32_t lds_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(uintptr_t)smem + 2048u * w));
-  auto issue = [&](int kb) {   // block kb -> stage kb % 4; blocks past the end fetch zeros (keeps the wait counts uniform)
+  // The ring stage of a block is a compile-time constant (the loop below is unrolled over the ring), so that every LDS
+  // address is a per-lane constant plus an immediate offset: a stage taken from kb at run time costs an integer add per
+  // fragment read, a sixth of the loop's vector instructions.
+  auto issue = [&](int kb, auto stg) {   // block kb -> stage kb % NSTAGE = stg; blocks past the end fetch zeros (keeps the wait counts uniform)
     const uint32_t adv = kb < nkb ? (uint32_t)kb * (BKV * HD) : OOB;
-    const uint32_t base = lds_w + (uint32_t)(kb % NSTAGE) * STAGE;
+    const uint32_t base = lds_w + (uint32_t)decltype(stg)::value * STAGE;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       load_to_lds(rsrc_k, off_k[j] + adv, base + 1024u * j);
@@ -170,8 +174,8 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_kernel(FwdArgs a) {
   float l_run = 0.0f;         // this lane's share of sum_j rho_p p_ij
   float raw_max = -INFINITY;  // this lane's share of max_j (Q K^T)_ij, before scaling
 
-  auto scores = [&](int kb, v16f* st) {   // st[kt][r] = sum_d K[key][d] Q[q][d], key = 64 kb + 32 kt + 8 (r/4) + 4 g + (r%4)
-    const uint8_t* sk = smem + (kb % NSTAGE) * STAGE;
+  auto scores = [&](v16f* st, auto stg) {   // st[kt][r] = sum_d K[key][d] Q[q][d], key = 64 kb + 32 kt + 8 (r/4) + 4 g + (r%4)
+    const uint8_t* sk = smem + decltype(stg)::value * STAGE;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
@@ -189,18 +193,19 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_kernel(FwdArgs a) {
   };
 
   FOG_SETTLE(qf[0]); FOG_SETTLE(qf[1]);
-  issue(0);
-  issue(1);
+  issue(0, Stg<0>{});
+  issue(1, Stg<1>{});
   v16f sc[2];
 
   // One key block.
-  auto block = [&](int kb, v16f* sc) {
+  auto block = [&](int kb, v16f* sc, auto stg) {
+    constexpr int STG = decltype(stg)::value;
     // block kb landed (block kb + 1 may be in flight: vmcnt = 4), own LDS reads done (lgkmcnt = 0)
     __builtin_amdgcn_s_waitcnt(0x0074);
     __syncthreads();
-    issue(kb + 2);   // into the stage of block kb - 1, which every wave finished reading before the barrier
+    issue(kb + 2, Stg<(STG + 2) % NSTAGE>{});   // into the stage of block kb - 1, which every wave finished reading before the barrier
     if (kb < nkb_wave) {               // this wave needs the block: scores, softmax, P V
-      scores(kb, sc);
+      scores(sc, stg);
       const int key0 = kb * BKV;
       if (CAUSAL && key0 + BKV - 1 > q0) {   // causal mask on blocks that reach past the wave's first query
 #pragma unroll
@@ -253,7 +258,7 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_kernel(FwdArgs a) {
       }
       // O^T += V^T P^T.  Byte 4 qd' + b of dword (4 kt + qd') of pf is key key0 + 32 kt + 8 qd' + 4 g + b;
       // the V^T fragment lists its 32 keys in the same order (read r covers rows 16 r + vrow).
-      const uint8_t* sv = smem + (kb % NSTAGE) * STAGE + TILE_BYTES;
+      const uint8_t* sv = smem + STG * STAGE + TILE_BYTES;
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
         v8i vf;
@@ -267,7 +272,17 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_kernel(FwdArgs a) {
       }
     }
   };
-  for (int kb = 0; kb < nkb; ++kb) block(kb, sc);
+  static_assert(NSTAGE == 3, "the loop is unrolled over a ring of three stages");
+  int kb = 0;
+  for (; kb + NSTAGE <= nkb; kb += NSTAGE) {
+    block(kb, sc, Stg<0>{});
+    block(kb + 1, sc, Stg<1>{});
+    block(kb + 2, sc, Stg<2>{});
+  }
+  if (kb < nkb) {
+    block(kb, sc, Stg<0>{});
+    if (kb + 1 < nkb) block(kb + 1, sc, Stg<1>{});
+  }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
 
   if (!wave_on) return;
