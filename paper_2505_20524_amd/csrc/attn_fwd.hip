@@ -52,12 +52,17 @@ struct FwdArgs {
 };
 
 FOG_DEVICE float lane_xor32(float v) { return __shfl_xor(v, 32, 64); }
+// The larger of two values as the hardware's NaN-propagating maximum (v_maximum3_f32 takes three operands).  fmaxf has
+// to return the other operand when one is a NaN, and for that the compiler first passes every operand that comes
+// straight from a matrix instruction or a lane exchange through a quieting max(x, x): a dozen extra vector
+// instructions per key block.  On numbers the two agree; a NaN score makes its row NaN either way.
+FOG_DEVICE float vmax(float a, float b) { return __builtin_elementwise_maximum(a, b); }
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 // max of a lane's value and that of lane ^ 32 (both lanes get it), exchanged inside the vector ALU
 // (v_permlane32_swap: no trip through LDS in the middle of the softmax's dependency chain)
 FOG_DEVICE float pair_max32(float v) {
   const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  return vmax(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
 // LDS chunk swizzles (16-byte chunks inside a 128-byte row), applied by choosing which global chunk
@@ -221,15 +226,15 @@ __global__ __launch_bounds__(kThreads, 3) void attn_fwd_kernel(FwdArgs a) {
       for (int ch = 0; ch < 4; ++ch) {
         const v16f& x = sc[ch >> 1];
         const int b = 8 * (ch & 1);
-        float m = fmaxf(fmaxf(x[b], x[b + 1]), x[b + 2]);
-        m = fmaxf(fmaxf(m, x[b + 3]), x[b + 4]);
-        m = fmaxf(fmaxf(m, x[b + 5]), x[b + 6]);
-        cm[ch] = fmaxf(m, x[b + 7]);
+        float m = vmax(vmax(x[b], x[b + 1]), x[b + 2]);
+        m = vmax(vmax(m, x[b + 3]), x[b + 4]);
+        m = vmax(vmax(m, x[b + 5]), x[b + 6]);
+        cm[ch] = vmax(m, x[b + 7]);
       }
-      float bm = fmaxf(fmaxf(fmaxf(cm[0], cm[1]), cm[2]), cm[3]);
-      raw_max = fmaxf(raw_max, bm);
+      float bm = vmax(vmax(vmax(cm[0], cm[1]), cm[2]), cm[3]);
+      raw_max = vmax(raw_max, bm);
       bm = pair_max32(bm);
-      const float m_new = fmaxf(m_run, ceilf(bm * c));
+      const float m_new = vmax(m_run, ceilf(bm * c));
       if (__any(m_new != m_run)) {
         const float alpha = exp2f(m_run - m_new);   // exact power of two (0 on the first block)
         l_run *= alpha;
