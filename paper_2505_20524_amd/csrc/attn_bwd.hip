@@ -30,6 +30,10 @@ constexpr int STEP = 64;           // rows of the streamed operands per step
 constexpr int TILE = STEP * HD;    // 8 KB, 16-byte chunks swizzled by swz(row)
 constexpr int NSTAGE = 4;
 constexpr uint32_t OOB = 0x80000000u;
+// The ring stage of a block as a compile-time constant: the loops are unrolled over the ring so that every LDS address is a
+// per-lane constant plus an immediate offset (a stage taken from the block number at run time costs an integer add per
+// group of fragment reads).
+template <int N> struct Stg { static constexpr int value = N; };
 
 typedef __attribute__((address_space(3))) v2i* lds_v2i_ptr;
 
@@ -248,11 +252,11 @@ __global__ __launch_bounds__(kThreads, MODE == 0 ? 1 : 2) void attn_bwd_dkdv_ker
   const uint32_t lds_w = lds0 + 2048u * (uint32_t)__builtin_amdgcn_readfirstlane(w);
   const bool rows_d = __builtin_amdgcn_readfirstlane(w) & 1;   // odd waves fetch D, even waves lse (two copies each: identical bytes)
   int iss_i = 0, iss_g = 0;   // query block and head of the next block to issue (issue() is called once per block, in order)
-  auto issue = [&](int it) {  // block it of the stream -> stage it % 4; blocks past the end fetch zeros
+  auto issue = [&](auto stg) {  // the next block of the stream -> stage stg (= its number % 4); blocks past the end fetch zeros
     const uint32_t row0 = (uint32_t)(iss_g * S + (qb_first + iss_i) * STEP);
     const uint32_t adv = iss_g < G ? row0 * HD : OOB;
     const uint32_t radv = iss_g < G ? row0 * 4 : OOB;
-    const uint32_t base = (uint32_t)(it & (NSTAGE - 1)) * KV_STAGE;
+    const uint32_t base = (uint32_t)decltype(stg)::value * KV_STAGE;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       load16_to_lds(rsrc_q, off[j] + adv, lds_w + base + 1024u * j);
@@ -265,8 +269,8 @@ __global__ __launch_bounds__(kThreads, MODE == 0 ? 1 : 2) void attn_bwd_dkdv_ker
   const ColFrag cf = colfrag_addr();
 
   // S and dP tiles with lane = key: element r of tile qt is query qbase + 32 qt + 8 (r/4) + 4 g + (r%4)
-  auto scores = [&](int i, v16f* st, v16f* dp) {
-    const uint8_t* sq = smem + (i & (NSTAGE - 1)) * KV_STAGE;
+  auto scores = [&](auto stg, v16f* st, v16f* dp) {
+    const uint8_t* sq = smem + decltype(stg)::value * KV_STAGE;
     const uint8_t* sdo = sq + TILE;
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
@@ -285,33 +289,34 @@ __global__ __launch_bounds__(kThreads, MODE == 0 ? 1 : 2) void attn_bwd_dkdv_ker
 
   FOG_SETTLE(kf[0]); FOG_SETTLE(kf[1]);
   if (WANT_DK) { FOG_SETTLE(vf[0]); FOG_SETTLE(vf[1]); }
-  issue(0);
-  issue(1);
-  issue(2);
+  issue(Stg<0>{});
+  issue(Stg<1>{});
+  issue(Stg<2>{});
   __builtin_amdgcn_s_waitcnt(0x0F7A);  // vmcnt = 10: block 0 has landed (5 direct loads per thread and block)
   __syncthreads();
   v16f sa[2], da[2], sb[2], db[2];   // without the prefetch only sa / da are used
-  if (PREFETCH && skip == 0 && total > 0) scores(0, sa, da);
+  if (PREFETCH && skip == 0 && total > 0) scores(Stg<0>{}, sa, da);
 
   int cur_i = 0;
-  auto block = [&](const bool CLAMP_P, int it, v16f* st, v16f* dp, v16f* stn, v16f* dpn) __attribute__((always_inline)) {
+  auto block = [&](const bool CLAMP_P, auto stg, int it, v16f* st, v16f* dp, v16f* stn, v16f* dpn) __attribute__((always_inline)) {
+    constexpr int STG = decltype(stg)::value;   // = it % NSTAGE
     // vmcnt = 5: block it + 1 has landed (its scores are produced during this block); without the
     // prefetch only block it is needed and two younger blocks may stay in flight (vmcnt = 10).
     // lgkmcnt = 0: own LDS reads done
     if (PREFETCH) __builtin_amdgcn_s_waitcnt(0x0075);
     else if (it > 0) __builtin_amdgcn_s_waitcnt(0x007A);
     if (PREFETCH || it > 0) __syncthreads();
-    issue(it + 3);
+    issue(Stg<(STG + 3) % NSTAGE>{});   // block it + 3
     const int i = cur_i, i_next = i + 1 == nqb ? 0 : i + 1;   // query block within its head, of this block and of the next
     cur_i = i_next;
     const bool cur = i >= skip, nxt = i_next >= skip && it + 1 < total;
     if (PREFETCH) {
-      if (nxt) scores(it + 1, stn, dpn);
+      if (nxt) scores(Stg<(STG + 1) % NSTAGE>{}, stn, dpn);
     } else if (cur) {
-      scores(it, st, dp);
+      scores(stg, st, dp);
     }
     if (cur) {
-      const uint8_t* sq = smem + (it & (NSTAGE - 1)) * KV_STAGE;
+      const uint8_t* sq = smem + STG * KV_STAGE;
       const uint8_t* sdo = sq + TILE;
       const float* srow = reinterpret_cast<const float*>(sq + 2 * TILE);   // [0..63] lse - log2 rho_p, [64..127] D rho_ds / rho_p
       const int qbase = (qb_first + i) * STEP;
@@ -371,17 +376,17 @@ __global__ __launch_bounds__(kThreads, MODE == 0 ? 1 : 2) void attn_bwd_dkdv_ker
   };
   // The saturating form of the P cast is only needed for a scale above the format's maximum; the
   // choice is made once, outside the loop, so that the loop body stays one straight-line block.
-  if (clamp_p) {
-    for (int it = 0; it < total; it += 2) {   // two blocks per trip so that the score registers just swap roles
-      block(true, it, sa, da, sb, db);
-      if (it + 1 < total) block(true, it + 1, sb, db, sa, da);
+  // four blocks per trip: the ring stage is a constant in each copy, and the score registers just swap roles
+  auto trips = [&](const bool CLAMP_P) __attribute__((always_inline)) {
+    for (int it = 0; it < total; it += NSTAGE) {
+      block(CLAMP_P, Stg<0>{}, it, sa, da, sb, db);
+      if (it + 1 < total) block(CLAMP_P, Stg<1>{}, it + 1, sb, db, sa, da);
+      if (it + 2 < total) block(CLAMP_P, Stg<2>{}, it + 2, sa, da, sb, db);
+      if (it + 3 < total) block(CLAMP_P, Stg<3>{}, it + 3, sb, db, sa, da);
     }
-  } else {
-    for (int it = 0; it < total; it += 2) {
-      block(false, it, sa, da, sb, db);
-      if (it + 1 < total) block(false, it + 1, sb, db, sa, da);
-    }
-  }
+  };
+  if (clamp_p) trips(true);
+  else         trips(false);
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
   if (!wave_on) return;
   const float sdv = (*a.sinv_do) / rho_p;
@@ -444,9 +449,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(BwdArgs a) {
   uint32_t off[2];
   tile_load_offsets(off);
   const uint32_t lds_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(uintptr_t)smem + 2048u * w));
-  auto issue = [&](int kb) {
+  auto issue = [&](int kb, auto stg) {   // block kb -> stage kb % NSTAGE = stg
     const uint32_t adv = kb < nkb ? (uint32_t)kb * (STEP * HD) : OOB;
-    const uint32_t base = lds_w + (uint32_t)(kb & (NSTAGE - 1)) * (2 * TILE);
+    const uint32_t base = lds_w + (uint32_t)decltype(stg)::value * (2 * TILE);
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       load16_to_lds(rsrc_k, off[j] + adv, base + 1024u * j);
@@ -457,20 +462,21 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(BwdArgs a) {
   const ColFrag cf = colfrag_addr();
 
   FOG_SETTLE(qf[0]); FOG_SETTLE(qf[1]); FOG_SETTLE(dof[0]); FOG_SETTLE(dof[1]); FOG_SETTLE(lse); FOG_SETTLE(Dq);
-  issue(0);
-  issue(1);
-  issue(2);
+  issue(0, Stg<0>{});
+  issue(1, Stg<1>{});
+  issue(2, Stg<2>{});
   __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt = 8: block 0 has landed (4 direct loads per thread and block)
   __syncthreads();
 
-  for (int kb = 0; kb < nkb; ++kb) {
+  auto block = [&](int kb, auto stg) __attribute__((always_inline)) {
+    constexpr int STG = decltype(stg)::value;
     if (kb > 0) {
       __builtin_amdgcn_s_waitcnt(0x0078);  // vmcnt = 8: block kb landed (two younger blocks may be in flight); lgkmcnt = 0
       __syncthreads();
     }
-    issue(kb + 3);                         // into the stage of block kb - 1
-    if (kb >= nkb_wave) continue;
-    const uint8_t* sk = smem + (kb & (NSTAGE - 1)) * (2 * TILE);
+    issue(kb + 3, Stg<(STG + 3) % NSTAGE>{});   // into the stage of block kb - 1
+    if (kb >= nkb_wave) return;
+    const uint8_t* sk = smem + STG * (2 * TILE);
     const uint8_t* sv = sk + TILE;
     const int kbase = kb * STEP;
     // transposed tiles, lane = query: element r of tile kt is key kbase + 32 kt + 8 (r/4) + 4 g + (r%4)
@@ -518,6 +524,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(BwdArgs a) {
 #pragma unroll
     for (int d = 0; d < 4; ++d)
       dq[d] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(read_colfrag(sk, cf, d), dsf, dq[d], 0, 1, 0, 0, 0, 0);
+  };
+  static_assert(NSTAGE == 4, "the loops are unrolled over a ring of four stages");
+  for (int kb = 0; kb < nkb; kb += NSTAGE) {
+    block(kb, Stg<0>{});
+    if (kb + 1 < nkb) block(kb + 1, Stg<1>{});
+    if (kb + 2 < nkb) block(kb + 2, Stg<2>{});
+    if (kb + 3 < nkb) block(kb + 3, Stg<3>{});
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no direct load may still be writing LDS when the workgroup retires
   if (!wave_on) return;
