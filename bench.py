@@ -347,7 +347,7 @@ def main():
             l0 = blk.linears[0]
             patterns["the step's own operands (first 32 KB of X~ and of W~ of %s)" % l0.lin.name] = torch.cat(
                 [l0.X.q.reshape(-1)[:32768], l0.W.q.reshape(-1)[:32768]]).contiguous()
-        sink = torch.empty(1024 * 256, device="cuda")
+        sink = torch.empty(1024 * 512 + 4096, device="cuda")
         ceilings = {"mfma_loop": {}}
         for name, pat in patterns.items():
             fog.probe_mfma_rate(pat, 2000, sink)
@@ -369,6 +369,18 @@ def main():
                 "vector_ops": [0, 4, 8, 16, 32],
                 "with_matrix_instruction": [fog.probe_mfma_coissue(op, n, True, 2000, sink) for n in (0, 4, 8, 16, 32)],
                 "vector_ops_alone": [fog.probe_mfma_coissue(op, n, False, 2000, sink) for n in (0, 4, 8, 16, 32)]}
+        # Whether one wave's vector work runs under ANOTHER wave's matrix instructions on the same SIMD: two waves per SIMD with
+        # separate roles, each measured alone and while the other role (given more trips, so that it outlasts) is running.
+        ceilings["cross_wave_cycles"] = {}
+        for op, name in ((0, "v_fma_f32"), (1, "v_exp_f32"), (2, "v_cvt_pk_fp8_f32"), (3, "softmax quarter group (fma, exp, add, max3 | convert)")):
+            n_ops, trips = 8, 2000
+            _, v_alone = fog.probe_mfma_cross_wave(op, n_ops, 0, trips, sink)
+            m_alone, _ = fog.probe_mfma_cross_wave(op, n_ops, trips, 0, sink)
+            _, v_under = fog.probe_mfma_cross_wave(op, n_ops, int(trips * v_alone * 8 / 512 * 1.5) + trips, trips, sink)
+            m_under, _ = fog.probe_mfma_cross_wave(op, n_ops, trips, int(trips * 512 / (v_alone * 8) * 1.5) + 64, sink)
+            ceilings["cross_wave_cycles"][name] = {
+                "vector_ops_per_group": n_ops, "vector_group_alone": v_alone, "vector_group_under_matrix_wave": v_under,
+                "matrix_instruction_alone": m_alone, "matrix_instruction_under_vector_wave": m_under}
         # HBM: the abs-max kernel as a plain read (2 B per element) and a device copy, over buffers that do not fit the caches
         big = torch.empty(1 << 30, dtype=torch.int16, device="cuda")            # 2 GiB
         big.zero_()

@@ -70,6 +70,21 @@ fog_status fog_probe_mfma_coissue(int op, int vector_ops, int with_mfma, int ite
                                   double* cycles_per_slot, void* stream);
 
 /*
+ * Whether the vector work of one wave runs under the matrix instructions of ANOTHER wave on the same SIMD.  Workgroups of
+ * eight waves, one per compute unit: waves 0-3 issue nothing but independent v_mfma_f32_32x32x64_f8f6f4 (iters_matrix
+ * trips of eight), waves 4-7, which share their SIMDs, nothing but the vector operations of fog_probe_mfma_coissue
+ * (iters_vector trips of eight groups of `vector_ops` operations).  Each role counts its own shader cycles:
+ *   matrix_cycles_per_instruction : 64 when the matrix wave is not held up;
+ *   vector_cycles_per_group       : to be compared with the same call with iters_matrix = 0 (the vector waves alone).
+ * With trip counts chosen so that one role outlasts the other, the shorter role is measured entirely under the longer one.
+ *   op : as in fog_probe_mfma_coissue.   vector_ops : 8 or 32.   Both results are HOST pointers.
+ *   sink : DEVICE pointer, 8-byte aligned, compute units * 512 floats + compute units * 16 bytes.
+ * Errors: NULL, SHAPE, ALIGN, WORKSPACE, HIP.  Synchronises the stream.
+ */
+fog_status fog_probe_mfma_cross_wave(int op, int vector_ops, int iters_matrix, int iters_vector, float* sink, size_t sink_bytes,
+                                     double* matrix_cycles_per_instruction, double* vector_cycles_per_group, void* stream);
+
+/*
  * The NT product of fog_fp8_gemm (E4M3 x E4M3) with the epilogue of every tile left out: the same kernel, the same
  * operand loads and matrix instructions, but no tile is scaled, converted, staged or stored (C stays untouched).
  * Timed next to fog_fp8_gemm on the same operands it shows what the epilogues cost a launch, which is what a kernel

@@ -45,6 +45,9 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(const uint8_t* __restric
   sink[(size_t)blockIdx.x * 256 + t] = s;
 }
 
+// the hardware's NaN-propagating maximum, as in the forward kernel (no quieting max(x, x) of the operands)
+__device__ __forceinline__ float vmax(float a, float b) { return __builtin_elementwise_maximum(a, b); }
+
 // WHAT 0: score products, softmax arithmetic, P V products; 1: the products only; 2: the arithmetic only.
 // One key block the way the forward kernel takes it: scores into the one set of score registers, softmax, P V.
 template <int WHAT>
@@ -67,12 +70,12 @@ __device__ __forceinline__ void attention_block(v8i* kf, const v8i* qf, const v8
     for (int ch = 0; ch < 4; ++ch) {
       const v16f& x = sc[ch >> 1];
       const int b = 8 * (ch & 1);
-      float m = fmaxf(fmaxf(x[b], x[b + 1]), x[b + 2]);
-      m = fmaxf(fmaxf(m, x[b + 3]), x[b + 4]);
-      m = fmaxf(fmaxf(m, x[b + 5]), x[b + 6]);
-      cm[ch] = fmaxf(m, x[b + 7]);
+      float m = vmax(vmax(x[b], x[b + 1]), x[b + 2]);
+      m = vmax(vmax(m, x[b + 3]), x[b + 4]);
+      m = vmax(vmax(m, x[b + 5]), x[b + 6]);
+      cm[ch] = vmax(m, x[b + 7]);
     }
-    m_run = fmaxf(m_run, fmaxf(fmaxf(fmaxf(cm[0], cm[1]), cm[2]), cm[3]) * c);
+    m_run = vmax(m_run, vmax(vmax(vmax(cm[0], cm[1]), cm[2]), cm[3]) * c);
     const float shift = 3.0f - m_run;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
@@ -196,6 +199,69 @@ void coissue_launch(int nv, int grid, float* sink, int iters, long long* cycles,
   }
 }
 
+// Two waves per SIMD with separate roles (waves w and w + 4 of a workgroup share a SIMD): waves 0-3 issue nothing but
+// independent matrix instructions, waves 4-7 nothing but the vector operations.  Each role counts its own cycles.
+template <int OP, int NV>
+__global__ __launch_bounds__(512) void cross_wave_kernel(float* __restrict__ sink, int iters_matrix, int iters_vector,
+                                                         long long* __restrict__ cycles) {
+  const int t = threadIdx.x;
+  const bool vector_role = __builtin_amdgcn_readfirstlane(t >> 8) != 0;
+  float s = 0.0f;
+  long long c0 = 0, c1 = 0;
+  if (!vector_role) {
+    v8i a[2], b[2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      a[0][i] = 0x30313233 + t * (i + 1); a[1][i] = 0x2c2d2e2f + t * (i + 3);
+      b[0][i] = 0x34353637 ^ (t << i); b[1][i] = 0x31323334 ^ (t << (i + 1));
+    }
+    v16f acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+    c0 = __builtin_readcyclecounter();
+    for (int it = 0; it < iters_matrix; ++it) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        acc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[j & 1], b[(j >> 1) & 1], acc[j], 0, 0, 0, 0, 0, 0);
+    }
+    c1 = __builtin_readcyclecounter();
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += acc[j][r];
+  } else {
+    float x[8], y[4] = {0, 0, 0, 0}, z[4] = {1, 1, 1, 1}, u[4] = {0, 0, 0, 0}, m3[2] = {0, 0};
+    uint32_t pq[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = 0.001f * (t + i);
+    c0 = __builtin_readcyclecounter();
+    for (int it = 0; it < iters_vector; ++it) {
+#pragma unroll
+      for (int v = 0; v < 8 * NV; ++v) {
+        if (OP == 0) asm volatile("v_fma_f32 %0, %0, %1, %0" : "+v"(x[v & 7]) : "v"(x[(v + 1) & 7]));
+        if (OP == 1) asm volatile("v_exp_f32 %0, %0" : "+v"(x[v & 7]));
+        if (OP == 2) asm volatile("v_cvt_pk_fp8_f32 %0, %1, %2" : "=v"(pq[v & 3]) : "v"(x[v & 7]), "v"(x[(v + 1) & 7]));
+        if (OP == 3) {
+          asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(y[v & 3]) : "v"(x[v & 7]), "v"(x[(v + 1) & 7]), "v"(x[(v + 2) & 7]));
+          asm volatile("v_exp_f32 %0, %1" : "=v"(z[v & 3]) : "v"(y[(v + 2) & 3]));
+          asm volatile("v_add_f32 %0, %1, %2" : "=v"(u[v & 3]) : "v"(z[(v + 2) & 3]), "v"(u[(v + 1) & 3]));
+          if (v & 1) asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(m3[(v >> 1) & 1]) : "v"(x[v & 7]), "v"(x[(v + 3) & 7]), "v"(m3[((v >> 1) + 1) & 1]));
+          else asm volatile("v_cvt_pk_fp8_f32 %0, %1, %2" : "=v"(pq[(v >> 1) & 3]) : "v"(z[v & 3]), "v"(z[(v + 1) & 3]));
+        }
+      }
+    }
+    c1 = __builtin_readcyclecounter();
+    s = y[0] + y[1] + y[2] + y[3] + z[0] + z[1] + z[2] + z[3] + u[0] + u[1] + u[2] + u[3] + m3[0] + m3[1];
+    s += (float)(pq[0] ^ pq[1] ^ pq[2] ^ pq[3]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += x[i];
+  }
+  sink[(size_t)blockIdx.x * 512 + t] = s;
+  if ((t & 255) == 0) cycles[2 * blockIdx.x + (t >> 8)] = c1 - c0;
+}
+
 }  // namespace
 
 extern "C" fog_status fog_probe_attention_loop(int what, int waves_per_simd, int iters, float* sink, size_t sink_bytes,
@@ -298,5 +364,47 @@ extern "C" fog_status fog_probe_mfma_coissue(int op, int vector_ops, int with_mf
   double sum = 0.0;
   for (int i = 0; i < n; ++i) sum += (double)host[i];
   *cycles_per_slot = sum / n / iters / 8.0;
+  return FOG_OK;
+}
+
+extern "C" fog_status fog_probe_mfma_cross_wave(int op, int vector_ops, int iters_matrix, int iters_vector, float* sink, size_t sink_bytes,
+                                                double* matrix_cycles_per_instruction, double* vector_cycles_per_group, void* stream) {
+  if (!sink || !matrix_cycles_per_instruction || !vector_cycles_per_group) return FOG_ERR_NULL;
+  if (iters_matrix < 0 || iters_vector < 0 || iters_matrix + iters_vector < 1 || op < 0 || op > 3) return FOG_ERR_SHAPE;
+  if (vector_ops != 8 && vector_ops != 32) return FOG_ERR_SHAPE;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    return FOG_ERR_HIP;
+  // the sink's tail holds two cycle counts per workgroup (8 bytes each, 8-byte aligned)
+  const size_t cyc_off = ((size_t)cus * 512 * sizeof(float) + 7) & ~(size_t)7;
+  if (sink_bytes < cyc_off + (size_t)cus * 2 * sizeof(long long)) return FOG_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(sink) & 7u) != 0) return FOG_ERR_ALIGN;
+  long long* cycles = reinterpret_cast<long long*>(reinterpret_cast<char*>(sink) + cyc_off);
+  hipStream_t s = (hipStream_t)stream;
+  auto launch = [&](int nm, int nv) {
+    if (vector_ops == 8) {
+      if (op == 0) cross_wave_kernel<0, 8><<<cus, 512, 0, s>>>(sink, nm, nv, cycles);
+      else if (op == 1) cross_wave_kernel<1, 8><<<cus, 512, 0, s>>>(sink, nm, nv, cycles);
+      else if (op == 2) cross_wave_kernel<2, 8><<<cus, 512, 0, s>>>(sink, nm, nv, cycles);
+      else cross_wave_kernel<3, 8><<<cus, 512, 0, s>>>(sink, nm, nv, cycles);
+    } else {
+      if (op == 0) cross_wave_kernel<0, 32><<<cus, 512, 0, s>>>(sink, nm, nv, cycles);
+      else if (op == 1) cross_wave_kernel<1, 32><<<cus, 512, 0, s>>>(sink, nm, nv, cycles);
+      else if (op == 2) cross_wave_kernel<2, 32><<<cus, 512, 0, s>>>(sink, nm, nv, cycles);
+      else cross_wave_kernel<3, 32><<<cus, 512, 0, s>>>(sink, nm, nv, cycles);
+    }
+  };
+  launch(iters_matrix < 32 ? iters_matrix : 32, iters_vector < 32 ? iters_vector : 32);   // warm-up
+  launch(iters_matrix, iters_vector);
+  fog_status st = fog_launch_status();
+  if (st != FOG_OK) return st;
+  if (hipStreamSynchronize(s) != hipSuccess) return FOG_ERR_HIP;
+  static thread_local long long host[2048];
+  const int n = cus < 1024 ? cus : 1024;
+  if (hipMemcpy(host, cycles, (size_t)n * 2 * sizeof(long long), hipMemcpyDeviceToHost) != hipSuccess) return FOG_ERR_HIP;
+  double sm = 0.0, sv = 0.0;
+  for (int i = 0; i < n; ++i) { sm += (double)host[2 * i]; sv += (double)host[2 * i + 1]; }
+  *matrix_cycles_per_instruction = iters_matrix ? sm / n / iters_matrix / 8.0 : 0.0;
+  *vector_cycles_per_group = iters_vector ? sv / n / iters_vector / 8.0 : 0.0;
   return FOG_OK;
 }

@@ -57,6 +57,7 @@ PROBE_SIGNATURES = {
     "fog_probe_mfma_rate": (_I, [_P, _I, _P, _SZ, _c.POINTER(_c.c_double), _c.POINTER(_c.c_double), _P]),
     "fog_probe_attention_loop": (_I, [_I, _I, _I, _P, _SZ, _c.POINTER(_c.c_double), _P]),
     "fog_probe_mfma_coissue": (_I, [_I, _I, _I, _I, _P, _SZ, _c.POINTER(_c.c_double), _P]),
+    "fog_probe_mfma_cross_wave": (_I, [_I, _I, _I, _I, _P, _SZ, _c.POINTER(_c.c_double), _c.POINTER(_c.c_double), _P]),
     "fog_probe_gemm_products_only": (_I, [_I64, _I64, _I64, _P, _I64, _P, _I64, _P, _P, _P, _I64, _P]),
 }
 
@@ -283,6 +284,15 @@ def probe_mfma_coissue(op, vector_ops, with_mfma, iters, sink, stream=None):
     _check(load().fog_probe_mfma_coissue(op, vector_ops, int(with_mfma), iters, _ptr(sink), sink.numel() * sink.element_size(),
                                          _c.byref(cyc), _stream(stream)), "fog_probe_mfma_coissue")
     return cyc.value
+
+
+def probe_mfma_cross_wave(op, vector_ops, iters_matrix, iters_vector, sink, stream=None):
+    """(cycles per matrix instruction of the matrix waves, cycles per group of vector_ops operations of the vector waves that
+    share their SIMDs); a role with zero trips is absent."""
+    cm, cv = _c.c_double(0.0), _c.c_double(0.0)
+    _check(load().fog_probe_mfma_cross_wave(op, vector_ops, iters_matrix, iters_vector, _ptr(sink), sink.numel() * sink.element_size(),
+                                            _c.byref(cm), _c.byref(cv), _stream(stream)), "fog_probe_mfma_cross_wave")
+    return cm.value, cv.value
 
 
 def probe_gemm_products_only(M, N, K, A, sinv_a, B, sinv_b, C, stream=None):

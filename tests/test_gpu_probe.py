@@ -77,3 +77,27 @@ def test_products_only_gemm_probe_runs_writes_nothing_and_checks_arguments():
     assert call(M, N, K, None, C.data_ptr()) == 1
     assert call(M, N, K, A.data_ptr() + 1, C.data_ptr()) == 3
     assert call(0, N, K, A.data_ptr(), C.data_ptr()) == 2
+
+
+def test_cross_wave_probe_shows_overlap_between_waves_and_checks_arguments():
+    """A matrix-only wave keeps its 64 cycles per instruction while a vector-only wave shares its SIMD, and the vector wave
+    slows down by far less than the matrix time it runs under (the two units do overlap across waves)."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.zeros(cus * 512 + cus * 4 + 16, device="cuda")
+    _, v_alone = fog.probe_mfma_cross_wave(0, 8, 0, 500, sink)
+    m_alone, _ = fog.probe_mfma_cross_wave(0, 8, 500, 0, sink)
+    m_long, v_under = fog.probe_mfma_cross_wave(0, 8, 1500, 500, sink)      # 1500 x 512 cycles of matrix work outlast the vector trips
+    assert 63.0 <= m_alone <= 70.0 and 63.0 <= m_long <= 70.0
+    assert 30.0 <= v_alone <= 60.0                                            # eight fused multiply-adds: 4-5 cycles each plus the loop
+    assert v_alone <= v_under <= v_alone + 0.5 * 64.0
+    lib = fog.load()
+    import ctypes as C
+    a, b = C.c_double(0.0), C.c_double(0.0)
+    nbytes = sink.numel() * 4
+    call = lib.fog_probe_mfma_cross_wave
+    assert call(0, 8, 10, 10, sink.data_ptr(), nbytes, None, C.byref(b), None) == 1
+    assert call(4, 8, 10, 10, sink.data_ptr(), nbytes, C.byref(a), C.byref(b), None) == 2
+    assert call(0, 16, 10, 10, sink.data_ptr(), nbytes, C.byref(a), C.byref(b), None) == 2
+    assert call(0, 8, 0, 0, sink.data_ptr(), nbytes, C.byref(a), C.byref(b), None) == 2
+    assert call(0, 8, 10, 10, sink.data_ptr() + 4, nbytes - 4, C.byref(a), C.byref(b), None) == 3
+    assert call(0, 8, 10, 10, sink.data_ptr(), 1024, C.byref(a), C.byref(b), None) == 5
