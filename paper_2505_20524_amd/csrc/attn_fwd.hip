@@ -20,11 +20,12 @@
 //
 // Pipeline.  K and V blocks stream from global memory straight into a 3-stage LDS ring (buffer_load ... lds), two
 // blocks in flight.  A wave takes a block through scores, softmax and P V one after the other and keeps a single
-// set of score registers: 168 registers per lane, so THREE workgroups share a CU (three waves per SIMD) and one
+// set of score registers: under 168 registers per lane, so THREE workgroups share a CU (three waves per SIMD) and one
 // wave's exponentials and converts run under another's matrix instructions and LDS waits.  (Producing the next
 // block's scores ahead of the softmax needs a second score set, 229 registers and two waves per SIMD: 5 % slower.)
 // The softmax costs about 4 vector instructions per score (max3, fma, exp2, add, half a convert): with FP8 the
-// kernel is bound by the vector ALU's issue, not by the matrix core.
+// kernel is bound by the vector ALU's issue, not by the matrix core, and every vector instruction that is not
+// arithmetic (address adds, quieting moves) counts: see the notes at Stg and vmax.
 #include "common.h"
 #include "launch.h"
 
