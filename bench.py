@@ -357,9 +357,10 @@ def main():
         # cores and the vector ALU overlap on this part, at one to three waves per SIMD.
         ceilings["attention_loop_ns_per_wave_block"] = {}
         for wps in (1, 2, 3):
-            t_all, t_mfma, t_valu = (fog.probe_attention_loop(w, wps, 3000, sink) for w in (0, 1, 2))
+            t_all, t_mfma, t_valu, t_ilv = (fog.probe_attention_loop(w, wps, 3000, sink) for w in (0, 1, 2, 3))
             ceilings["attention_loop_ns_per_wave_block"]["%d waves per SIMD" % wps] = {
                 "everything": t_all, "matrix instructions only": t_mfma, "softmax arithmetic only": t_valu,
+                "everything, P V products dealt out between the softmax groups": t_ilv,
                 "matrix_core_share_of_everything": t_mfma / t_all}
         # What one matrix instruction takes from the vector ALU of its own wave: shader cycles per slot (one matrix instruction
         # followed by n vector operations, order pinned), and the same vector operations alone.

@@ -43,11 +43,14 @@ fog_status fog_probe_mfma_rate(const uint8_t* operand_bytes, int iters, float* s
  * lane's 32 scores (max, fused multiply-add, exp2, row-sum add, two packed FP8 converts per four values) and four
  * P V products.  Timed three ways on a grid of compute units * waves_per_simd workgroups of four waves:
  *   what = 0 : everything;   what = 1 : the eight matrix instructions only;   what = 2 : the softmax arithmetic only.
+ *   what = 3 : everything, with the four P V products of the PREVIOUS block dealt out between the four groups of eight scores
+ *              of this block's softmax (one matrix instruction, then eight scores' worth of vector work, order pinned): what an
+ *              interleave inside the wave gains over taking the phases in turn.
  * If the matrix cores and the vector ALU overlapped perfectly, time(0) would be max(time(1), time(2)); what the part
  * does with this mix is an upper bound for any attention kernel built from these instructions.
  *   ns_per_block : HOST pointer, receives nanoseconds per key block and wave, divided by waves_per_simd (the time a SIMD
  *                  spends per wave-block).   sink : as in fog_probe_mfma_rate, compute units * waves_per_simd * 256 floats.
- * Errors: NULL, SHAPE (iters < 1, waves_per_simd outside 1..3, what outside 0..2), WORKSPACE (sink too small), HIP.
+ * Errors: NULL, SHAPE (iters < 1, waves_per_simd outside 1..3, what outside 0..3), WORKSPACE (sink too small), HIP.
  */
 fog_status fog_probe_attention_loop(int what, int waves_per_simd, int iters, float* sink, size_t sink_bytes,
                                     double* ns_per_block, void* stream);

@@ -101,6 +101,52 @@ __device__ __forceinline__ void attention_block(v8i* kf, const v8i* qf, const v8
   }
 }
 
+// WHAT 3: the same work with the P V products of the PREVIOUS block dealt out between the four groups of eight scores of
+// this block's softmax (order pinned): a matrix instruction, then the exponentials, sums and converts of eight scores.
+__device__ __forceinline__ void attention_block_interleaved(v8i* kf, const v8i* qf, const v8i* vf, const v16f& zero16, v16f* sc,
+                                                            v16f* o, v8i& pf_prev, float& l_run, float& m_run, float c) {
+  asm volatile("" : "+v"(kf[0]), "+v"(kf[1]));
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) {
+    sc[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf[kt], qf[0], zero16, 0, 0, 0, 0, 0, 0);
+    sc[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf[kt], qf[1], sc[kt], 0, 0, 0, 0, 0, 0);
+  }
+  float cm[4];
+#pragma unroll
+  for (int ch = 0; ch < 4; ++ch) {
+    const v16f& x = sc[ch >> 1];
+    const int b = 8 * (ch & 1);
+    float m = vmax(vmax(x[b], x[b + 1]), x[b + 2]);
+    m = vmax(vmax(m, x[b + 3]), x[b + 4]);
+    m = vmax(vmax(m, x[b + 5]), x[b + 6]);
+    cm[ch] = vmax(m, x[b + 7]);
+  }
+  m_run = vmax(m_run, vmax(vmax(vmax(cm[0], cm[1]), cm[2]), cm[3]) * c);
+  const float shift = 3.0f - m_run;
+  v8i pf;
+#pragma unroll
+  for (int grp = 0; grp < 4; ++grp) {
+    __builtin_amdgcn_sched_barrier(0);
+    o[grp] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vf[grp], pf_prev, o[grp], 0, 0, 0, 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    const int kt = grp >> 1;
+#pragma unroll
+    for (int qq = 0; qq < 2; ++qq) {
+      const int qd = 2 * (grp & 1) + qq;
+      const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 0], c, shift));
+      const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 1], c, shift));
+      const float e2 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 2], c, shift));
+      const float e3 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kt][4 * qd + 3], c, shift));
+      l_run += (e0 + e1) + (e2 + e3);
+      const uint32_t pk = __builtin_amdgcn_cvt_pk_fp8_f32(e0, e1, any_u32(), false);
+      pf[4 * kt + qd] = (int)__builtin_amdgcn_cvt_pk_fp8_f32(e2, e3, pk, true);
+    }
+    asm volatile("" : "+v"(pf[4 * kt + 2 * (grp & 1)]), "+v"(pf[4 * kt + 2 * (grp & 1) + 1]), "+v"(l_run));
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  pf_prev = pf;
+}
+
 template <int WHAT>
 __global__ __launch_bounds__(256, 3) void attention_loop_kernel(float* __restrict__ sink, int iters) {
   const int t = threadIdx.x;
@@ -122,7 +168,15 @@ __global__ __launch_bounds__(256, 3) void attention_loop_kernel(float* __restric
   }
   float l_run = 0.0f, m_run = 0.0f;
   const float c = 1e-6f;
-  for (int it = 0; it < iters; ++it) attention_block<WHAT>(kf, qf, vf, zero16, sc, o, l_run, m_run, c, it);
+  if (WHAT == 3) {
+    v8i pf_prev;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pf_prev[i] = 0x38383838;
+    for (int it = 0; it < iters; ++it) attention_block_interleaved(kf, qf, vf, zero16, sc, o, pf_prev, l_run, m_run, c);
+    asm volatile("" ::"v"(pf_prev));
+  } else {
+    for (int it = 0; it < iters; ++it) attention_block<(WHAT == 3 ? 0 : WHAT)>(kf, qf, vf, zero16, sc, o, l_run, m_run, c, it);
+  }
   float s = l_run + m_run;
 #pragma unroll
   for (int d = 0; d < 4; ++d)
@@ -267,7 +321,7 @@ __global__ __launch_bounds__(512) void cross_wave_kernel(float* __restrict__ sin
 extern "C" fog_status fog_probe_attention_loop(int what, int waves_per_simd, int iters, float* sink, size_t sink_bytes,
                                                double* ns_per_block, void* stream) {
   if (!sink || !ns_per_block) return FOG_ERR_NULL;
-  if (iters < 1 || waves_per_simd < 1 || waves_per_simd > 3 || what < 0 || what > 2) return FOG_ERR_SHAPE;
+  if (iters < 1 || waves_per_simd < 1 || waves_per_simd > 3 || what < 0 || what > 3) return FOG_ERR_SHAPE;
   int dev = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
     return FOG_ERR_HIP;
@@ -280,7 +334,8 @@ extern "C" fog_status fog_probe_attention_loop(int what, int waves_per_simd, int
   auto launch = [&](int n) {
     if (what == 0) attention_loop_kernel<0><<<grid, 256, 0, s>>>(sink, n);
     else if (what == 1) attention_loop_kernel<1><<<grid, 256, 0, s>>>(sink, n);
-    else attention_loop_kernel<2><<<grid, 256, 0, s>>>(sink, n);
+    else if (what == 2) attention_loop_kernel<2><<<grid, 256, 0, s>>>(sink, n);
+    else attention_loop_kernel<3><<<grid, 256, 0, s>>>(sink, n);
   };
   launch(iters < 32 ? iters : 32);   // warm-up
   (void)hipEventRecord(e0, s);

@@ -31,11 +31,13 @@ def test_attention_loop_probe_orders_its_three_timings():
     t_all, t_mfma, t_valu = (fog.probe_attention_loop(w, 2, 500, sink) for w in (0, 1, 2))
     assert 0 < t_mfma <= t_all * 1.05 and 0 < t_valu <= t_all * 1.05        # a part cannot take longer than the whole
     assert t_all <= (t_mfma + t_valu) * 1.15                                 # and the whole no longer than the parts in sequence
+    t_ilv = fog.probe_attention_loop(3, 2, 500, sink)                        # the same work, interleaved inside the wave
+    assert t_mfma <= t_ilv * 1.05 and t_ilv <= (t_mfma + t_valu) * 1.15
     lib = fog.load()
     ns = ctypes.c_double(0)
     st = torch.cuda.current_stream().cuda_stream
     assert lib.fog_probe_attention_loop(0, 4, 10, sink.data_ptr(), sink.numel() * 4, ctypes.byref(ns), st) == 2
-    assert lib.fog_probe_attention_loop(3, 1, 10, sink.data_ptr(), sink.numel() * 4, ctypes.byref(ns), st) == 2
+    assert lib.fog_probe_attention_loop(4, 1, 10, sink.data_ptr(), sink.numel() * 4, ctypes.byref(ns), st) == 2
     assert lib.fog_probe_attention_loop(0, 1, 10, None, 0, ctypes.byref(ns), st) == 1
     assert lib.fog_probe_attention_loop(0, 2, 10, sink.data_ptr(), 64, ctypes.byref(ns), st) == 5
 
