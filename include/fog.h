@@ -189,6 +189,33 @@ size_t fog_quantize_delayed_state(void);
 fog_status fog_delayed_amax(const void* state, int64_t step, float* amax, void* stream);
 
 /*
+ * fog_quantize_delayed for up to FOG_CAST_BATCH_MAX tensors in ONE launch (a launch costs about 4 us of ramp and tail
+ * whatever it does; the casts of a layer's tensors are independent of each other).  Same results, bit for bit, as the
+ * calls one by one with the same `step`.  A job describes a dense row-major tensor (ldx = ldq = cols, no transposed
+ * copy) of rows * cols elements, a multiple of 16, at 16-byte aligned x_bf16 and q; history, state, amax_prev, scale and
+ * scale_inv are as in fog_quantize_delayed and belong to that tensor alone (no two jobs may share any of them).
+ *   jobs : HOST array of `count` (0..FOG_CAST_BATCH_MAX) descriptions, read before the call returns.
+ *   step : the call number, the same for every job of the batch (tensors cast once per training step).
+ * Errors: NULL, SHAPE (count, non-positive sizes, history_len < 1, step < 0, margin), ALIGN, WORKSPACE (a state too
+ * small), UNSUPPORTED (a format, or a size that is not a multiple of 16: cast that tensor with fog_quantize_delayed).
+ */
+typedef struct {
+  const void* x_bf16;
+  int64_t rows, cols;
+  fog_fp8 fmt;
+  int margin;
+  float* history;
+  int history_len;
+  void* state;
+  size_t state_bytes;
+  uint8_t* q;
+  float* amax_prev;   /* may be NULL */
+  float* scale;
+  float* scale_inv;   /* may be NULL */
+} fog_delayed_job;
+fog_status fog_quantize_delayed_batch(const fog_delayed_job* jobs, int count, int64_t step, void* stream);
+
+/*
  * QK RMS normalisation with a frozen gain, fused with the FP8 cast (Section 3: N_gamma(x) =
  * gamma x / rms(x), rms(x) = ||x||_2 / sqrt(D), applied to every query / key vector; the FOG
  * variants freeze the gains and Appendix A folds their value into the softmax scale, which

@@ -90,10 +90,25 @@ class CastBatch:
         self.jobs = fog.make_cast_jobs([(c.x, c.fmt, c.q, c.amax, c.scale, c.sinv) for c in self.batched])
         self.ws = torch.empty(max(fog.quantize_jit_batch_workspace(len(self.batched)), 16), dtype=torch.uint8, device="cuda")
         self.bytes = sum(c.bytes_jit for c in self.batched)
+        self.delayed_jobs = None   # built on the first delayed-scaling pass
 
     def run(self, timer=None, delayed=False):
         if delayed:
-            for c in self.batched + self.single:
+            # one launch for the batch (fog_quantize_delayed_batch); what the batched call does not cover goes one by one
+            if self.batched:
+                if self.delayed_jobs is None:
+                    for c in self.batched:
+                        c.history = torch.zeros(1024, device="cuda")
+                        c.state = torch.zeros(fog.quantize_delayed_state(), dtype=torch.uint8, device="cuda")
+                    self.delayed_jobs = fog.make_delayed_jobs([(c.x, c.fmt, c.q, c.history, c.state, c.amax, c.scale, c.sinv) for c in self.batched])
+                    self.delayed_step = 0
+                if timer:
+                    timer.begin("cast_delayed", sum(c.bytes_jit - 2 * c.x.numel() for c in self.batched), launches=len(self.batched))
+                fog.quantize_delayed_batch(self.delayed_jobs, self.delayed_step)
+                if timer:
+                    timer.end()
+                self.delayed_step += 1
+            for c in self.single:
                 c.run_delayed(timer)
             return
         if self.batched:

@@ -387,6 +387,39 @@ __global__ __launch_bounds__(kThreads) void quantize_batch_kernel(BatchJobs b, c
   else                      quantize_rows_body<FOG_E5M2, false>(b.x[j], 1, chunks, chunks * 16, nullptr, b.q[j], chunks * 16, nullptr, js, bid, nb);
 }
 
+// ---------------------------------------------------------------- several tensors per launch (delayed scaling)
+// fog_quantize_delayed for up to kBatchMax contiguous tensors in ONE launch: a workgroup finds its job from the prefix
+// sums and does, inside it, exactly what it does in the one-tensor launch (the history update and the scale from the
+// previous pass's maxima, the cast, this pass's maxima into the job's own state).
+struct DelayedJobs {
+  int count;
+  int first[kBatchMax + 1];        // first workgroup of each job (prefix sums)
+  int prev_off, cur_off, next_off; // word offsets of the three rotating buffers inside a job's state (the same for every job)
+  const uint16_t* x[kBatchMax];
+  int64_t n[kBatchMax];            // elements, a multiple of 16
+  uint8_t* q[kBatchMax];
+  int fmt[kBatchMax], margin[kBatchMax];
+  float* amax_prev[kBatchMax];
+  float* scale[kBatchMax];
+  float* scale_inv[kBatchMax];
+  float* hist[kBatchMax];
+  int hlen[kBatchMax], slot[kBatchMax];
+  uint32_t* state[kBatchMax];
+};
+
+__global__ __launch_bounds__(kThreads) void quantize_delayed_batch_kernel(DelayedJobs b) {
+  int j = 0;
+  for (int k = 1; k < b.count; ++k)
+    if ((int)blockIdx.x >= b.first[k]) j = k;
+  const int bid = (int)blockIdx.x - b.first[j], nb = b.first[j + 1] - b.first[j];
+  uint32_t* st = b.state[j];
+  const ScaleSource js{st + b.prev_off, kDelayedSlots, b.fmt[j], b.margin[j], b.amax_prev[j], b.scale[j], b.scale_inv[j],
+                       b.hist[j], b.hlen[j], b.slot[j], st + b.cur_off, st + b.next_off};
+  const int64_t chunks = b.n[j] / 16;
+  if (b.fmt[j] == FOG_E4M3) quantize_rows_body<FOG_E4M3, true>(b.x[j], 1, chunks, chunks * 16, nullptr, b.q[j], chunks * 16, st + b.cur_off, js, bid, nb);
+  else                      quantize_rows_body<FOG_E5M2, true>(b.x[j], 1, chunks, chunks * 16, nullptr, b.q[j], chunks * 16, st + b.cur_off, js, bid, nb);
+}
+
 // ---------------------------------------------------------------- cast fused with transpose
 // One workgroup handles a 128 x 128 element tile.  A thread owns units of 4 rows x 8 columns:
 // it loads 16 bytes from each of four consecutive rows, casts, stores 8 code bytes per row to q,
@@ -739,5 +772,50 @@ extern "C" fog_status fog_quantize_jit_batch(const fog_cast_job* jobs, int count
   uint32_t* ws = reinterpret_cast<uint32_t*>(workspace);
   amax_batch_kernel<<<b.amax_first[count], kThreads, 0, s>>>(b, ws);
   quantize_batch_kernel<<<b.cast_first[count], kThreads, 0, s>>>(b, ws);
+  return fog_launch_status();
+}
+
+extern "C" fog_status fog_quantize_delayed_batch(const fog_delayed_job* jobs, int count, int64_t step, void* stream) {
+  if (count == 0) return FOG_OK;
+  if (!jobs) return FOG_ERR_NULL;
+  if (count < 0 || count > kBatchMax || step < 0) return FOG_ERR_SHAPE;
+  DelayedJobs b;
+  b.count = count;
+  b.first[0] = 0;
+  b.prev_off = (int)((step + 2) % 3) * kDelayedSlots;
+  b.cur_off = (int)(step % 3) * kDelayedSlots;
+  b.next_off = (int)((step + 1) % 3) * kDelayedSlots;
+  for (int j = 0; j < count; ++j) {
+    const fog_delayed_job& t = jobs[j];
+    if (!t.x_bf16 || !t.q || !t.history || !t.state || !t.scale) return FOG_ERR_NULL;
+    if (t.rows <= 0 || t.cols <= 0 || t.history_len < 1 || t.margin < -64 || t.margin > 64) return FOG_ERR_SHAPE;
+    if (t.fmt != FOG_E4M3 && t.fmt != FOG_E5M2) return FOG_ERR_UNSUPPORTED;
+    if (!aligned16(t.x_bf16) || !aligned16(t.q) || (reinterpret_cast<uintptr_t>(t.state) & 3u) != 0) return FOG_ERR_ALIGN;
+    if (t.state_bytes < fog_quantize_delayed_state()) return FOG_ERR_WORKSPACE;
+    const int64_t n = t.rows * t.cols;
+    if (n % 16 != 0) return FOG_ERR_UNSUPPORTED;
+    int64_t cb = (n / 16 + 2 * kThreads - 1) / (2 * kThreads);
+    if (cb > 2048) cb = 2048;
+    b.first[j + 1] = b.first[j] + (int)cb;
+    b.x[j] = reinterpret_cast<const uint16_t*>(t.x_bf16);
+    b.n[j] = n;
+    b.q[j] = t.q;
+    b.fmt[j] = (int)t.fmt;
+    b.margin[j] = t.margin;
+    b.amax_prev[j] = t.amax_prev;
+    b.scale[j] = t.scale;
+    b.scale_inv[j] = t.scale_inv;
+    b.hist[j] = t.history;
+    b.hlen[j] = t.history_len;
+    b.slot[j] = (int)(step % t.history_len);
+    b.state[j] = reinterpret_cast<uint32_t*>(t.state);
+  }
+  for (int j = count; j < kBatchMax; ++j) {
+    b.first[j + 1] = b.first[count];
+    b.x[j] = nullptr; b.n[j] = 0; b.q[j] = nullptr; b.fmt[j] = 0; b.margin[j] = 0;
+    b.amax_prev[j] = b.scale[j] = b.scale_inv[j] = b.hist[j] = nullptr;
+    b.hlen[j] = 1; b.slot[j] = 0; b.state[j] = nullptr;
+  }
+  quantize_delayed_batch_kernel<<<b.first[count], kThreads, 0, (hipStream_t)stream>>>(b);
   return fog_launch_status();
 }

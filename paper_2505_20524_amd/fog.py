@@ -32,6 +32,7 @@ SIGNATURES = {
     "fog_quantize_jit_batch": (_I, [_P, _I, _P, _SZ, _P]),
     "fog_quantize_jit_batch_workspace": (_SZ, [_I]),
     "fog_quantize_delayed": (_I, [_P, _I64, _I64, _I64, _I, _I, _P, _I, _I64, _P, _SZ, _P, _I64, _P, _I64, _P, _P, _P, _P]),
+    "fog_quantize_delayed_batch": (_I, [_P, _I, _I64, _P]),
     "fog_quantize_delayed_state": (_SZ, []),
     "fog_delayed_amax": (_I, [_P, _I64, _P, _P]),
     "fog_rmsnorm_quantize": (_I, [_P, _I64, _I64, _I64, _F, _I, _P, _P, _I64, _P, _P]),
@@ -169,6 +170,30 @@ def quantize_delayed(x, fmt, history, step, state, scale_out, scale_inv_out=None
                                        _ptr(qT), qT.stride(0) if qT is not None else 0,
                                        _ptr(amax_prev), _ptr(scale_out), _ptr(scale_inv_out), _stream(stream)),
            "fog_quantize_delayed")
+
+
+class DelayedJob(ctypes.Structure):
+    """Mirror of fog_delayed_job."""
+    _fields_ = [("x_bf16", _P), ("rows", _I64), ("cols", _I64), ("fmt", _I), ("margin", _I), ("history", _P), ("history_len", _I),
+                ("state", _P), ("state_bytes", _SZ), ("q", _P), ("amax_prev", _P), ("scale", _P), ("scale_inv", _P)]
+
+
+def make_delayed_jobs(items, margin=0):
+    """items: (x, fmt, q, history, state, amax_prev, scale, scale_inv) tuples of contiguous tensors (amax_prev and
+    scale_inv may be None) -> ctypes array for quantize_delayed_batch."""
+    arr = (DelayedJob * len(items))()
+    for job, (x, fmt, q, history, state, amax_prev, scale_t, sinv_t) in zip(arr, items):
+        rows, cols = x.shape
+        job.x_bf16, job.rows, job.cols, job.fmt, job.margin = _ptr(x), rows, cols, fmt, margin
+        job.history, job.history_len = _ptr(history), history.numel()
+        job.state, job.state_bytes = _ptr(state), state.numel() * state.element_size()
+        job.q, job.amax_prev, job.scale, job.scale_inv = _ptr(q), _ptr(amax_prev), _ptr(scale_t), _ptr(sinv_t)
+    return arr
+
+
+def quantize_delayed_batch(jobs, step, stream=None):
+    """jobs: the array make_delayed_jobs returns (built once, reused while the tensors stay in place); step: the call number."""
+    _check(load().fog_quantize_delayed_batch(ctypes.cast(jobs, _P), len(jobs), step, _stream(stream)), "fog_quantize_delayed_batch")
 
 
 def quantize_delayed_state():

@@ -453,3 +453,71 @@ def test_only_infinities_saturate_and_give_scale_one():
         top = 0x7E if fmt == fp8.E4M3 else 0x7B
         assert got[5, 7] == top and got[60, 0] == (top | 0x80)
     assert gpu_amax(xb) == np.float32(np.inf)
+
+
+def test_quantize_delayed_batch_equals_the_calls_one_by_one_and_the_oracle():
+    """fog_quantize_delayed_batch over six steps with changing data: three tensors of different sizes, formats and history
+    lengths in one launch; scales, codes, previous abs-maxes and histories bit for bit against the oracle's history
+    functions (Appendix E) and against fog_quantize_delayed on a second set of states."""
+    rng = np.random.default_rng(2024)
+    specs = [(64, 256, fp8.E4M3, 1024), (1500, 4096, fp8.E5M2, 3), (333, 48, fp8.E4M3, 2)]   # the second spans more workgroups than state slots
+    dst = fog.quantize_delayed_state()
+    T = []
+    for rows, cols, fmt, hl in specs:
+        T.append(dict(rows=rows, cols=cols, fmt=fmt, x=torch.zeros((rows, cols), dtype=torch.int16, device="cuda"),
+                      q=torch.full((rows, cols), 0xAA, dtype=torch.uint8, device="cuda"),
+                      q1=torch.full((rows, cols), 0xAA, dtype=torch.uint8, device="cuda"),
+                      hist=torch.zeros(hl, device="cuda"), hist1=torch.zeros(hl, device="cuda"),
+                      state=torch.zeros(dst, dtype=torch.uint8, device="cuda"), state1=torch.zeros(dst, dtype=torch.uint8, device="cuda"),
+                      ap=torch.full((1,), -1.0, device="cuda"), s=torch.zeros(1, device="cuda"), si=torch.zeros(1, device="cuda"),
+                      ap1=torch.full((1,), -1.0, device="cuda"), s1=torch.zeros(1, device="cuda"), si1=torch.zeros(1, device="cuda"),
+                      ring=np.zeros(hl, np.float32), prev=np.float32(0.0)))
+    jobs = fog.make_delayed_jobs([(t["x"], t["fmt"], t["q"], t["hist"], t["state"], t["ap"], t["s"], t["si"]) for t in T], margin=1)
+    for step, gain in enumerate((1.0, 80.0, 0.02, 3.0, 3.0, 0.5)):
+        xbs = []
+        for k, t in enumerate(T):
+            xb = synth.f32_to_bf16_bits(rng.standard_normal((t["rows"], t["cols"])).astype(np.float32) * gain * (k + 1))
+            t["x"].copy_(dev(xb))
+            xbs.append(xb)
+        fog.quantize_delayed_batch(jobs, step)
+        for t in T:
+            fog.quantize_delayed(t["x"], t["fmt"], t["hist1"], step, t["state1"], t["s1"], t["si1"], q=t["q1"], amax_prev=t["ap1"], margin=1)
+        torch.cuda.synchronize()
+        for t, xb in zip(T, xbs):
+            hl = t["ring"].size
+            t["ring"][step % hl] = t["prev"]
+            rho, rinv = scaling.history_scale(t["ring"], t["fmt"], margin=1)
+            assert np.float32(t["s"].item()).tobytes() == rho.tobytes(), step
+            assert np.float32(t["si"].item()).tobytes() == rinv.tobytes(), step
+            assert np.float32(t["ap"].item()) == t["prev"]
+            assert np.array_equal(t["hist"].cpu().numpy(), t["ring"])
+            assert np.array_equal(t["q"].cpu().numpy(), scaling.quantize(xb, rho, t["fmt"])), step
+            for a, b in (("q", "q1"), ("s", "s1"), ("si", "si1"), ("ap", "ap1"), ("hist", "hist1"), ("state", "state1")):
+                assert torch.equal(t[a], t[b]), (step, a)
+            t["prev"] = scaling.amax(xb)
+            am = torch.full((1,), -1.0, device="cuda")
+            fog.delayed_amax(t["state"], step, am)
+            assert np.float32(am.item()) == t["prev"]
+    # argument errors: nothing is launched
+    lib = fog.load()
+    st = torch.cuda.current_stream().cuda_stream
+    import ctypes as C
+    call = lib.fog_quantize_delayed_batch
+    ptr = C.cast(jobs, C.c_void_p)
+    assert call(ptr, 0, 0, st) == 0
+    assert call(None, 3, 0, st) == 1
+    assert call(ptr, 33, 0, st) == 2
+    assert call(ptr, 3, -1, st) == 2
+    before = [t["q"].clone() for t in T]
+    bad = fog.make_delayed_jobs([(T[0]["x"], T[0]["fmt"], T[0]["q"], T[0]["hist"], T[0]["state"][:64], None, T[0]["s"], None)])
+    assert call(C.cast(bad, C.c_void_p), 1, 6, st) == 5
+    bad = fog.make_delayed_jobs([(T[0]["x"][:, :8], T[0]["fmt"], T[0]["q"][:, :8], T[0]["hist"], T[0]["state"], None, T[0]["s"], None)])
+    bad[0].rows, bad[0].cols = 1, 8
+    assert call(C.cast(bad, C.c_void_p), 1, 6, st) == 4
+    bad = fog.make_delayed_jobs([(T[0]["x"], 7, T[0]["q"], T[0]["hist"], T[0]["state"], None, T[0]["s"], None)])
+    assert call(C.cast(bad, C.c_void_p), 1, 6, st) == 4
+    bad = fog.make_delayed_jobs([(T[0]["x"], T[0]["fmt"], T[0]["q"], T[0]["hist"], T[0]["state"], None, T[0]["s"], None)])
+    bad[0].scale = None
+    assert call(C.cast(bad, C.c_void_p), 1, 6, st) == 1
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, t["q"]) for a, t in zip(before, T))
