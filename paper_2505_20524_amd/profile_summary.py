@@ -77,7 +77,7 @@ def stats_summary(cid, d, out_dir, bench_line):
          "Command (on the GPU box, from the repo root, after `cd /tmp && export TMPDIR=/tmp && cd $GRAFT_REPO_ROOT`):\n",
          "    rocprofv3 --kernel-trace --stats --output-format csv -d OUT/stats -o bench -- python3 bench.py --config %d --steps 5 --warmup 2 --no-cpu-baseline\n" % cid,
          "24 passes of the block: 12 under just-in-time scaling (2 warm-up + 5 timed + 5 with every kernel class bracketed by events) and 12 under "
-         "delayed scaling (2 + 5 + 5; `fog_quantize_delayed`, one launch per cast: the `quantize_*_kernel<..., true>` instantiations), then the side "
+         "delayed scaling (2 + 5 + 5; `fog_quantize_delayed_batch`, one launch per layer's casts: `quantize_delayed_batch_kernel`), then the side "
          "figures (kurtosis monitor, fused cast + transpose, fused producers); `bench_kernel_stats.csv`:\n",
          "| kernel | calls | total ms | avg us | % |\n|---|---|---|---|---|"]
     per = {}
@@ -107,7 +107,7 @@ def stats_summary(cid, d, out_dir, bench_line):
                             ("attention backward (row constants, dV, dK, dQ)", lambda k: "attn_bwd" in k, 24),
                             ("abs-max pass (just-in-time passes only)", lambda k: "amax_batch_kernel" in k or "amax_kernel" in k, 12),
                             ("cast pass, just-in-time", lambda k: "quantize_batch_kernel" in k or ("quantize_rows_kernel" in k and "false>" in k.split("(")[0]), 12),
-                            ("cast pass with abs-max output, delayed", lambda k: "quantize_rows_kernel" in k and "true>" in k.split("(")[0], 12)):
+                            ("cast pass with abs-max output, delayed", lambda k: "quantize_delayed_batch_kernel" in k or ("quantize_rows_kernel" in k and "true>" in k.split("(")[0]), 12)):
         c, t = grp(pred)
         if c:
             parts.append("%s %.3f ms" % (name, t / div / 1e6))
